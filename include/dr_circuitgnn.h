@@ -1,0 +1,193 @@
+/*
+ * dr_circuitgnn.h -- C ABI of the MI355X (gfx950) implementation of the DR-CircuitGNN
+ * HeteroConv hot path: row-wise Dynamic-ReLU (top-k) of the node embeddings, the DR-SpMM of
+ * each relation's CSR adjacency with the resulting row-sparse operand, and the backward SpMM
+ * on the transposed adjacency evaluated at the saved top-k positions.
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ *  - Plain C.  No exceptions cross the boundary.  Every call returns an int status:
+ *    DR_OK (0) or a negative DR_ERR_* code; dr_last_error() returns a thread-local message.
+ *  - Every array argument is a caller-owned DEVICE pointer (HBM of the current HIP device),
+ *    borrowed until the enqueued work has finished.  dr_csr structs themselves live on the
+ *    host; the three pointers inside them are device pointers.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *    enqueue work; none of them synchronises the host.
+ *  - All arguments are validated on the host before anything is launched, so argument
+ *    errors are reported without touching the GPU.
+ *  - Matrices are row-major fp32; graph indices are int32; CBSR column indices are uint16.
+ *  - Relations are stored as CSR with rows = destination nodes and columns = source nodes
+ *    (the paper's A^psi, M_dst x N_src).  Column order inside a row is free and duplicate
+ *    entries are allowed; they count as separate edges.
+ *  - CBSR (compressed balanced sparse row, paper Section 3.1): for each embedding row exactly k
+ *    (value, column) pairs, stored as vals[n,k] and idx[n,k] with columns ascending.
+ */
+#ifndef DR_CIRCUITGNN_H
+#define DR_CIRCUITGNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DR_OK               0
+#define DR_ERR_INVALID_ARG (-1)  /* null pointer, k < 1, k > D, bad shape, misaligned pointer, ... */
+#define DR_ERR_UNSUPPORTED (-2)  /* legal request outside what this build implements (e.g. D too large) */
+#define DR_ERR_HIP         (-3)  /* a HIP runtime call failed; message carries hipGetErrorString */
+#define DR_ERR_WORKSPACE   (-4)  /* workspace_bytes smaller than the matching *_workspace_bytes() */
+
+#define DR_NORM_MEAN 0           /* SageConv 'mean' aggregation: a_ij = 1 / deg_in(i)                       */
+#define DR_NORM_SYM  1           /* GraphConv: a_ij = 1 / sqrt(max(deg_in(i),1) * max(deg_out(j),1))        */
+
+#define DR_MAX_D 1024            /* largest embedding width accepted by dr_topk / dr_spmm_*                 */
+
+/* CSR adjacency of one relation.  rowptr[n_rows+1], colidx[nnz], vals[nnz] are device pointers.
+ * vals may be NULL only where a call says so.  nnz must be < 2^31 and equal rowptr[n_rows]. */
+typedef struct dr_csr {
+    int64_t n_rows;          /* M: destination nodes */
+    int64_t n_cols;          /* N: source nodes      */
+    int64_t nnz;             /* E: stored edges      */
+    const int32_t* rowptr;
+    const int32_t* colidx;
+    const float* vals;
+} dr_csr;
+
+/* Message of the last failing call on this thread ("" if none). */
+const char* dr_last_error(void);
+
+/* ABI version of this header (bumped on incompatible change). */
+int dr_abi_version(void);
+
+/*
+ * (1) D-ReLU, paper Section 3.1 (threshold th_i = min(topk(X_i, k)) and the piecewise f(X)).
+ * For each of the n rows of X[n,D] keep exactly the k largest signed values (no clamping of
+ * negatives); among equal values the lower column wins; -0.0 and +0.0 compare equal.  Writes the
+ * survivors in ascending column order: vals[n,k] (bit copies of the inputs) and idx[n,k].
+ * Precondition: inputs finite.  Requires 1 <= k <= D <= DR_MAX_D.  n == 0 is a no-op.
+ */
+int dr_topk(const float* X, int64_t n, int32_t D, int32_t k,
+            float* vals, uint16_t* idx, void* stream);
+
+/*
+ * (2) DR-SpMM forward, paper Section 3.2 / Alg. 1:  H[M,D] = A * f(X), with f(X) given as the CBSR
+ * (xs_vals[N,k], xs_idx[N,k]) of the source node type:
+ *     H[i,c] = sum over edges e of row i, pairs t:  A.vals[e] * xs_vals[colidx[e], t]  where xs_idx[colidx[e], t] == c.
+ * H is fully overwritten; rows without edges become zeros.  fp32 accumulation, order unspecified.
+ * Requires A->vals != NULL, 1 <= k <= D <= DR_MAX_D, every xs_idx < D (not checked).
+ */
+int dr_spmm_fwd(const dr_csr* A, const float* xs_vals, const uint16_t* xs_idx,
+                int32_t D, int32_t k, float* H, void* stream);
+
+/*
+ * (3) DR-SpMM backward, paper Section 3.3 / Alg. 2: gradient w.r.t. the k surviving entries of every
+ * source row, using the transposed adjacency At (CSR of A^T: N rows = sources, M columns =
+ * destinations), the dense upstream gradient dH[M,D] and the CBSR indices saved by the forward:
+ *     dXs[j,t] (=|+=) sum over edges e of row j of At:  At.vals[e] * dH[At.colidx[e], xs_idx[j,t]].
+ * accumulate == 0 overwrites dXs[N,k]; accumulate != 0 adds to its current contents (the paper's
+ * accumulation of the per-relation pieces, done without atomics on HBM).
+ */
+int dr_spmm_bwd(const dr_csr* At, const float* dH, const uint16_t* xs_idx,
+                int32_t D, int32_t k, float* dXs, int accumulate, void* stream);
+
+/*
+ * Setup: stable CSR transpose (Alg. 2 stage 1, "transpose A to CSC").  Row j of the result lists the
+ * entries of column j of A in increasing original row and, for equal rows, original storage order.
+ * Outputs t_rowptr[n_cols+1], t_colidx[nnz], t_vals[nnz] (t_vals and A->vals may both be NULL for a
+ * pattern-only transpose).  Integer-exact and deterministic.  workspace: device scratch of at least
+ * dr_csr_transpose_workspace_bytes() bytes, 256-byte aligned, contents undefined before and after.
+ */
+size_t dr_csr_transpose_workspace_bytes(int64_t n_rows, int64_t n_cols, int64_t nnz);
+int dr_csr_transpose(const dr_csr* A, int32_t* t_rowptr, int32_t* t_colidx, float* t_vals,
+                     void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Setup: edge values of the three modules (GraphSAGE 'mean' mode and GCN normalisation, paper
+ * Section 4.1): fills vals_out[nnz] for the pattern (rowptr, colidx) according to `mode`
+ * (DR_NORM_MEAN or DR_NORM_SYM).  Values are evaluated in fp64 and rounded once to fp32.
+ * workspace: at least dr_csr_normalize_workspace_bytes() bytes (0 for DR_NORM_MEAN; may be NULL then).
+ */
+size_t dr_csr_normalize_workspace_bytes(int mode, int64_t n_rows, int64_t n_cols, int64_t nnz);
+int dr_csr_normalize(int mode, int64_t n_rows, int64_t n_cols, int64_t nnz,
+                     const int32_t* rowptr, const int32_t* colidx, float* vals_out,
+                     void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * The HeteroConv layer (paper Fig. 3, Sections 3.2-3.4): three relation modules on three HIP streams,
+ *     near   (cell->cell, SageConv mean):  Z_near   = f(X_cell) Wself_near + (A_near   f(X_cell)) Wneigh_near
+ *     pins   (cell->net,  SageConv mean):  Y_net    = f(X_net)  Wself_pins + (A_pins   f(X_cell)) Wneigh_pins
+ *     pinned (net->cell,  GraphConv sym):  Z_pinned =                        (A_pinned f(X_net))  W_pinned
+ *     Y_cell = max(Z_near, Z_pinned) element-wise, mask = [Z_near >= Z_pinned]   (ties go to near)
+ * and the matching backward (gradient routed by mask, transposed SpMM gated by the saved indices).
+ * Every weight is [D,D] row-major with the Y = X W convention; there are no biases.
+ * ---------------------------------------------------------------------------------------------- */
+
+typedef struct dr_heteroconv dr_heteroconv;   /* opaque: transposed adjacencies, streams, events, scratch */
+
+typedef struct dr_heteroconv_weights {        /* device pointers, each [D,D]; read-only in fwd and bwd */
+    const float* self_near;
+    const float* neigh_near;
+    const float* self_pins;
+    const float* neigh_pins;
+    const float* pinned;
+} dr_heteroconv_weights;
+
+typedef struct dr_heteroconv_wgrads {         /* device pointers, each [D,D]; overwritten by heteroconv_bwd */
+    float* self_near;
+    float* neigh_near;
+    float* self_pins;
+    float* neigh_pins;
+    float* pinned;
+} dr_heteroconv_wgrads;
+
+typedef struct dr_heteroconv_saved {          /* caller-owned device buffers written by fwd, read by bwd */
+    float*    vals_cell;  /* [Nc,k_cell] CBSR of the cell embeddings  */
+    uint16_t* idx_cell;   /* [Nc,k_cell]                              */
+    float*    vals_net;   /* [Nn,k_net]  CBSR of the net embeddings   */
+    uint16_t* idx_net;    /* [Nn,k_net]                               */
+    float*    H_near;     /* [Nc,D] aggregated messages per relation  */
+    float*    H_pins;     /* [Nn,D]                                   */
+    float*    H_pinned;   /* [Nc,D]                                   */
+    uint8_t*  mask;       /* [Nc,D] 1 where the near branch won the max-merge */
+} dr_heteroconv_saved;
+
+/*
+ * Build the per-graph context: validates the three relations (near Nc x Nc, pins Nn x Nc,
+ * pinned Nc x Nn, all with vals), transposes them on the device, creates three streams and the events
+ * that join them, and allocates the scratch the backward pass needs.  This is the only call of the
+ * library that allocates device memory; heteroconv_destroy releases it.  The CSR arrays passed in stay
+ * owned by the caller and must outlive the context.  The call synchronises the device before returning.
+ * Requires D in {32, 64, 96, 128}, 1 <= k_cell, k_net <= D.
+ */
+int heteroconv_create(dr_heteroconv** ctx, const dr_csr* near, const dr_csr* pins, const dr_csr* pinned,
+                      int32_t D, int32_t k_cell, int32_t k_net);
+
+/*
+ * Forward of one layer.  Inputs X_cell[Nc,D], X_net[Nn,D]; outputs Y_cell[Nc,D], Y_net[Nn,D] and every
+ * buffer of `saved`.  Work is forked from `stream` onto the context's three relation streams and joined
+ * back into `stream` before the call returns (device-side joins; the host does not wait).
+ */
+int heteroconv_fwd(dr_heteroconv* ctx, const float* X_cell, const float* X_net,
+                   const dr_heteroconv_weights* W, float* Y_cell, float* Y_net,
+                   const dr_heteroconv_saved* saved, void* stream);
+
+/*
+ * Backward of one layer.  Inputs dY_cell[Nc,D], dY_net[Nn,D], the weights and what fwd saved.  Outputs
+ * dX_cell[Nc,D] and dX_net[Nn,D] (dense; exactly zero outside the saved top-k positions) and the five
+ * weight gradients.  Same stream semantics as heteroconv_fwd.
+ */
+int heteroconv_bwd(dr_heteroconv* ctx, const float* dY_cell, const float* dY_net,
+                   const dr_heteroconv_weights* W, const dr_heteroconv_saved* saved,
+                   float* dX_cell, float* dX_net, const dr_heteroconv_wgrads* dW, void* stream);
+
+/* Transposed adjacency of a relation held by the context (which: 0 near, 1 pins, 2 pinned); the
+ * returned struct's pointers are device memory owned by the context. */
+int heteroconv_get_transpose(const dr_heteroconv* ctx, int which, dr_csr* out);
+
+int heteroconv_destroy(dr_heteroconv* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DR_CIRCUITGNN_H */

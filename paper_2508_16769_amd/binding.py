@@ -1,0 +1,233 @@
+"""Thin ctypes binding of libdrcgnn.so: argument marshalling only.
+
+Every function has the name of the C entry point it calls (see ``include/dr_circuitgnn.h``) and does
+no arithmetic of its own.  Tensors are torch CUDA tensors used purely as device-memory handles
+(``data_ptr()``); streams are taken from ``torch.cuda.current_stream()`` unless given.  A missing or
+unloadable library raises: there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Dict, Optional
+
+import torch
+
+from . import build as _build
+
+DR_OK = 0
+DR_ERR_INVALID_ARG = -1
+DR_ERR_UNSUPPORTED = -2
+DR_ERR_HIP = -3
+DR_ERR_WORKSPACE = -4
+DR_NORM_MEAN = 0
+DR_NORM_SYM = 1
+
+WEIGHT_NAMES = ("self_near", "neigh_near", "self_pins", "neigh_pins", "pinned")
+EXPORTS = (
+    "dr_last_error", "dr_abi_version", "dr_topk", "dr_spmm_fwd", "dr_spmm_bwd",
+    "dr_csr_transpose_workspace_bytes", "dr_csr_transpose",
+    "dr_csr_normalize_workspace_bytes", "dr_csr_normalize",
+    "heteroconv_create", "heteroconv_fwd", "heteroconv_bwd", "heteroconv_get_transpose", "heteroconv_destroy",
+)
+
+
+class DrError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"libdrcgnn error {code}: {message}")
+        self.code = code
+
+
+class dr_csr(ctypes.Structure):
+    _fields_ = [("n_rows", ctypes.c_int64), ("n_cols", ctypes.c_int64), ("nnz", ctypes.c_int64),
+                ("rowptr", ctypes.c_void_p), ("colidx", ctypes.c_void_p), ("vals", ctypes.c_void_p)]
+
+
+class dr_heteroconv_weights(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in WEIGHT_NAMES]
+
+
+class dr_heteroconv_saved(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in
+                ("vals_cell", "idx_cell", "vals_net", "idx_net", "H_near", "H_pins", "H_pinned", "mask")]
+
+
+_lib = None
+_hip = None
+
+
+def library_path() -> str:
+    return _build.LIB
+
+
+def hip_runtime() -> ctypes.CDLL:
+    """The HIP runtime PyTorch itself uses.  libdrcgnn needs ``libamdhip64.so.7``; loading torch's copy
+    first makes the dynamic loader resolve that soname to the same runtime, so streams and device
+    pointers are shared between PyTorch and the library."""
+    global _hip
+    if _hip is None:
+        bundled = os.path.join(os.path.dirname(torch.__file__), "lib", "libamdhip64.so")
+        _hip = ctypes.CDLL(bundled if os.path.exists(bundled) else "libamdhip64.so", mode=ctypes.RTLD_GLOBAL)
+    return _hip
+
+
+def load() -> ctypes.CDLL:
+    """Load the in-tree library (building it first only if no built library exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_build.LIB):
+            _build.build(verbose=False)
+        hip_runtime()
+        lib = ctypes.CDLL(_build.LIB)
+        lib.dr_last_error.restype = ctypes.c_char_p
+        lib.dr_csr_transpose_workspace_bytes.restype = ctypes.c_size_t
+        lib.dr_csr_normalize_workspace_bytes.restype = ctypes.c_size_t
+        _lib = lib
+    return _lib
+
+
+def _check(rc: int) -> None:
+    if rc != DR_OK:
+        raise DrError(rc, load().dr_last_error().decode())
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return ctypes.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+@dataclass
+class Csr:
+    """Device CSR of one relation (rows = destinations, columns = sources)."""
+    n_rows: int
+    n_cols: int
+    rowptr: torch.Tensor            # int32 [n_rows+1]
+    colidx: torch.Tensor            # int32 [nnz]
+    vals: Optional[torch.Tensor]    # float32 [nnz] or None
+
+    @property
+    def nnz(self) -> int:
+        return int(self.colidx.shape[0])
+
+    def c(self) -> dr_csr:
+        return dr_csr(self.n_rows, self.n_cols, self.nnz, self.rowptr.data_ptr(), self.colidx.data_ptr(),
+                      0 if self.vals is None else self.vals.data_ptr())
+
+
+def dr_last_error() -> str:
+    return load().dr_last_error().decode()
+
+
+def dr_abi_version() -> int:
+    return int(load().dr_abi_version())
+
+
+def dr_topk(X: torch.Tensor, k: int, vals: torch.Tensor, idx: torch.Tensor, stream=None) -> None:
+    n, D = X.shape
+    _check(load().dr_topk(_ptr(X), ctypes.c_int64(n), ctypes.c_int32(D), ctypes.c_int32(k), _ptr(vals), _ptr(idx),
+                          _stream(stream)))
+
+
+def dr_spmm_fwd(A: Csr, xs_vals: torch.Tensor, xs_idx: torch.Tensor, D: int, k: int, H: torch.Tensor,
+                stream=None) -> None:
+    a = A.c()
+    _check(load().dr_spmm_fwd(ctypes.byref(a), _ptr(xs_vals), _ptr(xs_idx), ctypes.c_int32(D), ctypes.c_int32(k),
+                              _ptr(H), _stream(stream)))
+
+
+def dr_spmm_bwd(At: Csr, dH: torch.Tensor, xs_idx: torch.Tensor, D: int, k: int, dXs: torch.Tensor,
+                accumulate: bool = False, stream=None) -> None:
+    a = At.c()
+    _check(load().dr_spmm_bwd(ctypes.byref(a), _ptr(dH), _ptr(xs_idx), ctypes.c_int32(D), ctypes.c_int32(k),
+                              _ptr(dXs), ctypes.c_int(1 if accumulate else 0), _stream(stream)))
+
+
+def dr_csr_transpose_workspace_bytes(n_rows: int, n_cols: int, nnz: int) -> int:
+    return int(load().dr_csr_transpose_workspace_bytes(ctypes.c_int64(n_rows), ctypes.c_int64(n_cols),
+                                                       ctypes.c_int64(nnz)))
+
+
+def dr_csr_transpose(A: Csr, t_rowptr: torch.Tensor, t_colidx: torch.Tensor, t_vals: Optional[torch.Tensor],
+                     workspace: torch.Tensor, stream=None) -> None:
+    a = A.c()
+    _check(load().dr_csr_transpose(ctypes.byref(a), _ptr(t_rowptr), _ptr(t_colidx), _ptr(t_vals), _ptr(workspace),
+                                   ctypes.c_size_t(workspace.numel() * workspace.element_size()), _stream(stream)))
+
+
+def dr_csr_normalize_workspace_bytes(mode: int, n_rows: int, n_cols: int, nnz: int) -> int:
+    return int(load().dr_csr_normalize_workspace_bytes(ctypes.c_int(mode), ctypes.c_int64(n_rows),
+                                                       ctypes.c_int64(n_cols), ctypes.c_int64(nnz)))
+
+
+def dr_csr_normalize(mode: int, n_rows: int, n_cols: int, rowptr: torch.Tensor, colidx: torch.Tensor,
+                     vals_out: torch.Tensor, workspace: Optional[torch.Tensor], stream=None) -> None:
+    wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().dr_csr_normalize(ctypes.c_int(mode), ctypes.c_int64(n_rows), ctypes.c_int64(n_cols),
+                                   ctypes.c_int64(colidx.shape[0]), _ptr(rowptr), _ptr(colidx), _ptr(vals_out),
+                                   _ptr(workspace), ctypes.c_size_t(wsb), _stream(stream)))
+
+
+class HeteroConv:
+    """Owner of a ``dr_heteroconv*`` context (heteroconv_create / heteroconv_destroy)."""
+
+    def __init__(self, near: Csr, pins: Csr, pinned: Csr, D: int, k_cell: int, k_net: int):
+        self._keep = (near, pins, pinned)
+        self.Nc, self.Nn, self.D, self.k_cell, self.k_net = near.n_rows, pins.n_rows, D, k_cell, k_net
+        self._ctx = ctypes.c_void_p(0)
+        a, b, c = near.c(), pins.c(), pinned.c()
+        _check(load().heteroconv_create(ctypes.byref(self._ctx), ctypes.byref(a), ctypes.byref(b), ctypes.byref(c),
+                                        ctypes.c_int32(D), ctypes.c_int32(k_cell), ctypes.c_int32(k_net)))
+
+    def alloc_saved(self, device="cuda") -> Dict[str, torch.Tensor]:
+        Nc, Nn, D = self.Nc, self.Nn, self.D
+        f32, dev = torch.float32, device
+        return dict(
+            vals_cell=torch.empty((Nc, self.k_cell), dtype=f32, device=dev),
+            idx_cell=torch.empty((Nc, self.k_cell), dtype=torch.int16, device=dev),
+            vals_net=torch.empty((Nn, self.k_net), dtype=f32, device=dev),
+            idx_net=torch.empty((Nn, self.k_net), dtype=torch.int16, device=dev),
+            H_near=torch.empty((Nc, D), dtype=f32, device=dev),
+            H_pins=torch.empty((Nn, D), dtype=f32, device=dev),
+            H_pinned=torch.empty((Nc, D), dtype=f32, device=dev),
+            mask=torch.empty((Nc, D), dtype=torch.uint8, device=dev),
+        )
+
+    @staticmethod
+    def _saved(saved: Dict[str, torch.Tensor]) -> dr_heteroconv_saved:
+        return dr_heteroconv_saved(*[saved[n].data_ptr() for n, _ in dr_heteroconv_saved._fields_])
+
+    @staticmethod
+    def _weights(W: Dict[str, torch.Tensor]) -> dr_heteroconv_weights:
+        return dr_heteroconv_weights(*[W[n].data_ptr() for n in WEIGHT_NAMES])
+
+    def heteroconv_fwd(self, X_cell, X_net, W, Y_cell, Y_net, saved, stream=None) -> None:
+        w, s = self._weights(W), self._saved(saved)
+        _check(load().heteroconv_fwd(self._ctx, _ptr(X_cell), _ptr(X_net), ctypes.byref(w), _ptr(Y_cell),
+                                     _ptr(Y_net), ctypes.byref(s), _stream(stream)))
+
+    def heteroconv_bwd(self, dY_cell, dY_net, W, saved, dX_cell, dX_net, dW, stream=None) -> None:
+        w, s, g = self._weights(W), self._saved(saved), self._weights(dW)
+        _check(load().heteroconv_bwd(self._ctx, _ptr(dY_cell), _ptr(dY_net), ctypes.byref(w), ctypes.byref(s),
+                                     _ptr(dX_cell), _ptr(dX_net), ctypes.byref(g), _stream(stream)))
+
+    def heteroconv_get_transpose(self, which: int) -> dr_csr:
+        out = dr_csr()
+        _check(load().heteroconv_get_transpose(self._ctx, ctypes.c_int(which), ctypes.byref(out)))
+        return out
+
+    def heteroconv_destroy(self) -> None:
+        if self._ctx:
+            _check(load().heteroconv_destroy(self._ctx))
+            self._ctx = ctypes.c_void_p(0)
+
+    def __del__(self):
+        try:
+            self.heteroconv_destroy()
+        except Exception:
+            pass

@@ -1,0 +1,208 @@
+// Per-graph setup kernels: module edge values (mean / symmetric normalisation) and the stable CSR
+// transpose used by the backward pass (paper Alg. 2, stage 1).  These run once per graph, not per
+// iteration; they are written for clarity and determinism, not tuned.
+#include "dr_internal.h"
+
+namespace drc {
+
+__global__ void fill_u32_kernel(uint32_t* p, size_t n, uint32_t v) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) p[i] = v;
+}
+
+int launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t s) {
+    if (n == 0) return DR_OK;
+    size_t blocks = (n + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p, n, v);
+    DRC_HIP(hipGetLastError());
+    return DR_OK;
+}
+
+// row of edge e: largest i with rowptr[i] <= e (rows may be empty)
+__device__ __forceinline__ int row_of_edge(const int32_t* __restrict__ rowptr, int n_rows, int e) {
+    int lo = 0, hi = n_rows;  // invariant: rowptr[lo] <= e < rowptr[hi]
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (rowptr[mid] <= e) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+__global__ void count_columns_kernel(const int32_t* __restrict__ colidx, int nnz, int32_t* __restrict__ count) {
+    int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e < nnz) atomicAdd(&count[colidx[e]], 1);
+}
+
+__global__ void normalize_kernel(int mode, const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colidx,
+                                 int n_rows, int nnz, const int32_t* __restrict__ deg_out,
+                                 float* __restrict__ vals) {
+    int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= nnz) return;
+    int i = row_of_edge(rowptr, n_rows, e);
+    int di = rowptr[i + 1] - rowptr[i];
+    if (mode == DR_NORM_MEAN) {
+        vals[e] = (float)(1.0 / (double)di);
+    } else {
+        int dj = deg_out[colidx[e]];
+        double a = (double)(di > 1 ? di : 1) * (double)(dj > 1 ? dj : 1);
+        vals[e] = (float)(1.0 / sqrt(a));
+    }
+}
+
+int launch_csr_normalize(int mode, int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t* rowptr,
+                         const int32_t* colidx, float* vals_out, void* ws, hipStream_t s) {
+    int32_t* deg_out = static_cast<int32_t*>(ws);
+    unsigned blocks = (unsigned)((nnz + 255) / 256);
+    if (mode == DR_NORM_SYM) {
+        if (int rc = launch_fill_u32(reinterpret_cast<uint32_t*>(deg_out), (size_t)n_cols, 0u, s)) return rc;
+        hipLaunchKernelGGL(count_columns_kernel, dim3(blocks), dim3(256), 0, s, colidx, (int)nnz, deg_out);
+    }
+    hipLaunchKernelGGL(normalize_kernel, dim3(blocks), dim3(256), 0, s, mode, rowptr, colidx, (int)n_rows, (int)nnz,
+                       deg_out, vals_out);
+    DRC_HIP(hipGetLastError());
+    return DR_OK;
+}
+
+// ---------------------------------------------------------------------------------------------------
+// stable transpose
+//   1. count[c+1] += 1 per stored entry (integer atomics: order does not matter)
+//   2. inclusive scan -> t_rowptr
+//   3. every entry e takes some slot of its column segment (atomic cursor) and records key e there
+//   4. per segment, each entry's final place is the number of smaller keys in the segment: increasing e
+//      is exactly "increasing original row, then storage order", so the result is the stable order
+//      whatever slots step 3 handed out.
+// ---------------------------------------------------------------------------------------------------
+
+constexpr int kScanBlock = 1024;
+
+__device__ __forceinline__ int block_inclusive_scan(int v, int* smem /* [kScanBlock/64] */) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int x = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        int y = __shfl_up(x, d, 64);
+        if (lane >= d) x += y;
+    }
+    if (lane == 63) smem[wave] = x;
+    __syncthreads();
+    if (wave == 0) {
+        int w = (lane < kScanBlock / 64) ? smem[lane] : 0;
+#pragma unroll
+        for (int d = 1; d < kScanBlock / 64; d <<= 1) {
+            int y = __shfl_up(w, d, 64);
+            if (lane >= d) w += y;
+        }
+        if (lane < kScanBlock / 64) smem[lane] = w;
+    }
+    __syncthreads();
+    int prefix = (wave > 0) ? smem[wave - 1] : 0;
+    __syncthreads();
+    return x + prefix;
+}
+
+// a[0..n) -> per-block totals
+__global__ __launch_bounds__(kScanBlock) void scan_block_sums_kernel(const int32_t* __restrict__ a, int n,
+                                                                     int32_t* __restrict__ sums) {
+    __shared__ int smem[kScanBlock / 64];
+    int i = blockIdx.x * kScanBlock + threadIdx.x;
+    int v = (i < n) ? a[i] : 0;
+    int inc = block_inclusive_scan(v, smem);
+    if (threadIdx.x == kScanBlock - 1) sums[blockIdx.x] = inc;
+}
+
+// exclusive scan of the block totals, one workgroup, sequential over chunks
+__global__ __launch_bounds__(kScanBlock) void scan_sums_kernel(int32_t* __restrict__ sums, int nb) {
+    __shared__ int smem[kScanBlock / 64];
+    __shared__ int carry_s;
+    if (threadIdx.x == 0) carry_s = 0;
+    __syncthreads();
+    for (int base = 0; base < nb; base += kScanBlock) {
+        int i = base + threadIdx.x;
+        int v = (i < nb) ? sums[i] : 0;
+        int inc = block_inclusive_scan(v, smem);
+        int carry = carry_s;
+        __syncthreads();
+        if (i < nb) sums[i] = carry + inc - v;
+        if (threadIdx.x == kScanBlock - 1) carry_s = carry + inc;
+        __syncthreads();
+    }
+}
+
+__global__ __launch_bounds__(kScanBlock) void scan_apply_kernel(int32_t* __restrict__ a, int n,
+                                                                const int32_t* __restrict__ sums) {
+    __shared__ int smem[kScanBlock / 64];
+    int i = blockIdx.x * kScanBlock + threadIdx.x;
+    int v = (i < n) ? a[i] : 0;
+    int inc = block_inclusive_scan(v, smem);
+    if (i < n) a[i] = inc + sums[blockIdx.x];
+}
+
+__global__ void transpose_scatter_kernel(const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colidx,
+                                         int n_rows, int nnz, const int32_t* __restrict__ t_rowptr,
+                                         int32_t* __restrict__ cursor, int32_t* __restrict__ key,
+                                         int32_t* __restrict__ erow) {
+    int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= nnz) return;
+    erow[e] = row_of_edge(rowptr, n_rows, e);
+    int c = colidx[e];
+    int slot = t_rowptr[c] + atomicAdd(&cursor[c], 1);
+    key[slot] = e;
+}
+
+// one wavefront per output row
+__global__ __launch_bounds__(256) void transpose_place_kernel(const int32_t* __restrict__ t_rowptr, int n_cols,
+                                                              const int32_t* __restrict__ key,
+                                                              const int32_t* __restrict__ erow,
+                                                              const float* __restrict__ vals,
+                                                              int32_t* __restrict__ t_colidx,
+                                                              float* __restrict__ t_vals) {
+    const int lane = threadIdx.x & 63;
+    const int j = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (j >= n_cols) return;
+    const int b = t_rowptr[j], e = t_rowptr[j + 1];
+    for (int p = b + lane; p < e; p += kWave) {
+        int my = key[p];
+        int rank = 0;
+        for (int q = b; q < e; ++q) rank += (key[q] < my) ? 1 : 0;
+        t_colidx[b + rank] = erow[my];
+        if (t_vals) t_vals[b + rank] = vals[my];
+    }
+}
+
+static size_t align256(size_t b) { return (b + 255) & ~size_t(255); }
+
+int launch_csr_transpose(const dr_csr* A, int32_t* t_rowptr, int32_t* t_colidx, float* t_vals, void* ws,
+                         hipStream_t s) {
+    const int n_rows = (int)A->n_rows, n_cols = (int)A->n_cols, nnz = (int)A->nnz;
+    char* w = static_cast<char*>(ws);
+    int32_t* cursor = reinterpret_cast<int32_t*>(w);
+    w += align256(4 * (size_t)(n_cols + 1));
+    int32_t* key = reinterpret_cast<int32_t*>(w);
+    w += align256(4 * (size_t)(nnz + 1));
+    int32_t* erow = reinterpret_cast<int32_t*>(w);
+    w += align256(4 * (size_t)(nnz + 1));
+    int32_t* sums = reinterpret_cast<int32_t*>(w);
+
+    if (int rc = launch_fill_u32(reinterpret_cast<uint32_t*>(t_rowptr), (size_t)n_cols + 1, 0u, s)) return rc;
+    if (int rc = launch_fill_u32(reinterpret_cast<uint32_t*>(cursor), (size_t)n_cols + 1, 0u, s)) return rc;
+    if (nnz > 0) {
+        unsigned eb = (unsigned)((nnz + 255) / 256);
+        hipLaunchKernelGGL(count_columns_kernel, dim3(eb), dim3(256), 0, s, A->colidx, nnz, t_rowptr + 1);
+        // inclusive scan of t_rowptr[1..n_cols]
+        int nb = (n_cols + kScanBlock - 1) / kScanBlock;
+        hipLaunchKernelGGL(scan_block_sums_kernel, dim3(nb), dim3(kScanBlock), 0, s, t_rowptr + 1, n_cols, sums);
+        hipLaunchKernelGGL(scan_sums_kernel, dim3(1), dim3(kScanBlock), 0, s, sums, nb);
+        hipLaunchKernelGGL(scan_apply_kernel, dim3(nb), dim3(kScanBlock), 0, s, t_rowptr + 1, n_cols, sums);
+        hipLaunchKernelGGL(transpose_scatter_kernel, dim3(eb), dim3(256), 0, s, A->rowptr, A->colidx, n_rows, nnz,
+                           t_rowptr, cursor, key, erow);
+        unsigned pb = (unsigned)((n_cols + 3) / 4);
+        hipLaunchKernelGGL(transpose_place_kernel, dim3(pb), dim3(256), 0, s, t_rowptr, n_cols, key, erow, A->vals,
+                           t_colidx, t_vals);
+    }
+    DRC_HIP(hipGetLastError());
+    return DR_OK;
+}
+
+}  // namespace drc

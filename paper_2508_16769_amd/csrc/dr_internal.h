@@ -1,0 +1,91 @@
+// Internal declarations shared by the HIP translation units of libdrcgnn (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstddef>
+#include <cstdint>
+#include <cstdio>
+
+#include "dr_circuitgnn.h"
+
+namespace drc {
+
+constexpr int kWave = 64;      // CDNA wavefront width
+constexpr int kNumXcd = 8;     // MI355X: 8 accelerator complex dies, one L2 each
+
+// thread-local error text ------------------------------------------------------------------------
+void set_error(const char* fmt, ...);
+int fail(int code, const char* fmt, ...);
+int hip_fail(hipError_t e, const char* what);
+
+#define DRC_HIP(call)                                                   \
+    do {                                                                \
+        hipError_t drc_e__ = (call);                                    \
+        if (drc_e__ != hipSuccess) return ::drc::hip_fail(drc_e__, #call); \
+    } while (0)
+
+#define DRC_REQUIRE(cond, ...)                                          \
+    do {                                                                \
+        if (!(cond)) return ::drc::fail(DR_ERR_INVALID_ARG, __VA_ARGS__); \
+    } while (0)
+
+int check_csr(const dr_csr* A, const char* name, bool need_vals);
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+inline hipStream_t as_stream(void* s) { return static_cast<hipStream_t>(s); }
+
+// Workgroups are dealt to the XCDs round-robin by workgroup id.  Remap so that each XCD walks one
+// contiguous range of logical tiles (neighbouring tiles share gathered rows in that XCD's L2).
+// `per_xcd` = ceil(n_tiles / kNumXcd); launch per_xcd * kNumXcd workgroups and drop ids >= n_tiles.
+__device__ __forceinline__ int xcd_contiguous_tile(int wg, int per_xcd) {
+    return (wg % kNumXcd) * per_xcd + wg / kNumXcd;
+}
+
+// launchers (host side, argument checks already done by the ABI layer) ------------------------------
+int launch_topk(const float* X, int64_t n, int D, int k, float* vals, uint16_t* idx, hipStream_t s);
+int launch_spmm_fwd(const dr_csr* A, const float* xs_vals, const uint16_t* xs_idx, int D, int k, float* H,
+                    hipStream_t s);
+int launch_spmm_bwd(const dr_csr* At, const float* dH, const uint16_t* xs_idx, int D, int k, float* dXs,
+                    int accumulate, hipStream_t s);
+int launch_csr_transpose(const dr_csr* A, int32_t* t_rowptr, int32_t* t_colidx, float* t_vals, void* ws,
+                         hipStream_t s);
+int launch_csr_normalize(int mode, int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t* rowptr,
+                         const int32_t* colidx, float* vals_out, void* ws, hipStream_t s);
+int launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t s);
+
+// dense part of the layer ------------------------------------------------------------------------------
+struct GemmOperand {              // one K-segment of C = sum_seg A_seg * B_seg
+    const float* dense;           // [rows, D] or nullptr
+    const float* cbsr_vals;       // [rows, k] (with cbsr_idx) when the operand is a D-ReLU output
+    const uint16_t* cbsr_idx;
+    int k;
+    const uint8_t* mask;          // optional [rows, D] gate applied to `dense`
+    int mask_keep;                // keep elements whose mask byte equals this value
+    const float* W;               // [D, D]
+    int transpose_w;              // 0: B = W, 1: B = W^T
+};
+enum GemmEpilogue { kEpiStore = 0, kEpiMaxMerge = 1, kEpiSampleAdd = 2 };
+// C[rows, D] = sum over segments; epilogue:
+//   kEpiStore     : out[rows,D] = C
+//   kEpiMaxMerge  : mask_out = (out >= C); out = max(out, C)          (out holds the near branch on entry)
+//   kEpiSampleAdd : compact[rows,k] += C[row, idx[row,t]]
+int launch_gemm(const GemmOperand* segs, int nseg, int64_t rows, int D, GemmEpilogue epi, float* out,
+                uint8_t* mask_out, const uint16_t* sample_idx, int sample_k, float* compact, hipStream_t s);
+
+struct WgradOperand {             // dW[D,D] = A^T B over `rows` rows
+    const float* a_dense;         // [rows, D] or nullptr
+    const float* a_cbsr_vals;     // CBSR alternative for A
+    const uint16_t* a_cbsr_idx;
+    int k;
+    const float* b;               // [rows, D]
+    const uint8_t* b_mask;        // optional gate on b
+    int b_mask_keep;
+};
+size_t wgrad_scratch_bytes(int64_t rows, int D);
+int launch_wgrad(const WgradOperand& op, int64_t rows, int D, float* dW, void* scratch, hipStream_t s);
+
+int launch_scatter_compact(const float* compact, const uint16_t* idx, int64_t n, int D, int k, float* dense,
+                           hipStream_t s);
+
+}  // namespace drc

@@ -1,0 +1,311 @@
+// HeteroConv layer: per-graph context and the forward / backward schedules.  The three relation
+// pipelines (near, pins, pinned) run on three HIP streams of the one GPU and are joined by events only
+// where the data flow demands it (paper Section 3.4: independent sub-graph updates launched together,
+// merged at the cell node type).  The host never waits inside fwd / bwd.
+#include "dr_internal.h"
+
+#include <new>
+
+struct dr_heteroconv {
+    int64_t Nc, Nn;
+    int D, k_cell, k_net;
+    dr_csr A[3];        // near, pins, pinned (borrowed)
+    dr_csr At[3];       // transposes (owned)
+    void* owned[32];
+    int n_owned;
+    hipStream_t st[3];  // near, pins, pinned
+    hipEvent_t ev_fork, ev_topk_cell, ev_topk_net, ev_near, ev_pins, ev_pinned, ev_gnear, ev_gpins;
+    // backward scratch
+    float* dH[3];       // [Nc,D], [Nn,D], [Nc,D]
+    float* dXs_cell;    // [Nc,k_cell]
+    float* dXs_net;     // [Nn,k_net]
+    float* wg_scratch[3];
+    int device;
+};
+
+using namespace drc;
+
+namespace {
+
+int dev_alloc(dr_heteroconv* c, void** p, size_t bytes) {
+    *p = nullptr;
+    if (bytes == 0) bytes = 256;
+    DRC_HIP(hipMalloc(p, bytes));
+    c->owned[c->n_owned++] = *p;
+    return DR_OK;
+}
+
+void release(dr_heteroconv* c) {
+    if (!c) return;
+    for (int i = 0; i < c->n_owned; ++i) (void)hipFree(c->owned[i]);
+    for (int i = 0; i < 3; ++i)
+        if (c->st[i]) (void)hipStreamDestroy(c->st[i]);
+    hipEvent_t* evs[] = {&c->ev_fork, &c->ev_topk_cell, &c->ev_topk_net, &c->ev_near,
+                         &c->ev_pins, &c->ev_pinned, &c->ev_gnear, &c->ev_gpins};
+    for (hipEvent_t* e : evs)
+        if (*e) (void)hipEventDestroy(*e);
+    delete c;
+}
+
+}  // namespace
+
+extern "C" {
+
+int heteroconv_create(dr_heteroconv** ctx, const dr_csr* near, const dr_csr* pins, const dr_csr* pinned,
+                      int32_t D, int32_t k_cell, int32_t k_net) {
+    DRC_REQUIRE(ctx != nullptr, "heteroconv_create: null ctx");
+    *ctx = nullptr;
+    if (int rc = check_csr(near, "heteroconv_create: near", true)) return rc;
+    if (int rc = check_csr(pins, "heteroconv_create: pins", true)) return rc;
+    if (int rc = check_csr(pinned, "heteroconv_create: pinned", true)) return rc;
+    DRC_REQUIRE(near->n_rows == near->n_cols, "heteroconv_create: near must be square (cell x cell)");
+    const int64_t Nc = near->n_rows, Nn = pins->n_rows;
+    DRC_REQUIRE(pins->n_cols == Nc, "heteroconv_create: pins must be Nn x Nc");
+    DRC_REQUIRE(pinned->n_rows == Nc && pinned->n_cols == Nn, "heteroconv_create: pinned must be Nc x Nn");
+    DRC_REQUIRE(k_cell >= 1 && k_net >= 1, "heteroconv_create: k must be >= 1");
+    DRC_REQUIRE(k_cell <= D && k_net <= D, "heteroconv_create: k exceeds D");
+    if (!(D == 32 || D == 64 || D == 96 || D == 128))
+        return fail(DR_ERR_UNSUPPORTED, "heteroconv_create: D = %d not in {32,64,96,128}", D);
+    DRC_REQUIRE(Nc * (int64_t)D < (int64_t(1) << 31) * 2 && Nn * (int64_t)D < (int64_t(1) << 31) * 2,
+                "heteroconv_create: n*D too large");
+
+    dr_heteroconv* c = new (std::nothrow) dr_heteroconv();
+    DRC_REQUIRE(c != nullptr, "heteroconv_create: out of host memory");
+    c->Nc = Nc; c->Nn = Nn; c->D = D; c->k_cell = k_cell; c->k_net = k_net;
+    c->A[0] = *near; c->A[1] = *pins; c->A[2] = *pinned;
+
+    int rc = DR_OK;
+    auto bail = [&](int code) { release(c); return code; };
+    if (hipGetDevice(&c->device) != hipSuccess) return bail(hip_fail(hipGetLastError(), "hipGetDevice"));
+    for (int i = 0; i < 3; ++i)
+        if (hipStreamCreateWithFlags(&c->st[i], hipStreamNonBlocking) != hipSuccess)
+            return bail(hip_fail(hipGetLastError(), "hipStreamCreateWithFlags"));
+    hipEvent_t* evs[] = {&c->ev_fork, &c->ev_topk_cell, &c->ev_topk_net, &c->ev_near,
+                         &c->ev_pins, &c->ev_pinned, &c->ev_gnear, &c->ev_gpins};
+    for (hipEvent_t* e : evs)
+        if (hipEventCreateWithFlags(e, hipEventDisableTiming) != hipSuccess)
+            return bail(hip_fail(hipGetLastError(), "hipEventCreateWithFlags"));
+
+    // transposed adjacencies
+    for (int i = 0; i < 3 && rc == DR_OK; ++i) {
+        const dr_csr& A = c->A[i];
+        int32_t *rp = nullptr, *ci = nullptr;
+        float* v = nullptr;
+        void* ws = nullptr;
+        size_t wsb = dr_csr_transpose_workspace_bytes(A.n_rows, A.n_cols, A.nnz);
+        if ((rc = dev_alloc(c, (void**)&rp, 4 * (size_t)(A.n_cols + 1)))) break;
+        if ((rc = dev_alloc(c, (void**)&ci, 4 * (size_t)A.nnz))) break;
+        if ((rc = dev_alloc(c, (void**)&v, 4 * (size_t)A.nnz))) break;
+        if (hipMalloc(&ws, wsb) != hipSuccess) { rc = hip_fail(hipGetLastError(), "hipMalloc(transpose workspace)"); break; }
+        rc = dr_csr_transpose(&A, rp, ci, v, ws, wsb, c->st[i]);
+        hipError_t e = hipStreamSynchronize(c->st[i]);
+        (void)hipFree(ws);
+        if (rc == DR_OK && e != hipSuccess) rc = hip_fail(e, "hipStreamSynchronize(transpose)");
+        c->At[i] = dr_csr{A.n_cols, A.n_rows, A.nnz, rp, ci, v};
+    }
+    if (rc) return bail(rc);
+
+    const int64_t drows[3] = {Nc, Nn, Nc};
+    for (int i = 0; i < 3; ++i) {
+        if ((rc = dev_alloc(c, (void**)&c->dH[i], 4 * (size_t)drows[i] * D))) return bail(rc);
+        if ((rc = dev_alloc(c, (void**)&c->wg_scratch[i], wgrad_scratch_bytes(Nc > Nn ? Nc : Nn, D)))) return bail(rc);
+    }
+    if ((rc = dev_alloc(c, (void**)&c->dXs_cell, 4 * (size_t)Nc * k_cell))) return bail(rc);
+    if ((rc = dev_alloc(c, (void**)&c->dXs_net, 4 * (size_t)Nn * k_net))) return bail(rc);
+    if (hipDeviceSynchronize() != hipSuccess) return bail(hip_fail(hipGetLastError(), "hipDeviceSynchronize"));
+    *ctx = c;
+    return DR_OK;
+}
+
+int heteroconv_destroy(dr_heteroconv* ctx) {
+    if (!ctx) return DR_OK;
+    (void)hipDeviceSynchronize();
+    release(ctx);
+    return DR_OK;
+}
+
+int heteroconv_get_transpose(const dr_heteroconv* ctx, int which, dr_csr* out) {
+    DRC_REQUIRE(ctx && out, "heteroconv_get_transpose: null argument");
+    DRC_REQUIRE(which >= 0 && which < 3, "heteroconv_get_transpose: which must be 0, 1 or 2");
+    *out = ctx->At[which];
+    return DR_OK;
+}
+
+static int check_weights(const dr_heteroconv_weights* W, const char* fn) {
+    DRC_REQUIRE(W != nullptr, "%s: null weights", fn);
+    DRC_REQUIRE(W->self_near && W->neigh_near && W->self_pins && W->neigh_pins && W->pinned,
+                "%s: null weight matrix", fn);
+    DRC_REQUIRE(aligned(W->self_near, 16) && aligned(W->neigh_near, 16) && aligned(W->self_pins, 16) &&
+                    aligned(W->neigh_pins, 16) && aligned(W->pinned, 16),
+                "%s: weight matrices must be 16-byte aligned", fn);
+    return DR_OK;
+}
+
+static int check_saved(const dr_heteroconv_saved* S, const char* fn) {
+    DRC_REQUIRE(S != nullptr, "%s: null saved", fn);
+    DRC_REQUIRE(S->vals_cell && S->idx_cell && S->vals_net && S->idx_net && S->H_near && S->H_pins &&
+                    S->H_pinned && S->mask,
+                "%s: null buffer in saved", fn);
+    DRC_REQUIRE(aligned(S->H_near, 16) && aligned(S->H_pins, 16) && aligned(S->H_pinned, 16) &&
+                    aligned(S->mask, 4) && aligned(S->vals_cell, 4) && aligned(S->vals_net, 4),
+                "%s: misaligned buffer in saved", fn);
+    return DR_OK;
+}
+
+#define DRC_TRY(expr)            \
+    do {                         \
+        int drc_rc__ = (expr);   \
+        if (drc_rc__) return drc_rc__; \
+    } while (0)
+
+int heteroconv_fwd(dr_heteroconv* c, const float* X_cell, const float* X_net, const dr_heteroconv_weights* W,
+                   float* Y_cell, float* Y_net, const dr_heteroconv_saved* S, void* stream) {
+    DRC_REQUIRE(c != nullptr, "heteroconv_fwd: null context");
+    DRC_REQUIRE(X_cell && X_net && Y_cell && Y_net, "heteroconv_fwd: null tensor");
+    DRC_REQUIRE(aligned(X_cell, 16) && aligned(X_net, 16) && aligned(Y_cell, 16) && aligned(Y_net, 16),
+                "heteroconv_fwd: tensors must be 16-byte aligned");
+    DRC_TRY(check_weights(W, "heteroconv_fwd"));
+    DRC_TRY(check_saved(S, "heteroconv_fwd"));
+    hipStream_t user = as_stream(stream);
+    hipStream_t s_near = c->st[0], s_pins = c->st[1], s_pinned = c->st[2];
+    const int D = c->D;
+
+    DRC_HIP(hipEventRecord(c->ev_fork, user));
+    for (int i = 0; i < 3; ++i) DRC_HIP(hipStreamWaitEvent(c->st[i], c->ev_fork, 0));
+
+    // D-ReLU of both node types
+    DRC_TRY(launch_topk(X_cell, c->Nc, D, c->k_cell, S->vals_cell, S->idx_cell, s_near));
+    DRC_HIP(hipEventRecord(c->ev_topk_cell, s_near));
+    DRC_TRY(launch_topk(X_net, c->Nn, D, c->k_net, S->vals_net, S->idx_net, s_pinned));
+    DRC_HIP(hipEventRecord(c->ev_topk_net, s_pinned));
+
+    // near: cell -> cell
+    DRC_TRY(launch_spmm_fwd(&c->A[0], S->vals_cell, S->idx_cell, D, c->k_cell, S->H_near, s_near));
+    {
+        GemmOperand seg[2] = {};
+        seg[0].cbsr_vals = S->vals_cell; seg[0].cbsr_idx = S->idx_cell; seg[0].k = c->k_cell; seg[0].W = W->self_near;
+        seg[1].dense = S->H_near; seg[1].W = W->neigh_near;
+        DRC_TRY(launch_gemm(seg, 2, c->Nc, D, kEpiStore, Y_cell, nullptr, nullptr, 0, nullptr, s_near));
+    }
+    DRC_HIP(hipEventRecord(c->ev_near, s_near));
+
+    // pins: cell -> net
+    DRC_HIP(hipStreamWaitEvent(s_pins, c->ev_topk_cell, 0));
+    DRC_TRY(launch_spmm_fwd(&c->A[1], S->vals_cell, S->idx_cell, D, c->k_cell, S->H_pins, s_pins));
+    DRC_HIP(hipStreamWaitEvent(s_pins, c->ev_topk_net, 0));
+    {
+        GemmOperand seg[2] = {};
+        seg[0].cbsr_vals = S->vals_net; seg[0].cbsr_idx = S->idx_net; seg[0].k = c->k_net; seg[0].W = W->self_pins;
+        seg[1].dense = S->H_pins; seg[1].W = W->neigh_pins;
+        DRC_TRY(launch_gemm(seg, 2, c->Nn, D, kEpiStore, Y_net, nullptr, nullptr, 0, nullptr, s_pins));
+    }
+    DRC_HIP(hipEventRecord(c->ev_pins, s_pins));
+
+    // pinned: net -> cell, merged into Y_cell by max once the near branch is there
+    DRC_TRY(launch_spmm_fwd(&c->A[2], S->vals_net, S->idx_net, D, c->k_net, S->H_pinned, s_pinned));
+    DRC_HIP(hipStreamWaitEvent(s_pinned, c->ev_near, 0));
+    {
+        GemmOperand seg[1] = {};
+        seg[0].dense = S->H_pinned; seg[0].W = W->pinned;
+        DRC_TRY(launch_gemm(seg, 1, c->Nc, D, kEpiMaxMerge, Y_cell, S->mask, nullptr, 0, nullptr, s_pinned));
+    }
+    DRC_HIP(hipEventRecord(c->ev_pinned, s_pinned));
+
+    DRC_HIP(hipStreamWaitEvent(user, c->ev_pins, 0));
+    DRC_HIP(hipStreamWaitEvent(user, c->ev_pinned, 0));
+    return DR_OK;
+}
+
+int heteroconv_bwd(dr_heteroconv* c, const float* dY_cell, const float* dY_net, const dr_heteroconv_weights* W,
+                   const dr_heteroconv_saved* S, float* dX_cell, float* dX_net, const dr_heteroconv_wgrads* dW,
+                   void* stream) {
+    DRC_REQUIRE(c != nullptr, "heteroconv_bwd: null context");
+    DRC_REQUIRE(dY_cell && dY_net && dX_cell && dX_net, "heteroconv_bwd: null tensor");
+    DRC_REQUIRE(aligned(dY_cell, 16) && aligned(dY_net, 16) && aligned(dX_cell, 4) && aligned(dX_net, 4),
+                "heteroconv_bwd: misaligned tensor");
+    DRC_TRY(check_weights(W, "heteroconv_bwd"));
+    DRC_TRY(check_saved(S, "heteroconv_bwd"));
+    DRC_REQUIRE(dW && dW->self_near && dW->neigh_near && dW->self_pins && dW->neigh_pins && dW->pinned,
+                "heteroconv_bwd: null weight gradient");
+    hipStream_t user = as_stream(stream);
+    hipStream_t s_near = c->st[0], s_pins = c->st[1], s_pinned = c->st[2];
+    const int D = c->D;
+
+    DRC_HIP(hipEventRecord(c->ev_fork, user));
+    for (int i = 0; i < 3; ++i) DRC_HIP(hipStreamWaitEvent(c->st[i], c->ev_fork, 0));
+
+    // ---- near stream: dH_near, its transposed SpMM (first piece of dXs_cell), near weight gradients ----
+    {
+        GemmOperand seg[1] = {};
+        seg[0].dense = dY_cell; seg[0].mask = S->mask; seg[0].mask_keep = 1;
+        seg[0].W = W->neigh_near; seg[0].transpose_w = 1;
+        DRC_TRY(launch_gemm(seg, 1, c->Nc, D, kEpiStore, c->dH[0], nullptr, nullptr, 0, nullptr, s_near));
+    }
+    DRC_TRY(launch_spmm_bwd(&c->At[0], c->dH[0], S->idx_cell, D, c->k_cell, c->dXs_cell, 0, s_near));
+    DRC_HIP(hipEventRecord(c->ev_gnear, s_near));
+    {
+        WgradOperand op = {};
+        op.a_dense = S->H_near; op.b = dY_cell; op.b_mask = S->mask; op.b_mask_keep = 1;
+        DRC_TRY(launch_wgrad(op, c->Nc, D, dW->neigh_near, c->wg_scratch[0], s_near));
+        WgradOperand os = {};
+        os.a_cbsr_vals = S->vals_cell; os.a_cbsr_idx = S->idx_cell; os.k = c->k_cell;
+        os.b = dY_cell; os.b_mask = S->mask; os.b_mask_keep = 1;
+        DRC_TRY(launch_wgrad(os, c->Nc, D, dW->self_near, c->wg_scratch[0], s_near));
+    }
+    DRC_HIP(hipEventRecord(c->ev_near, s_near));
+
+    // ---- pins stream: dH_pins, second piece of dXs_cell, near self term, dense dX_cell, pins weight gradients ----
+    {
+        GemmOperand seg[1] = {};
+        seg[0].dense = dY_net; seg[0].W = W->neigh_pins; seg[0].transpose_w = 1;
+        DRC_TRY(launch_gemm(seg, 1, c->Nn, D, kEpiStore, c->dH[1], nullptr, nullptr, 0, nullptr, s_pins));
+    }
+    DRC_HIP(hipStreamWaitEvent(s_pins, c->ev_gnear, 0));
+    DRC_TRY(launch_spmm_bwd(&c->At[1], c->dH[1], S->idx_cell, D, c->k_cell, c->dXs_cell, 1, s_pins));
+    {
+        GemmOperand seg[1] = {};
+        seg[0].dense = dY_cell; seg[0].mask = S->mask; seg[0].mask_keep = 1;
+        seg[0].W = W->self_near; seg[0].transpose_w = 1;
+        DRC_TRY(launch_gemm(seg, 1, c->Nc, D, kEpiSampleAdd, nullptr, nullptr, S->idx_cell, c->k_cell, c->dXs_cell,
+                            s_pins));
+    }
+    DRC_TRY(launch_scatter_compact(c->dXs_cell, S->idx_cell, c->Nc, D, c->k_cell, dX_cell, s_pins));
+    {
+        WgradOperand op = {};
+        op.a_dense = S->H_pins; op.b = dY_net;
+        DRC_TRY(launch_wgrad(op, c->Nn, D, dW->neigh_pins, c->wg_scratch[1], s_pins));
+        WgradOperand os = {};
+        os.a_cbsr_vals = S->vals_net; os.a_cbsr_idx = S->idx_net; os.k = c->k_net; os.b = dY_net;
+        DRC_TRY(launch_wgrad(os, c->Nn, D, dW->self_pins, c->wg_scratch[1], s_pins));
+    }
+    DRC_HIP(hipEventRecord(c->ev_pins, s_pins));
+
+    // ---- pinned stream: dH_pinned, dXs_net, pins self term, dense dX_net, pinned weight gradient ----
+    {
+        GemmOperand seg[1] = {};
+        seg[0].dense = dY_cell; seg[0].mask = S->mask; seg[0].mask_keep = 0;
+        seg[0].W = W->pinned; seg[0].transpose_w = 1;
+        DRC_TRY(launch_gemm(seg, 1, c->Nc, D, kEpiStore, c->dH[2], nullptr, nullptr, 0, nullptr, s_pinned));
+    }
+    DRC_TRY(launch_spmm_bwd(&c->At[2], c->dH[2], S->idx_net, D, c->k_net, c->dXs_net, 0, s_pinned));
+    {
+        GemmOperand seg[1] = {};
+        seg[0].dense = dY_net; seg[0].W = W->self_pins; seg[0].transpose_w = 1;
+        DRC_TRY(launch_gemm(seg, 1, c->Nn, D, kEpiSampleAdd, nullptr, nullptr, S->idx_net, c->k_net, c->dXs_net,
+                            s_pinned));
+    }
+    DRC_TRY(launch_scatter_compact(c->dXs_net, S->idx_net, c->Nn, D, c->k_net, dX_net, s_pinned));
+    {
+        WgradOperand op = {};
+        op.a_dense = S->H_pinned; op.b = dY_cell; op.b_mask = S->mask; op.b_mask_keep = 0;
+        DRC_TRY(launch_wgrad(op, c->Nc, D, dW->pinned, c->wg_scratch[2], s_pinned));
+    }
+    DRC_HIP(hipEventRecord(c->ev_pinned, s_pinned));
+
+    DRC_HIP(hipStreamWaitEvent(user, c->ev_near, 0));
+    DRC_HIP(hipStreamWaitEvent(user, c->ev_pins, 0));
+    DRC_HIP(hipStreamWaitEvent(user, c->ev_pinned, 0));
+    return DR_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,91 @@
+// D-ReLU (paper Section 3.1): per row keep the k largest signed values, ties to the lowest column,
+// survivors written in ascending column order as CBSR (vals, idx).
+//
+// One wavefront owns one row at a time.  Lane l holds columns l, 64+l, 128+l, ... (coalesced dword
+// loads).  Values are mapped to order-preserving unsigned keys; the k-th largest key is found by a
+// most-significant-bit-first search in which every step is one v_cmp per register plus a scalar
+// popcount of the ballot; compaction positions come from mbcnt prefix counts of the keep-ballots, which
+// yields ascending column order for free.
+#include "dr_internal.h"
+
+namespace drc {
+
+__device__ __forceinline__ uint32_t order_key(float v) {
+    uint32_t u = __float_as_uint(v);
+    if (u == 0x80000000u) u = 0u;                       // -0.0 ties with +0.0
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);  // larger float <=> larger key; all keys > 0
+}
+
+__device__ __forceinline__ int lanes_below(unsigned long long m) {
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+}
+
+template <int EPL>
+__global__ __launch_bounds__(256) void topk_rows_kernel(const float* __restrict__ X, int n, int D, int k,
+                                                        float* __restrict__ vals, uint16_t* __restrict__ idx) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x >> 6;
+    const int waves_per_grid = gridDim.x * (blockDim.x >> 6);
+    for (int row = blockIdx.x * (blockDim.x >> 6) + wave; row < n; row += waves_per_grid) {
+        const float* x = X + (size_t)row * D;
+        float v[EPL];
+        uint32_t key[EPL];
+#pragma unroll
+        for (int s = 0; s < EPL; ++s) {
+            int c = s * kWave + lane;
+            v[s] = (c < D) ? x[c] : 0.0f;
+            key[s] = (c < D) ? order_key(v[s]) : 0u;    // padding key 0 is below every real key
+        }
+        // T = largest threshold with count(key >= T) >= k  == the k-th largest key
+        uint32_t T = 0;
+#pragma unroll
+        for (int bit = 31; bit >= 0; --bit) {
+            uint32_t cand = T | (1u << bit);
+            int cnt = 0;
+#pragma unroll
+            for (int s = 0; s < EPL; ++s) cnt += __popcll(__ballot(key[s] >= cand));
+            if (cnt >= k) T = cand;
+        }
+        int n_gt = 0;
+#pragma unroll
+        for (int s = 0; s < EPL; ++s) n_gt += __popcll(__ballot(key[s] > T));
+        const int need_eq = k - n_gt;                   // >= 1 ties to take, lowest columns first
+        int kept_before = 0, eq_before = 0;
+        const size_t base = (size_t)row * k;
+#pragma unroll
+        for (int s = 0; s < EPL; ++s) {
+            bool gt = key[s] > T;
+            bool eq = key[s] == T;
+            unsigned long long meq = __ballot(eq);
+            bool keep = gt || (eq && (eq_before + lanes_below(meq)) < need_eq);
+            unsigned long long mk = __ballot(keep);
+            if (keep) {
+                int pos = kept_before + lanes_below(mk);
+                vals[base + pos] = v[s];
+                idx[base + pos] = (uint16_t)(s * kWave + lane);
+            }
+            kept_before += __popcll(mk);
+            eq_before += __popcll(meq);
+        }
+    }
+}
+
+template <int EPL>
+static void launch_epl(const float* X, int n, int D, int k, float* vals, uint16_t* idx, hipStream_t s) {
+    int waves_per_block = 4;
+    long blocks = ((long)n + waves_per_block - 1) / waves_per_block;
+    if (blocks > 32768) blocks = 32768;
+    hipLaunchKernelGGL(topk_rows_kernel<EPL>, dim3((unsigned)blocks), dim3(256), 0, s, X, n, D, k, vals, idx);
+}
+
+int launch_topk(const float* X, int64_t n, int D, int k, float* vals, uint16_t* idx, hipStream_t s) {
+    if (D <= 64) launch_epl<1>(X, (int)n, D, k, vals, idx, s);
+    else if (D <= 128) launch_epl<2>(X, (int)n, D, k, vals, idx, s);
+    else if (D <= 256) launch_epl<4>(X, (int)n, D, k, vals, idx, s);
+    else if (D <= 512) launch_epl<8>(X, (int)n, D, k, vals, idx, s);
+    else launch_epl<16>(X, (int)n, D, k, vals, idx, s);
+    DRC_HIP(hipGetLastError());
+    return DR_OK;
+}
+
+}  // namespace drc
