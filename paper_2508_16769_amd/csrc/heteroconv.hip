@@ -77,6 +77,8 @@ int heteroconv_create(dr_heteroconv** ctx, const dr_csr* near, const dr_csr* pin
     int rc = DR_OK;
     auto bail = [&](int code) { release(c); return code; };
     if (hipGetDevice(&c->device) != hipSuccess) return bail(hip_fail(hipGetLastError(), "hipGetDevice"));
+    // the caller may still be producing the CSR arrays on another stream
+    if (hipDeviceSynchronize() != hipSuccess) return bail(hip_fail(hipGetLastError(), "hipDeviceSynchronize"));
     for (int i = 0; i < 3; ++i)
         if (hipStreamCreateWithFlags(&c->st[i], hipStreamNonBlocking) != hipSuccess)
             return bail(hip_fail(hipGetLastError(), "hipStreamCreateWithFlags"));
