@@ -1,0 +1,255 @@
+#!/usr/bin/env python3
+"""Benchmark of the HeteroConv DR-SpMM hot path on one MI355X.
+
+A *step* is one HeteroConv forward + backward over one seeded synthetic circuit graph: D-ReLU top-k of
+both node types, the three DR-SpMM forwards, the projections and max-merge, and the whole backward
+(projection gradients, the three transposed DR-SpMMs gated by the saved indices, weight gradients).
+Graph setup (edge values, transposes) is done once before the timed region.  Inputs are resident in HBM
+when the timed region starts.
+
+Prints ONE JSON line (see the design doc for the byte model behind `value` and `roofline`).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix, published
+
+
+# ----------------------------------------------------------------------------------------------------
+# algorithmic (compulsory) bytes and flops per kernel: every array the kernel must read or write, once
+# ----------------------------------------------------------------------------------------------------
+
+def kernel_models(Nc, Nn, E, D, kc, kn):
+    """{kernel name: (bytes, flops)} for one step.  E = dict(near=, pins=, pinned=)."""
+    W = 4 * D * D
+
+    def topk(n, k):
+        return 4 * n * D + 6 * n * k, n * D
+
+    def fwd(M, N, e, k):      # rowptr + (colidx, vals) + CBSR of the sources + dense output
+        return 4 * (M + 1) + 8 * e + 6 * N * k + 4 * M * D, 2 * e * k
+
+    def bwd(Nsrc, M, e, k):   # rowptr + (colidx, vals) + saved idx + gathered dH + compact output
+        return 4 * (Nsrc + 1) + 8 * e + 2 * Nsrc * k + min(4 * e * k, 4 * M * D) + 4 * Nsrc * k, 2 * e * k
+
+    m = {}
+    m["dr_topk.cell"] = topk(Nc, kc)
+    m["dr_topk.net"] = topk(Nn, kn)
+    m["dr_spmm_fwd.near"] = fwd(Nc, Nc, E["near"], kc)
+    m["dr_spmm_fwd.pins"] = fwd(Nn, Nc, E["pins"], kc)
+    m["dr_spmm_fwd.pinned"] = fwd(Nc, Nn, E["pinned"], kn)
+    m["proj.near"] = (6 * Nc * kc + 4 * Nc * D + 2 * W + 4 * Nc * D, 2 * Nc * D * (D + kc))
+    m["proj.pins"] = (6 * Nn * kn + 4 * Nn * D + 2 * W + 4 * Nn * D, 2 * Nn * D * (D + kn))
+    m["proj.pinned+merge"] = (4 * Nc * D + W + 8 * Nc * D + Nc * D, 2 * Nc * D * D)
+    m["dproj.near"] = (5 * Nc * D + W + 4 * Nc * D, 2 * Nc * D * D)
+    m["dproj.pins"] = (4 * Nn * D + W + 4 * Nn * D, 2 * Nn * D * D)
+    m["dproj.pinned"] = (5 * Nc * D + W + 4 * Nc * D, 2 * Nc * D * D)
+    m["dr_spmm_bwd.near"] = bwd(Nc, Nc, E["near"], kc)
+    m["dr_spmm_bwd.pins"] = bwd(Nc, Nn, E["pins"], kc)
+    m["dr_spmm_bwd.pinned"] = bwd(Nn, Nc, E["pinned"], kn)
+    m["dself.near(sampled)"] = (5 * Nc * D + W + 10 * Nc * kc, 2 * Nc * D * kc)
+    m["dself.pins(sampled)"] = (4 * Nn * D + W + 10 * Nn * kn, 2 * Nn * D * kn)
+    m["wgrad.neigh_near"] = (4 * Nc * D + 5 * Nc * D + W, 2 * Nc * D * D)
+    m["wgrad.self_near"] = (6 * Nc * kc + 5 * Nc * D + W, 2 * Nc * D * kc)
+    m["wgrad.neigh_pins"] = (8 * Nn * D + W, 2 * Nn * D * D)
+    m["wgrad.self_pins"] = (6 * Nn * kn + 4 * Nn * D + W, 2 * Nn * D * kn)
+    m["wgrad.pinned"] = (4 * Nc * D + 5 * Nc * D + W, 2 * Nc * D * D)
+    m["scatter.cell"] = (6 * Nc * kc + 4 * Nc * D, 0)
+    m["scatter.net"] = (6 * Nn * kn + 4 * Nn * D, 0)
+    return m
+
+
+DR_KERNELS = ("dr_topk.cell", "dr_topk.net", "dr_spmm_fwd.near", "dr_spmm_fwd.pins", "dr_spmm_fwd.pinned",
+              "dr_spmm_bwd.near", "dr_spmm_bwd.pins", "dr_spmm_bwd.pinned")
+
+
+def cpu_baseline(name: str, D: int, k: int, scale: int):
+    """The oracle's layer forward + backward on a 1/scale-size graph drawn from the same laws."""
+    import numpy as np  # noqa: F401
+    import oracle
+    from circuit_synth import make_graph, make_tensors, workload
+    w = workload(name)
+    gw, gh = w["grid"]
+    f = scale ** 0.5
+    Nc, Nn = w["Nc"] // scale, w["Nn"] // scale
+    grid = (max(8, int(round(gw / f))), max(8, int(round(gh / f))))
+    while grid[0] * grid[1] < Nc:
+        grid = (grid[0] + 1, grid[1])
+    g = make_graph(name, seed=0, Nc=Nc, Nn=Nn, grid=grid)
+    T = make_tensors(Nc, Nn, D, seed=0)
+    rels = (oracle.relation(g.near, oracle.NORM_MEAN), oracle.relation(g.pins, oracle.NORM_MEAN),
+            oracle.relation(g.pinned, oracle.NORM_SYM))
+    t0 = time.perf_counter()
+    of = oracle.heteroconv_fwd(*rels, T.X_cell, T.X_net, T.W, k, k)
+    oracle.heteroconv_bwd(*rels, T.W, of, T.dY_cell, T.dY_net)
+    dt = time.perf_counter() - t0
+    models = kernel_models(Nc, Nn, dict(near=g.near.nnz, pins=g.pins.nnz, pinned=g.pinned.nnz), D, k, k)
+    step_bytes = sum(b for b, _ in models.values())
+    return dict(value=round(step_bytes / dt / 1e9, 4), unit="GB/s", cores=1, kind="oracle",
+                sample=f"oracle HeteroConv fwd+bwd (fp64, 1 thread) on a 1/{scale}-scale '{name}' graph: "
+                       f"{Nc} cells, {Nn} nets, E_near={g.near.nnz}, E_pins={g.pins.nnz}, D={D}, k={k}; "
+                       f"{dt:.2f} s for {step_bytes / 1e6:.1f} MB of algorithmic traffic",
+                seconds=round(dt, 3), host_cores_available=len(os.sched_getaffinity(0)))
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="large", help="tiny | small | medium | large | subgraph")
+    ap.add_argument("--k", type=int, default=None, help="D-ReLU k (default: the workload's; large sweeps 8..64)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-scale", type=int, default=None, help="oracle sample = 1/scale of the workload")
+    ap.add_argument("--no-profile-events", action="store_true", help="do not bracket kernels with HIP events")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (the path is single-GPU; see DESIGN.md for how it "
+              "would shard); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import paper_2508_16769_amd as P
+    from circuit_synth import make_graph, make_tensors, workload
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    w = workload(args.workload)
+    D = w["D"]
+    k = args.k if args.k is not None else w["k"]
+
+    t_setup = time.perf_counter()
+    g = make_graph(args.workload, seed=0)
+    T = make_tensors(g.Nc, g.Nn, D, seed=0)
+    E = dict(near=g.near.nnz, pins=g.pins.nnz, pinned=g.pinned.nnz)
+
+    def dev(a):
+        return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    near = P.device_relation(g.near, P.DR_NORM_MEAN)
+    pins = P.device_relation(g.pins, P.DR_NORM_MEAN)
+    pinned = P.device_relation(g.pinned, P.DR_NORM_SYM)
+    torch.cuda.synchronize()
+    t_graph = time.perf_counter()
+    layer = P.HeteroConv(near, pins, pinned, D, k, k)     # device transposes + scratch
+    t_ctx = time.perf_counter() - t_graph
+    saved = layer.alloc_saved()
+    Wd = {n: dev(T.W[n]) for n in P.WEIGHT_NAMES}
+    X_cell, X_net = dev(T.X_cell), dev(T.X_net)
+    dY_cell, dY_net = dev(T.dY_cell), dev(T.dY_net)
+    Y_cell = torch.empty((g.Nc, D), dtype=torch.float32, device="cuda")
+    Y_net = torch.empty((g.Nn, D), dtype=torch.float32, device="cuda")
+    dX_cell, dX_net = torch.empty_like(Y_cell), torch.empty_like(Y_net)
+    dW = {n: torch.empty((D, D), dtype=torch.float32, device="cuda") for n in P.WEIGHT_NAMES}
+    del T
+    torch.cuda.synchronize()
+    t_setup = time.perf_counter() - t_setup
+
+    def step():
+        layer.heteroconv_fwd(X_cell, X_net, Wd, Y_cell, Y_net, saved)
+        layer.heteroconv_bwd(dY_cell, dY_net, Wd, saved, dX_cell, dX_net, dW)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    if not args.no_profile_events:
+        layer.heteroconv_profile(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    times = {} if args.no_profile_events else layer.heteroconv_kernel_times()
+    layer.heteroconv_profile(False)
+
+    models = kernel_models(g.Nc, g.Nn, E, D, k, k)
+    step_bytes = sum(b for b, _ in models.values())
+    dr_bytes = sum(models[n][0] for n in DR_KERNELS)
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+
+    kernels = {}
+    for name, (ms_sum, cnt) in times.items():
+        if cnt == 0:
+            continue
+        avg = ms_sum / cnt
+        b, f = models[name]
+        kernels[name] = dict(ms=round(avg, 4), GBs=round(b / (avg * 1e-3) / 1e9, 1),
+                             GFLOPs=round(f / (avg * 1e-3) / 1e9, 1), MB=round(b / 1e6, 2))
+    roofline = None
+    dr_region = None
+    if kernels:
+        dom = max(kernels, key=lambda n: kernels[n]["ms"])
+        b, f = models[dom]
+        avg_s = kernels[dom]["ms"] * 1e-3
+        traffic = None
+        tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+        if os.path.exists(tpath):
+            try:
+                traffic = json.load(open(tpath)).get(f"{args.workload}.k{k}", {}).get(dom)
+            except Exception:
+                traffic = None
+        intensity = f / b
+        if intensity > MFMA_FP32_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9):
+            ach = f / avg_s / 1e12
+            roofline = dict(bound="mfma", achieved=round(ach, 2), peak=MFMA_FP32_PEAK_TFLOPS, unit="TFLOP/s",
+                            frac=round(ach / MFMA_FP32_PEAK_TFLOPS, 4), traffic=traffic, kernel=dom,
+                            avg_ms=kernels[dom]["ms"])
+        else:
+            ach = b / avg_s / 1e9
+            roofline = dict(bound="hbm", achieved=round(ach, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                            frac=round(ach / HBM_PEAK_GBS, 4), traffic=traffic, kernel=dom,
+                            avg_ms=kernels[dom]["ms"])
+        dr_ms = sum(kernels[n]["ms"] for n in DR_KERNELS if n in kernels)
+        dr_flops = sum(models[n][1] for n in DR_KERNELS if n.startswith("dr_spmm"))
+        dr_region = dict(kernels="D-ReLU x2 + DR-SpMM fwd x3 + bwd x3", sum_ms=round(dr_ms, 4),
+                         MB=round(dr_bytes / 1e6, 1), GBs=round(dr_bytes / (dr_ms * 1e-3) / 1e9, 1),
+                         frac_of_hbm_peak=round(dr_bytes / (dr_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                         GFLOPs=round(dr_flops / (dr_ms * 1e-3) / 1e9, 1))
+
+    out = {
+        "metric": "HeteroConv DR-SpMM fwd+bwd effective GB/s",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {g.Nc} cells, {g.Nn} nets, E_near={E['near']}, "
+                               f"E_pins={E['pins']}, D={D}, k={k}, one HeteroConv layer fwd+bwd",
+                   "step_algorithmic_MB": round(step_bytes / 1e6, 1),
+                   "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
+                   "setup_s": round(t_setup, 2), "context_create_s": round(t_ctx, 3)},
+        "roofline": roofline,
+        "dr_spmm_kernels": dr_region,
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        scale = args.cpu_scale or max(1, g.Nc // 48000)
+        out["cpu_baseline"] = cpu_baseline(args.workload, D, k, scale)
+    layer.heteroconv_destroy()
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

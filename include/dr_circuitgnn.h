@@ -187,6 +187,20 @@ int heteroconv_get_transpose(const dr_heteroconv* ctx, int which, dr_csr* out);
 
 int heteroconv_destroy(dr_heteroconv* ctx);
 
+/*
+ * Measurement aid (not part of the method): per-kernel device time of the layer's launches.
+ * heteroconv_profile(ctx, 1) makes every later heteroconv_fwd / heteroconv_bwd bracket each of its kernel
+ * launches with a pair of HIP events recorded on the stream that launch runs on; heteroconv_profile(ctx, 0)
+ * stops that.  heteroconv_kernel_times synchronises the device, adds up the elapsed time per kernel id since
+ * the previous call into ms_sum[n] / launches[n] (host arrays, n >= heteroconv_num_kernels()) and forgets the
+ * recorded launches.  heteroconv_kernel_name(id) names a kernel id ("dr_spmm_fwd.near", ...).
+ * With profiling on, the calls create HIP events on demand (host-side allocation).
+ */
+int heteroconv_profile(dr_heteroconv* ctx, int enable);
+int heteroconv_num_kernels(void);
+const char* heteroconv_kernel_name(int id);
+int heteroconv_kernel_times(dr_heteroconv* ctx, double* ms_sum, int64_t* launches, int n);
+
 #ifdef __cplusplus
 }
 #endif

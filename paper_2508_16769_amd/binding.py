@@ -30,6 +30,7 @@ EXPORTS = (
     "dr_csr_transpose_workspace_bytes", "dr_csr_transpose",
     "dr_csr_normalize_workspace_bytes", "dr_csr_normalize",
     "heteroconv_create", "heteroconv_fwd", "heteroconv_bwd", "heteroconv_get_transpose", "heteroconv_destroy",
+    "heteroconv_profile", "heteroconv_num_kernels", "heteroconv_kernel_name", "heteroconv_kernel_times",
 )
 
 
@@ -83,6 +84,7 @@ def load() -> ctypes.CDLL:
         lib.dr_last_error.restype = ctypes.c_char_p
         lib.dr_csr_transpose_workspace_bytes.restype = ctypes.c_size_t
         lib.dr_csr_normalize_workspace_bytes.restype = ctypes.c_size_t
+        lib.heteroconv_kernel_name.restype = ctypes.c_char_p
         _lib = lib
     return _lib
 
@@ -220,6 +222,18 @@ class HeteroConv:
         out = dr_csr()
         _check(load().heteroconv_get_transpose(self._ctx, ctypes.c_int(which), ctypes.byref(out)))
         return out
+
+    def heteroconv_profile(self, enable: bool) -> None:
+        _check(load().heteroconv_profile(self._ctx, ctypes.c_int(1 if enable else 0)))
+
+    def heteroconv_kernel_times(self) -> Dict[str, tuple]:
+        """{kernel name: (total ms, launches)} since the previous call (synchronises the device)."""
+        lib = load()
+        n = int(lib.heteroconv_num_kernels())
+        ms = (ctypes.c_double * n)()
+        cnt = (ctypes.c_int64 * n)()
+        _check(lib.heteroconv_kernel_times(self._ctx, ms, cnt, ctypes.c_int(n)))
+        return {lib.heteroconv_kernel_name(i).decode(): (float(ms[i]), int(cnt[i])) for i in range(n)}
 
     def heteroconv_destroy(self) -> None:
         if self._ctx:

@@ -5,6 +5,23 @@
 #include "dr_internal.h"
 
 #include <new>
+#include <vector>
+
+namespace {
+// kernel ids for the optional per-kernel timing (heteroconv_profile / heteroconv_kernel_times)
+enum KernelId {
+    kTopkCell, kTopkNet, kFwdNear, kFwdPins, kFwdPinned, kProjNear, kProjPins, kProjPinnedMerge,
+    kDhNear, kBwdNear, kWgNeighNear, kWgSelfNear, kDhPins, kBwdPins, kSelfNearSample, kScatterCell,
+    kWgNeighPins, kWgSelfPins, kDhPinned, kBwdPinned, kSelfPinsSample, kScatterNet, kWgPinned, kNumKernels
+};
+const char* const kKernelNames[kNumKernels] = {
+    "dr_topk.cell", "dr_topk.net", "dr_spmm_fwd.near", "dr_spmm_fwd.pins", "dr_spmm_fwd.pinned",
+    "proj.near", "proj.pins", "proj.pinned+merge",
+    "dproj.near", "dr_spmm_bwd.near", "wgrad.neigh_near", "wgrad.self_near", "dproj.pins", "dr_spmm_bwd.pins",
+    "dself.near(sampled)", "scatter.cell", "wgrad.neigh_pins", "wgrad.self_pins", "dproj.pinned",
+    "dr_spmm_bwd.pinned", "dself.pins(sampled)", "scatter.net", "wgrad.pinned"};
+struct TimedLaunch { int id; hipEvent_t start, stop; };
+}  // namespace
 
 struct dr_heteroconv {
     int64_t Nc, Nn;
@@ -21,6 +38,10 @@ struct dr_heteroconv {
     float* dXs_net;     // [Nn,k_net]
     float* wg_scratch[3];
     int device;
+    // optional per-kernel timing
+    bool profile;
+    std::vector<TimedLaunch>* timed;      // launches recorded since the last heteroconv_kernel_times
+    std::vector<hipEvent_t>* event_pool;  // idle timing events
 };
 
 using namespace drc;
@@ -44,8 +65,34 @@ void release(dr_heteroconv* c) {
                          &c->ev_pins, &c->ev_pinned, &c->ev_gnear, &c->ev_gpins};
     for (hipEvent_t* e : evs)
         if (*e) (void)hipEventDestroy(*e);
+    if (c->timed) {
+        for (TimedLaunch& t : *c->timed) { (void)hipEventDestroy(t.start); (void)hipEventDestroy(t.stop); }
+        delete c->timed;
+    }
+    if (c->event_pool) {
+        for (hipEvent_t e : *c->event_pool) (void)hipEventDestroy(e);
+        delete c->event_pool;
+    }
     delete c;
 }
+
+// Brackets one launch with timing events on its own stream when profiling is on.
+struct ScopedTiming {
+    dr_heteroconv* c; hipStream_t s; TimedLaunch t; bool on;
+    ScopedTiming(dr_heteroconv* c_, int id, hipStream_t s_) : c(c_), s(s_), t{id, nullptr, nullptr}, on(false) {
+        if (!c->profile) return;
+        for (hipEvent_t* e : {&t.start, &t.stop}) {
+            if (!c->event_pool->empty()) { *e = c->event_pool->back(); c->event_pool->pop_back(); }
+            else if (hipEventCreate(e) != hipSuccess) { *e = nullptr; }
+        }
+        if (t.start && t.stop && hipEventRecord(t.start, s) == hipSuccess) on = true;
+    }
+    ~ScopedTiming() {
+        if (!on) return;
+        (void)hipEventRecord(t.stop, s);
+        c->timed->push_back(t);
+    }
+};
 
 }  // namespace
 
@@ -73,6 +120,8 @@ int heteroconv_create(dr_heteroconv** ctx, const dr_csr* near, const dr_csr* pin
     DRC_REQUIRE(c != nullptr, "heteroconv_create: out of host memory");
     c->Nc = Nc; c->Nn = Nn; c->D = D; c->k_cell = k_cell; c->k_net = k_net;
     c->A[0] = *near; c->A[1] = *pins; c->A[2] = *pinned;
+    c->timed = new (std::nothrow) std::vector<TimedLaunch>();
+    c->event_pool = new (std::nothrow) std::vector<hipEvent_t>();
 
     int rc = DR_OK;
     auto bail = [&](int code) { release(c); return code; };
@@ -133,6 +182,32 @@ int heteroconv_get_transpose(const dr_heteroconv* ctx, int which, dr_csr* out) {
     return DR_OK;
 }
 
+int heteroconv_profile(dr_heteroconv* ctx, int enable) {
+    DRC_REQUIRE(ctx != nullptr, "heteroconv_profile: null context");
+    DRC_REQUIRE(ctx->timed && ctx->event_pool, "heteroconv_profile: out of host memory");
+    ctx->profile = enable != 0;
+    return DR_OK;
+}
+
+int heteroconv_num_kernels(void) { return kNumKernels; }
+
+const char* heteroconv_kernel_name(int id) { return (id >= 0 && id < kNumKernels) ? kKernelNames[id] : ""; }
+
+int heteroconv_kernel_times(dr_heteroconv* ctx, double* ms_sum, int64_t* launches, int n) {
+    DRC_REQUIRE(ctx && ms_sum && launches, "heteroconv_kernel_times: null argument");
+    DRC_REQUIRE(n >= kNumKernels, "heteroconv_kernel_times: arrays need heteroconv_num_kernels() entries");
+    for (int i = 0; i < n; ++i) { ms_sum[i] = 0.0; launches[i] = 0; }
+    DRC_HIP(hipDeviceSynchronize());
+    for (TimedLaunch& t : *ctx->timed) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, t.start, t.stop) == hipSuccess) { ms_sum[t.id] += ms; launches[t.id] += 1; }
+        ctx->event_pool->push_back(t.start);
+        ctx->event_pool->push_back(t.stop);
+    }
+    ctx->timed->clear();
+    return DR_OK;
+}
+
 static int check_weights(const dr_heteroconv_weights* W, const char* fn) {
     DRC_REQUIRE(W != nullptr, "%s: null weights", fn);
     DRC_REQUIRE(W->self_near && W->neigh_near && W->self_pins && W->neigh_pins && W->pinned,
@@ -176,40 +251,40 @@ int heteroconv_fwd(dr_heteroconv* c, const float* X_cell, const float* X_net, co
     for (int i = 0; i < 3; ++i) DRC_HIP(hipStreamWaitEvent(c->st[i], c->ev_fork, 0));
 
     // D-ReLU of both node types
-    DRC_TRY(launch_topk(X_cell, c->Nc, D, c->k_cell, S->vals_cell, S->idx_cell, s_near));
+    { ScopedTiming tm(c, kTopkCell, s_near); DRC_TRY(launch_topk(X_cell, c->Nc, D, c->k_cell, S->vals_cell, S->idx_cell, s_near)); }
     DRC_HIP(hipEventRecord(c->ev_topk_cell, s_near));
-    DRC_TRY(launch_topk(X_net, c->Nn, D, c->k_net, S->vals_net, S->idx_net, s_pinned));
+    { ScopedTiming tm(c, kTopkNet, s_pinned); DRC_TRY(launch_topk(X_net, c->Nn, D, c->k_net, S->vals_net, S->idx_net, s_pinned)); }
     DRC_HIP(hipEventRecord(c->ev_topk_net, s_pinned));
 
     // near: cell -> cell
-    DRC_TRY(launch_spmm_fwd(&c->A[0], S->vals_cell, S->idx_cell, D, c->k_cell, S->H_near, s_near));
+    { ScopedTiming tm(c, kFwdNear, s_near); DRC_TRY(launch_spmm_fwd(&c->A[0], S->vals_cell, S->idx_cell, D, c->k_cell, S->H_near, s_near)); }
     {
         GemmOperand seg[2] = {};
         seg[0].cbsr_vals = S->vals_cell; seg[0].cbsr_idx = S->idx_cell; seg[0].k = c->k_cell; seg[0].W = W->self_near;
         seg[1].dense = S->H_near; seg[1].W = W->neigh_near;
-        DRC_TRY(launch_gemm(seg, 2, c->Nc, D, kEpiStore, Y_cell, nullptr, nullptr, 0, nullptr, s_near));
+        { ScopedTiming tm(c, kProjNear, s_near); DRC_TRY(launch_gemm(seg, 2, c->Nc, D, kEpiStore, Y_cell, nullptr, nullptr, 0, nullptr, s_near)); }
     }
     DRC_HIP(hipEventRecord(c->ev_near, s_near));
 
     // pins: cell -> net
     DRC_HIP(hipStreamWaitEvent(s_pins, c->ev_topk_cell, 0));
-    DRC_TRY(launch_spmm_fwd(&c->A[1], S->vals_cell, S->idx_cell, D, c->k_cell, S->H_pins, s_pins));
+    { ScopedTiming tm(c, kFwdPins, s_pins); DRC_TRY(launch_spmm_fwd(&c->A[1], S->vals_cell, S->idx_cell, D, c->k_cell, S->H_pins, s_pins)); }
     DRC_HIP(hipStreamWaitEvent(s_pins, c->ev_topk_net, 0));
     {
         GemmOperand seg[2] = {};
         seg[0].cbsr_vals = S->vals_net; seg[0].cbsr_idx = S->idx_net; seg[0].k = c->k_net; seg[0].W = W->self_pins;
         seg[1].dense = S->H_pins; seg[1].W = W->neigh_pins;
-        DRC_TRY(launch_gemm(seg, 2, c->Nn, D, kEpiStore, Y_net, nullptr, nullptr, 0, nullptr, s_pins));
+        { ScopedTiming tm(c, kProjPins, s_pins); DRC_TRY(launch_gemm(seg, 2, c->Nn, D, kEpiStore, Y_net, nullptr, nullptr, 0, nullptr, s_pins)); }
     }
     DRC_HIP(hipEventRecord(c->ev_pins, s_pins));
 
     // pinned: net -> cell, merged into Y_cell by max once the near branch is there
-    DRC_TRY(launch_spmm_fwd(&c->A[2], S->vals_net, S->idx_net, D, c->k_net, S->H_pinned, s_pinned));
+    { ScopedTiming tm(c, kFwdPinned, s_pinned); DRC_TRY(launch_spmm_fwd(&c->A[2], S->vals_net, S->idx_net, D, c->k_net, S->H_pinned, s_pinned)); }
     DRC_HIP(hipStreamWaitEvent(s_pinned, c->ev_near, 0));
     {
         GemmOperand seg[1] = {};
         seg[0].dense = S->H_pinned; seg[0].W = W->pinned;
-        DRC_TRY(launch_gemm(seg, 1, c->Nc, D, kEpiMaxMerge, Y_cell, S->mask, nullptr, 0, nullptr, s_pinned));
+        { ScopedTiming tm(c, kProjPinnedMerge, s_pinned); DRC_TRY(launch_gemm(seg, 1, c->Nc, D, kEpiMaxMerge, Y_cell, S->mask, nullptr, 0, nullptr, s_pinned)); }
     }
     DRC_HIP(hipEventRecord(c->ev_pinned, s_pinned));
 
@@ -241,18 +316,18 @@ int heteroconv_bwd(dr_heteroconv* c, const float* dY_cell, const float* dY_net, 
         GemmOperand seg[1] = {};
         seg[0].dense = dY_cell; seg[0].mask = S->mask; seg[0].mask_keep = 1;
         seg[0].W = W->neigh_near; seg[0].transpose_w = 1;
-        DRC_TRY(launch_gemm(seg, 1, c->Nc, D, kEpiStore, c->dH[0], nullptr, nullptr, 0, nullptr, s_near));
+        { ScopedTiming tm(c, kDhNear, s_near); DRC_TRY(launch_gemm(seg, 1, c->Nc, D, kEpiStore, c->dH[0], nullptr, nullptr, 0, nullptr, s_near)); }
     }
-    DRC_TRY(launch_spmm_bwd(&c->At[0], c->dH[0], S->idx_cell, D, c->k_cell, c->dXs_cell, 0, s_near));
+    { ScopedTiming tm(c, kBwdNear, s_near); DRC_TRY(launch_spmm_bwd(&c->At[0], c->dH[0], S->idx_cell, D, c->k_cell, c->dXs_cell, 0, s_near)); }
     DRC_HIP(hipEventRecord(c->ev_gnear, s_near));
     {
         WgradOperand op = {};
         op.a_dense = S->H_near; op.b = dY_cell; op.b_mask = S->mask; op.b_mask_keep = 1;
-        DRC_TRY(launch_wgrad(op, c->Nc, D, dW->neigh_near, c->wg_scratch[0], s_near));
+        { ScopedTiming tm(c, kWgNeighNear, s_near); DRC_TRY(launch_wgrad(op, c->Nc, D, dW->neigh_near, c->wg_scratch[0], s_near)); }
         WgradOperand os = {};
         os.a_cbsr_vals = S->vals_cell; os.a_cbsr_idx = S->idx_cell; os.k = c->k_cell;
         os.b = dY_cell; os.b_mask = S->mask; os.b_mask_keep = 1;
-        DRC_TRY(launch_wgrad(os, c->Nc, D, dW->self_near, c->wg_scratch[0], s_near));
+        { ScopedTiming tm(c, kWgSelfNear, s_near); DRC_TRY(launch_wgrad(os, c->Nc, D, dW->self_near, c->wg_scratch[0], s_near)); }
     }
     DRC_HIP(hipEventRecord(c->ev_near, s_near));
 
@@ -260,25 +335,25 @@ int heteroconv_bwd(dr_heteroconv* c, const float* dY_cell, const float* dY_net, 
     {
         GemmOperand seg[1] = {};
         seg[0].dense = dY_net; seg[0].W = W->neigh_pins; seg[0].transpose_w = 1;
-        DRC_TRY(launch_gemm(seg, 1, c->Nn, D, kEpiStore, c->dH[1], nullptr, nullptr, 0, nullptr, s_pins));
+        { ScopedTiming tm(c, kDhPins, s_pins); DRC_TRY(launch_gemm(seg, 1, c->Nn, D, kEpiStore, c->dH[1], nullptr, nullptr, 0, nullptr, s_pins)); }
     }
     DRC_HIP(hipStreamWaitEvent(s_pins, c->ev_gnear, 0));
-    DRC_TRY(launch_spmm_bwd(&c->At[1], c->dH[1], S->idx_cell, D, c->k_cell, c->dXs_cell, 1, s_pins));
+    { ScopedTiming tm(c, kBwdPins, s_pins); DRC_TRY(launch_spmm_bwd(&c->At[1], c->dH[1], S->idx_cell, D, c->k_cell, c->dXs_cell, 1, s_pins)); }
     {
         GemmOperand seg[1] = {};
         seg[0].dense = dY_cell; seg[0].mask = S->mask; seg[0].mask_keep = 1;
         seg[0].W = W->self_near; seg[0].transpose_w = 1;
-        DRC_TRY(launch_gemm(seg, 1, c->Nc, D, kEpiSampleAdd, nullptr, nullptr, S->idx_cell, c->k_cell, c->dXs_cell,
-                            s_pins));
+        { ScopedTiming tm(c, kSelfNearSample, s_pins); DRC_TRY(launch_gemm(seg, 1, c->Nc, D, kEpiSampleAdd, nullptr, nullptr, S->idx_cell, c->k_cell, c->dXs_cell,
+                            s_pins)); }
     }
-    DRC_TRY(launch_scatter_compact(c->dXs_cell, S->idx_cell, c->Nc, D, c->k_cell, dX_cell, s_pins));
+    { ScopedTiming tm(c, kScatterCell, s_pins); DRC_TRY(launch_scatter_compact(c->dXs_cell, S->idx_cell, c->Nc, D, c->k_cell, dX_cell, s_pins)); }
     {
         WgradOperand op = {};
         op.a_dense = S->H_pins; op.b = dY_net;
-        DRC_TRY(launch_wgrad(op, c->Nn, D, dW->neigh_pins, c->wg_scratch[1], s_pins));
+        { ScopedTiming tm(c, kWgNeighPins, s_pins); DRC_TRY(launch_wgrad(op, c->Nn, D, dW->neigh_pins, c->wg_scratch[1], s_pins)); }
         WgradOperand os = {};
         os.a_cbsr_vals = S->vals_net; os.a_cbsr_idx = S->idx_net; os.k = c->k_net; os.b = dY_net;
-        DRC_TRY(launch_wgrad(os, c->Nn, D, dW->self_pins, c->wg_scratch[1], s_pins));
+        { ScopedTiming tm(c, kWgSelfPins, s_pins); DRC_TRY(launch_wgrad(os, c->Nn, D, dW->self_pins, c->wg_scratch[1], s_pins)); }
     }
     DRC_HIP(hipEventRecord(c->ev_pins, s_pins));
 
@@ -287,20 +362,20 @@ int heteroconv_bwd(dr_heteroconv* c, const float* dY_cell, const float* dY_net, 
         GemmOperand seg[1] = {};
         seg[0].dense = dY_cell; seg[0].mask = S->mask; seg[0].mask_keep = 0;
         seg[0].W = W->pinned; seg[0].transpose_w = 1;
-        DRC_TRY(launch_gemm(seg, 1, c->Nc, D, kEpiStore, c->dH[2], nullptr, nullptr, 0, nullptr, s_pinned));
+        { ScopedTiming tm(c, kDhPinned, s_pinned); DRC_TRY(launch_gemm(seg, 1, c->Nc, D, kEpiStore, c->dH[2], nullptr, nullptr, 0, nullptr, s_pinned)); }
     }
-    DRC_TRY(launch_spmm_bwd(&c->At[2], c->dH[2], S->idx_net, D, c->k_net, c->dXs_net, 0, s_pinned));
+    { ScopedTiming tm(c, kBwdPinned, s_pinned); DRC_TRY(launch_spmm_bwd(&c->At[2], c->dH[2], S->idx_net, D, c->k_net, c->dXs_net, 0, s_pinned)); }
     {
         GemmOperand seg[1] = {};
         seg[0].dense = dY_net; seg[0].W = W->self_pins; seg[0].transpose_w = 1;
-        DRC_TRY(launch_gemm(seg, 1, c->Nn, D, kEpiSampleAdd, nullptr, nullptr, S->idx_net, c->k_net, c->dXs_net,
-                            s_pinned));
+        { ScopedTiming tm(c, kSelfPinsSample, s_pinned); DRC_TRY(launch_gemm(seg, 1, c->Nn, D, kEpiSampleAdd, nullptr, nullptr, S->idx_net, c->k_net, c->dXs_net,
+                            s_pinned)); }
     }
-    DRC_TRY(launch_scatter_compact(c->dXs_net, S->idx_net, c->Nn, D, c->k_net, dX_net, s_pinned));
+    { ScopedTiming tm(c, kScatterNet, s_pinned); DRC_TRY(launch_scatter_compact(c->dXs_net, S->idx_net, c->Nn, D, c->k_net, dX_net, s_pinned)); }
     {
         WgradOperand op = {};
         op.a_dense = S->H_pinned; op.b = dY_cell; op.b_mask = S->mask; op.b_mask_keep = 0;
-        DRC_TRY(launch_wgrad(op, c->Nc, D, dW->pinned, c->wg_scratch[2], s_pinned));
+        { ScopedTiming tm(c, kWgPinned, s_pinned); DRC_TRY(launch_wgrad(op, c->Nc, D, dW->pinned, c->wg_scratch[2], s_pinned)); }
     }
     DRC_HIP(hipEventRecord(c->ev_pinned, s_pinned));
 
