@@ -1,101 +1,190 @@
 // DR-SpMM forward (paper Section 3.2 / Alg. 1) and backward (Section 3.3 / Alg. 2) for one relation.
 //
-// Work decomposition (both directions).  A workgroup owns a block of kRowsPerBlock consecutive CSR rows.
-//   * The wavefront is split into groups of 8 lanes; a group owns one row at a time and walks that row's
-//     edges in storage order, so 8 rows are in flight per wavefront (the wave64 counterpart of the paper's
-//     "partition the warp into parts, one neighbour each") and a row's sum has one fixed order: results
-//     are reproducible bit for bit.
-//   * Rows of the block are counting-sorted by degree in LDS first (integer LDS atomics), and the 8 rows
-//     a wavefront takes together are neighbours in that order: the groups of a wavefront run the same
-//     number of edge iterations (the paper's degree classes, resolved per block).
-//   * Rows with more than kLongRow edges (high-fanout nets) are not given to one group: the whole
-//     workgroup strides over their edges into per-group partial sums that are then added in a fixed order.
+// Work decomposition (both directions).  A workgroup is ONE wavefront and owns kRW consecutive CSR rows;
+// there are no workgroup barriers to wait at, and the hardware dispatcher balances the (uneven) blocks.
+//   * The wavefront is split into 8 groups of 8 lanes; a group owns one row at a time and walks that
+//     row's edges in storage order, so 8 rows are in flight per wavefront (the wave64 counterpart of the
+//     paper's "partition the warp into parts, one neighbour each") and every row sum has one fixed
+//     order: results are reproducible bit for bit.
+//   * The block's rows are ranked by degree and dealt to the groups in that order, boustrophedon, so the
+//     rows the groups hold at any time have (nearly) equal degree -- the paper's degree classes, resolved
+//     per block -- and the per-group totals come out balanced.
+//   * Rows with more than kSolo edges are not given to one group: all 8 groups stride over their edges
+//     into per-group partial sums that are then added in a fixed order (high-fanout nets, the tail of
+//     the power-law `near` degrees).
+//   * Edge records (source column, edge value) are staged into LDS in sorted-row order with independent
+//     coalesced loads.  A group then consumes its rows as ONE stream of records across row boundaries,
+//     so the gather pipeline never drains between rows (rows have only a handful of edges).
+//   * Gathers are issued in two ping-pong batches of several edges per group: while one batch is being
+//     accumulated the other is in flight, and no load in the loop is conditional (exhausted lanes gather
+//     a valid dummy row), which lets the compiler wait on exactly the older batch.
 //   * Workgroup ids are remapped so each XCD walks a contiguous range of row blocks: neighbouring rows of
 //     the spatially local `near` relation gather overlapping source rows, which then hit in that XCD's L2.
 //
 // Forward.  Lane t of a group loads pairs [t*k/8, (t+1)*k/8) of the gathered source row with vector
 // loads (one 128-byte line of values per source row at k = 32) and adds a*v into the group's private
 // LDS row buffer with plain read-modify-write: the pairs of one source row have distinct columns and
-// no other group touches the buffer, so no atomics are needed (ds_add_f32 is far slower than plain LDS
-// traffic on this chip).  The finished row goes to HBM in 128-byte segments.
+// no other group touches the buffer, so no atomics are needed (ds_add_f32 runs at about 1/40 of the
+// plain LDS rate on this chip).  A finished row goes to HBM in 128-byte segments.
 //
 // Backward.  Lane t of a group owns the compact outputs t, t+8, t+16, ... of its source row and keeps
 // them in registers; per edge it reads dH[destination, idx[slot]] directly (the interleaved slot
-// assignment keeps the 8 lanes of one load inside one 128-byte line of the dH row when k*4 = D).
+// assignment keeps the 8 lanes of one load inside one 128-byte line of the dH row when 4k = D).
 #include "dr_internal.h"
 
 namespace drc {
 
-constexpr int kLPE = 8;             // lanes per row group
-constexpr int kLongRow = 256;       // rows with more edges are processed by the whole workgroup
-constexpr int kRowsPerBlock = 256;
-constexpr int kBins = kLongRow + 1;
+constexpr int kLPE = 8;          // lanes per row group
+constexpr int kNG = kWave / kLPE;  // groups per wavefront
+constexpr int kRW = 32;          // rows per wavefront-workgroup
+constexpr int kSolo = 64;        // rows with more edges are walked by all 8 groups together
+constexpr int kCap = 512;        // edge records staged in LDS per pass (rows never straddle passes)
+constexpr int kStageIters = kCap / kWave;
+constexpr unsigned kValid = 0x80000000u, kLast = 0x40000000u, kRowMask = 0x0000ffffu;
 
-struct BlockPlan {
-    int* sRp;      // [kRowsPerBlock + 1] row pointers of the block
-    int* sOrder;   // [kRowsPerBlock] short rows, degree descending
-    int* sHist;    // [kBins + 1]
-    int* sLong;    // [kRowsPerBlock] long rows
-    int* sCnt;     // [4]: number of long rows
+struct WavePlan {
+    int* sRp;      // [kRW + 1] row pointers of the block
+    int* sOrder;   // [kRW]     slot -> local row; solo rows by degree, descending
+    int* sStart;   // [kRW + 1] slot -> offset of the row's records in sorted-row order
+    int2* sRec;    // [kCap]    staged (column, value bits) records
+    int n_solo;
+    unsigned long long coop_mask, zero_mask;
 };
 
-__host__ __device__ constexpr int plan_ints() { return (kRowsPerBlock + 1) + kRowsPerBlock + (kBins + 1) + kRowsPerBlock + 4; }
+__host__ __device__ constexpr int plan_ints() { return (kRW + 1) + kRW + (kRW + 1) + 2 /*pad*/ + 2 * kCap; }
 
-__device__ __forceinline__ BlockPlan carve_plan(int* base) {
-    BlockPlan p;
+__device__ __forceinline__ void lds_fence() { __syncthreads(); }   // one wavefront per workgroup: orders LDS traffic
+
+__device__ __forceinline__ WavePlan make_plan(int* base, const int32_t* __restrict__ rowptr, int r0, int nr) {
+    WavePlan p;
     p.sRp = base;
-    p.sOrder = p.sRp + (kRowsPerBlock + 1);
-    p.sHist = p.sOrder + kRowsPerBlock;
-    p.sLong = p.sHist + (kBins + 1);
-    p.sCnt = p.sLong + kRowsPerBlock;
+    p.sOrder = p.sRp + (kRW + 1);
+    p.sStart = p.sOrder + kRW;
+    int* r = p.sStart + (kRW + 1);
+    r += (reinterpret_cast<uintptr_t>(r) & 7) ? 1 : 0;   // 8-byte alignment for int2
+    p.sRec = reinterpret_cast<int2*>(r);
+
+    const int lane = threadIdx.x;
+    const int rp_lo = rowptr[r0 + min(lane, nr)];
+    const int rp_hi = rowptr[r0 + min(lane + 1, nr)];
+    if (lane <= nr) p.sRp[lane] = rp_lo;
+    const int deg = (lane < nr) ? (rp_hi - rp_lo) : -1;
+    const bool solo = deg >= 1 && deg <= kSolo;
+    p.coop_mask = __ballot(deg > kSolo);
+    p.zero_mask = __ballot(deg == 0);
+    p.n_solo = __popcll(__ballot(solo));
+    // rank of every solo row among the solo rows: degree descending, row ascending
+    const int key = solo ? deg : -1;
+    int rank = 0;
+#pragma unroll
+    for (int j = 0; j < kRW; ++j) {
+        const int kj = __shfl(key, j, kWave);
+        rank += (kj > key || (kj == key && j < lane)) ? 1 : 0;
+    }
+    if (solo) {
+        p.sOrder[rank] = lane;
+        p.sStart[rank] = deg;
+    }
+    lds_fence();
+    const int x = (lane < p.n_solo) ? p.sStart[lane] : 0;
+    int incl = x;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const int y = __shfl_up(incl, d, kWave);
+        if (lane >= d) incl += y;
+    }
+    lds_fence();
+    if (lane <= p.n_solo) p.sStart[lane] = incl - x;     // exclusive prefix; entry n_solo = total
+    lds_fence();
     return p;
 }
 
-// Loads the block's row pointers and sorts its rows by degree (descending).  Returns the number of
-// short rows; p.sCnt[0] holds the number of long rows.  Ends with a barrier.
-__device__ __forceinline__ int plan_block(const BlockPlan& p, const int32_t* __restrict__ rowptr, int r0, int nr) {
-    const int tid = threadIdx.x, bd = blockDim.x;
-    for (int i = tid; i <= nr; i += bd) p.sRp[i] = rowptr[r0 + i];
-    for (int i = tid; i <= kBins; i += bd) p.sHist[i] = 0;
-    if (tid < 4) p.sCnt[tid] = 0;
-    __syncthreads();
-    for (int i = tid; i < nr; i += bd) {
-        int deg = p.sRp[i + 1] - p.sRp[i];
-        if (deg > kLongRow) p.sLong[atomicAdd(&p.sCnt[0], 1)] = i;
-        else atomicAdd(&p.sHist[kLongRow - deg], 1);        // bin 0 = largest degree
-    }
-    __syncthreads();
-    if (tid < kWave) {                                       // exclusive scan of the bins by one wavefront
-        constexpr int kPer = (kBins + kWave - 1) / kWave;
-        int c[kPer], s = 0;
-#pragma unroll
-        for (int q = 0; q < kPer; ++q) {
-            int b = tid * kPer + q;
-            c[q] = (b < kBins) ? p.sHist[b] : 0;
-            s += c[q];
-        }
-        int incl = s;
-#pragma unroll
-        for (int d = 1; d < kWave; d <<= 1) {
-            int y = __shfl_up(incl, d, kWave);
-            if (tid >= d) incl += y;
-        }
-        int excl = incl - s;
-#pragma unroll
-        for (int q = 0; q < kPer; ++q) {
-            int b = tid * kPer + q;
-            if (b < kBins) p.sHist[b] = excl;
-            excl += c[q];
-        }
-    }
-    __syncthreads();
-    for (int i = tid; i < nr; i += bd) {
-        int deg = p.sRp[i + 1] - p.sRp[i];
-        if (deg <= kLongRow) p.sOrder[atomicAdd(&p.sHist[kLongRow - deg], 1)] = i;
-    }
-    __syncthreads();
-    return nr - p.sCnt[0];
+// End slot of the pass that starts at slot sa: as many whole solo rows as fit kCap records (at least one).
+__device__ __forceinline__ int pass_end(const WavePlan& p, int sa) {
+    const int lane = threadIdx.x;
+    const int base = p.sStart[sa];
+    const bool fits = lane > sa && lane <= p.n_solo && p.sStart[lane] - base <= kCap;
+    return sa + __popcll(__ballot(fits));
 }
+
+// Stages the records of solo slots [sa, sb) into sRec, laid out in slot order.  Every lane issues its
+// loads (at most kStageIters, all independent) before the first one is consumed.
+__device__ __forceinline__ void stage_solo(const WavePlan& p, const int32_t* __restrict__ colidx,
+                                           const float* __restrict__ avals, int sa, int sb) {
+    const int lane = threadIdx.x;
+    const int base = p.sStart[sa];
+    const int total = p.sStart[sb] - base;
+    int2 r[kStageIters];
+#pragma unroll
+    for (int j = 0; j < kStageIters; ++j) {
+        const int d = lane + kWave * j;
+        const int dd = (d < total) ? d : 0;
+        int lo = sa, hi = sb;                  // sStart[lo] - base <= dd < sStart[hi] - base
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (p.sStart[mid] - base <= dd) lo = mid; else hi = mid;
+        }
+        const int e = p.sRp[p.sOrder[lo]] + dd - (p.sStart[lo] - base);
+        r[j] = make_int2(colidx[e], __float_as_int(avals[e]));
+    }
+#pragma unroll
+    for (int j = 0; j < kStageIters; ++j) {
+        const int d = lane + kWave * j;
+        if (d < total) p.sRec[d] = r[j];
+    }
+}
+
+// Stages records [c0, c0 + n) of one long row (n <= kCap, n >= 1).
+__device__ __forceinline__ void stage_chunk(const WavePlan& p, const int32_t* __restrict__ colidx,
+                                            const float* __restrict__ avals, int c0, int n) {
+    const int lane = threadIdx.x;
+    int2 r[kStageIters];
+#pragma unroll
+    for (int j = 0; j < kStageIters; ++j) {
+        const int d = lane + kWave * j;
+        const int e = c0 + ((d < n) ? d : 0);
+        r[j] = make_int2(colidx[e], __float_as_int(avals[e]));
+    }
+#pragma unroll
+    for (int j = 0; j < kStageIters; ++j) {
+        const int d = lane + kWave * j;
+        if (d < n) p.sRec[d] = r[j];
+    }
+}
+
+// Record stream of one group.  Solo mode: the group's rows of the pass, boustrophedon over the slots
+// (sa + g, sa + 15 - g, sa + 16 + g, ...), one record after the other across row boundaries.
+// Strided mode (long rows): records g, g + 8, ... of the staged chunk, no row boundaries.
+struct Stream {
+    int round, cur, row_end, row, done;
+    __device__ __forceinline__ void next_row(const WavePlan& p, int g, int sa, int npass, int base) {
+        ++round;
+        const int li = round * kNG + ((round & 1) ? (kNG - 1 - g) : g);
+        if (li < npass) {
+            const int s = sa + li;
+            cur = p.sStart[s] - base;
+            row_end = p.sStart[s + 1] - base;
+            row = p.sOrder[s];
+        } else {
+            done = 1;
+        }
+    }
+    // returns the meta word of the record just taken and advances
+    template <bool STRIDED>
+    __device__ __forceinline__ unsigned advance(const WavePlan& p, int g, int sa, int npass, int base) {
+        unsigned m = kValid | (unsigned)row;
+        if constexpr (STRIDED) {
+            cur += kNG;
+            if (cur >= row_end) done = 1;
+        } else {
+            if (++cur == row_end) {
+                m |= kLast;
+                next_row(p, g, sa, npass, base);
+            }
+        }
+        return m;
+    }
+};
 
 // ---------------------------------------------------------------------------------------------------
 // forward
@@ -133,122 +222,158 @@ template <int KPL> struct Pairs {        // KPL consecutive (value, column) pair
     }
 };
 
-// One group walks edges e, e+stride, ... < e_end of its row, software-pipelined three deep: edge record
-// (column, value) -> gather of the source row's pairs -> LDS accumulation.  All 64 lanes stay in the
-// loop until every group of the wavefront is done.
-template <int KPL>
-__device__ __forceinline__ void fwd_walk(const int32_t* __restrict__ colidx, const float* __restrict__ avals,
-                                         const float* __restrict__ xs_vals, const uint16_t* __restrict__ xs_idx,
-                                         int e, int e_end, int stride, int k, int t, float* buf) {
-    if constexpr (KPL > 0) {
-        bool valid1 = e < e_end, valid2 = false;
-        int col1 = 0;
-        float a1 = 0.f, a2 = 0.f;
-        if (valid1) { col1 = colidx[e]; a1 = avals[e]; }
-        e += stride;
-        Pairs<KPL> p2;
-        while (__any(valid1 || valid2)) {
-            Pairs<KPL> pn;
-            const bool validn = valid1;
-            const float an = a1;
-            if (valid1) pn.load(xs_vals, xs_idx, (uint32_t)col1 * (uint32_t)k + (uint32_t)(t * KPL));
-            valid1 = e < e_end;
-            if (valid1) { col1 = colidx[e]; a1 = avals[e]; }
-            e += stride;
-            if (valid2) p2.accumulate(buf, a2);
-            if (validn) p2 = pn;
-            a2 = an;
-            valid2 = validn;
+__device__ __forceinline__ void flush_row(float* __restrict__ out, float* buf, int D, int t, int vec_store) {
+    if (vec_store) {
+        for (int c = t * 4; c < D; c += kLPE * 4) {
+            float4 v = *reinterpret_cast<const float4*>(buf + c);
+            *reinterpret_cast<float4*>(out + c) = v;
+            *reinterpret_cast<float4*>(buf + c) = make_float4(0.f, 0.f, 0.f, 0.f);
         }
     } else {
-        // generic k: lane t takes pairs t, t+8, ... with scalar loads
-        for (; __any(e < e_end); e += stride) {
-            if (e < e_end) {
-                const uint32_t base = (uint32_t)colidx[e] * (uint32_t)k;
-                const float a = avals[e];
-                for (int s = t; s < k; s += kLPE) {
-                    const int c = xs_idx[base + s];
-                    buf[c] = fmaf(a, xs_vals[base + s], buf[c]);
+        for (int c = t; c < D; c += kLPE) {
+            out[c] = buf[c];
+            buf[c] = 0.0f;
+        }
+    }
+}
+
+template <int KPL, int EPI> struct FwdBatch {   // EPI consecutive stream records of one group, gathered
+    Pairs<KPL> p[EPI];
+    float a[EPI];
+    unsigned meta[EPI];
+};
+
+template <int KPL, int EPI, bool STRIDED>
+__device__ __forceinline__ void fwd_issue(FwdBatch<KPL, EPI>& b, Stream& st, const WavePlan& plan,
+                                          const float* __restrict__ xs_vals, const uint16_t* __restrict__ xs_idx,
+                                          int k, int t, int g, int sa, int npass, int base) {
+#pragma unroll
+    for (int q = 0; q < EPI; ++q) {
+        const bool valid = !st.done;
+        const int2 rec = plan.sRec[valid ? st.cur : 0];
+        const uint32_t col = valid ? (uint32_t)rec.x : 0u;   // exhausted lanes gather source row 0
+        b.a[q] = __int_as_float(rec.y);
+        b.p[q].load(xs_vals, xs_idx, col * (uint32_t)k + (uint32_t)(t * KPL));
+        b.meta[q] = valid ? st.template advance<STRIDED>(plan, g, sa, npass, base) : 0u;
+    }
+}
+
+template <int KPL, int EPI>
+__device__ __forceinline__ void fwd_consume(const FwdBatch<KPL, EPI>& b, float* buf, float* __restrict__ Hblk,
+                                            int D, int t, int vec_store) {
+#pragma unroll
+    for (int q = 0; q < EPI; ++q) {
+        if (b.meta[q] & kValid) {
+            b.p[q].accumulate(buf, b.a[q]);
+            if (b.meta[q] & kLast) flush_row(Hblk + (size_t)(b.meta[q] & kRowMask) * D, buf, D, t, vec_store);
+        }
+    }
+}
+
+template <int KPL, int EPI, bool STRIDED>
+__device__ __forceinline__ void fwd_run(Stream& st, const WavePlan& plan, const float* __restrict__ xs_vals,
+                                        const uint16_t* __restrict__ xs_idx, float* buf, float* __restrict__ Hblk,
+                                        int D, int k, int t, int g, int sa, int npass, int base, int vec_store) {
+    if constexpr (KPL > 0) {
+        FwdBatch<KPL, EPI> A, B;
+        fwd_issue<KPL, EPI, STRIDED>(A, st, plan, xs_vals, xs_idx, k, t, g, sa, npass, base);
+        for (;;) {
+            fwd_issue<KPL, EPI, STRIDED>(B, st, plan, xs_vals, xs_idx, k, t, g, sa, npass, base);
+            fwd_consume(A, buf, Hblk, D, t, vec_store);
+            if (!__any(B.meta[0] & kValid)) break;
+            fwd_issue<KPL, EPI, STRIDED>(A, st, plan, xs_vals, xs_idx, k, t, g, sa, npass, base);
+            fwd_consume(B, buf, Hblk, D, t, vec_store);
+            if (!__any(A.meta[0] & kValid)) break;
+        }
+    } else {
+        // generic k: one record at a time, lane t takes pairs t, t+8, ... with scalar loads
+        while (__any(!st.done)) {
+            if (!st.done) {
+                const int2 rec = plan.sRec[st.cur];
+                const uint32_t rb = (uint32_t)rec.x * (uint32_t)k;
+                const float a = __int_as_float(rec.y);
+                for (int q = t; q < k; q += kLPE) {
+                    const int c = xs_idx[rb + q];
+                    buf[c] = fmaf(a, xs_vals[rb + q], buf[c]);
                 }
+                const unsigned m = st.template advance<STRIDED>(plan, g, sa, npass, base);
+                if (m & kLast) flush_row(Hblk + (size_t)(m & kRowMask) * D, buf, D, t, vec_store);
             }
         }
     }
 }
 
-template <int KPL>
-__global__ __launch_bounds__(256) void spmm_fwd_kernel(
+template <int KPL, int EPI>
+__global__ __launch_bounds__(kWave) void spmm_fwd_kernel(
     const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colidx, const float* __restrict__ avals,
     const float* __restrict__ xs_vals, const uint16_t* __restrict__ xs_idx, float* __restrict__ H,
     int M, int D, int k, int n_tiles, int per_xcd, int vec_store) {
     extern __shared__ float4 smem4[];
-    float* rowbuf = reinterpret_cast<float*>(smem4);                 // [groups][D], 16-byte aligned
-    const int groups = blockDim.x / kLPE;
-    BlockPlan plan = carve_plan(reinterpret_cast<int*>(rowbuf + groups * D));
-
+    float* rowbuf = reinterpret_cast<float*>(smem4);                 // [kNG][D], 16-byte aligned
     const int tile_id = xcd_contiguous_tile(blockIdx.x, per_xcd);
     if (tile_id >= n_tiles) return;
-    const int r0 = tile_id * kRowsPerBlock;
-    const int nr = min(kRowsPerBlock, M - r0);
-    const int tid = threadIdx.x;
-    const int g = tid / kLPE, t = tid % kLPE;
+    const int r0 = tile_id * kRW;
+    const int nr = min(kRW, M - r0);
+    const int lane = threadIdx.x;
+    const int g = lane / kLPE, t = lane % kLPE;
     float* buf = rowbuf + g * D;
+    float* Hblk = H + (size_t)r0 * D;
 
-    for (int i = tid; i < groups * D; i += blockDim.x) rowbuf[i] = 0.0f;
-    const int n_short = plan_block(plan, rowptr, r0, nr);   // barriers inside
-    const int n_long = plan.sCnt[0];
+    for (int i = lane; i < kNG * D; i += kWave) rowbuf[i] = 0.0f;
+    WavePlan plan = make_plan(reinterpret_cast<int*>(rowbuf + kNG * D), rowptr, r0, nr);
 
-    // ---- rows with very many edges: the whole workgroup, partial sums per group ----
-    for (int li = 0; li < n_long; ++li) {
-        const int row = plan.sLong[li];
-        fwd_walk<KPL>(colidx, avals, xs_vals, xs_idx, plan.sRp[row] + g, plan.sRp[row + 1], groups, k, t, buf);
-        __syncthreads();
-        float* out = H + (size_t)(r0 + row) * D;
-        for (int c = tid; c < D; c += blockDim.x) {
+    // ---- rows without edges: zeros ----
+    for (unsigned long long m = plan.zero_mask; m; m &= m - 1) {
+        float* out = Hblk + (size_t)(__ffsll((long long)m) - 1) * D;
+        for (int c = lane; c < D; c += kWave) out[c] = 0.0f;
+    }
+
+    // ---- long rows: all groups stride over the row, partial sums added in a fixed order ----
+    for (unsigned long long m = plan.coop_mask; m; m &= m - 1) {
+        const int row = __ffsll((long long)m) - 1;
+        const int e0 = plan.sRp[row], e1 = plan.sRp[row + 1];
+        for (int c0 = e0; c0 < e1; c0 += kCap) {
+            const int n = min(kCap, e1 - c0);
+            lds_fence();
+            stage_chunk(plan, colidx, avals, c0, n);
+            lds_fence();
+            Stream st{0, g, n, row, g >= n ? 1 : 0};
+            fwd_run<KPL, EPI, true>(st, plan, xs_vals, xs_idx, buf, Hblk, D, k, t, g, 0, 0, 0, vec_store);
+        }
+        lds_fence();
+        float* out = Hblk + (size_t)row * D;
+        for (int c = lane; c < D; c += kWave) {
             float s = 0.0f;
-            for (int q = 0; q < groups; ++q) {
+#pragma unroll
+            for (int q = 0; q < kNG; ++q) {
                 s += rowbuf[q * D + c];
                 rowbuf[q * D + c] = 0.0f;
             }
             out[c] = s;
         }
-        __syncthreads();
+        lds_fence();
     }
 
-    // ---- all other rows: one group per row, 8 rows of similar degree per wavefront ----
-    for (int slot = g; slot < n_short + (kWave / kLPE - 1); slot += groups) {
-        const bool has = slot < n_short;
-        if (!__any(has)) break;
-        const int row = has ? plan.sOrder[slot] : 0;
-        const int e0 = has ? plan.sRp[row] : 0;
-        const int e1 = has ? plan.sRp[row + 1] : 0;
-        fwd_walk<KPL>(colidx, avals, xs_vals, xs_idx, e0, e1, 1, k, t, buf);
-        if (has) {
-            float* out = H + (size_t)(r0 + row) * D;
-            if (vec_store) {
-                for (int c = t * 4; c < D; c += kLPE * 4) {
-                    float4 v = *reinterpret_cast<const float4*>(buf + c);
-                    *reinterpret_cast<float4*>(out + c) = v;
-                    *reinterpret_cast<float4*>(buf + c) = make_float4(0.f, 0.f, 0.f, 0.f);
-                }
-            } else {
-                for (int c = t; c < D; c += kLPE) {
-                    out[c] = buf[c];
-                    buf[c] = 0.0f;
-                }
-            }
-        }
+    // ---- all other rows, in passes of at most kCap staged records ----
+    for (int sa = 0; sa < plan.n_solo;) {
+        const int sb = pass_end(plan, sa);
+        lds_fence();
+        stage_solo(plan, colidx, avals, sa, sb);
+        lds_fence();
+        Stream st{-1, 0, 0, 0, 0};
+        st.next_row(plan, g, sa, sb - sa, plan.sStart[sa]);
+        fwd_run<KPL, EPI, false>(st, plan, xs_vals, xs_idx, buf, Hblk, D, k, t, g, sa, sb - sa, plan.sStart[sa],
+                                 vec_store);
+        sa = sb;
     }
 }
-
-static int spmm_block_threads(int D) { return D <= 256 ? 256 : (D <= 512 ? 128 : 64); }
 
 int launch_spmm_fwd(const dr_csr* A, const float* xs_vals, const uint16_t* xs_idx, int D, int k, float* H,
                     hipStream_t s) {
     const int M = (int)A->n_rows;
-    const int n_tiles = (M + kRowsPerBlock - 1) / kRowsPerBlock;
+    if (A->nnz == 0) return launch_fill_u32(reinterpret_cast<uint32_t*>(H), (size_t)M * D, 0u, s);
+    const int n_tiles = (M + kRW - 1) / kRW;
     const int per_xcd = (n_tiles + kNumXcd - 1) / kNumXcd;
-    const int threads = spmm_block_threads(D);
-    const int groups = threads / kLPE;
     const int vec_store = (D % 4 == 0 && aligned(H, 16)) ? 1 : 0;
     int kpl = 0;
     if (k % kLPE == 0) {
@@ -257,18 +382,18 @@ int launch_spmm_fwd(const dr_csr* A, const float* xs_vals, const uint16_t* xs_id
         else if (q == 2 && aligned(xs_vals, 8) && aligned(xs_idx, 4)) kpl = 2;
         else if ((q == 4 || q == 8 || q == 16) && aligned(xs_vals, 16) && aligned(xs_idx, 8)) kpl = q;
     }
-    const size_t lds = sizeof(float) * (size_t)groups * D + sizeof(int) * (size_t)plan_ints();
-    dim3 grid((unsigned)(per_xcd * kNumXcd)), block((unsigned)threads);
-#define DRC_LAUNCH_FWD(V)                                                                                      \
-    hipLaunchKernelGGL(spmm_fwd_kernel<V>, grid, block, lds, s, A->rowptr, A->colidx, A->vals, xs_vals, xs_idx, \
+    const size_t lds = sizeof(float) * (size_t)kNG * D + sizeof(int) * (size_t)plan_ints();
+    dim3 grid((unsigned)(per_xcd * kNumXcd)), block(kWave);
+#define DRC_LAUNCH_FWD(V, E)                                                                                       \
+    hipLaunchKernelGGL((spmm_fwd_kernel<V, E>), grid, block, lds, s, A->rowptr, A->colidx, A->vals, xs_vals, xs_idx, \
                        H, M, D, k, n_tiles, per_xcd, vec_store)
     switch (kpl) {
-        case 1: DRC_LAUNCH_FWD(1); break;
-        case 2: DRC_LAUNCH_FWD(2); break;
-        case 4: DRC_LAUNCH_FWD(4); break;
-        case 8: DRC_LAUNCH_FWD(8); break;
-        case 16: DRC_LAUNCH_FWD(16); break;
-        default: DRC_LAUNCH_FWD(0); break;
+        case 1: DRC_LAUNCH_FWD(1, 4); break;
+        case 2: DRC_LAUNCH_FWD(2, 4); break;
+        case 4: DRC_LAUNCH_FWD(4, 4); break;
+        case 8: DRC_LAUNCH_FWD(8, 2); break;
+        case 16: DRC_LAUNCH_FWD(16, 1); break;
+        default: DRC_LAUNCH_FWD(0, 1); break;
     }
 #undef DRC_LAUNCH_FWD
     DRC_HIP(hipGetLastError());
@@ -278,120 +403,166 @@ int launch_spmm_fwd(const dr_csr* A, const float* xs_vals, const uint16_t* xs_id
 // ---------------------------------------------------------------------------------------------------
 // backward: rows are sources j (rows of A^T); lane t of the row's group owns compact slots
 // s0 + t, s0 + t + 8, ... (KPL of them) in registers.  k larger than 8*KPL is covered by re-walking the
-// row for the next window of slots.
+// block for the next window of slots.
 // ---------------------------------------------------------------------------------------------------
 
+template <int KPL, int EPI> struct BwdBatch {
+    float v[EPI][KPL];
+    float a[EPI];
+    unsigned meta[EPI];
+};
+
 template <int KPL>
-__device__ __forceinline__ void bwd_walk(const int32_t* __restrict__ colidx, const float* __restrict__ avals,
-                                         const float* __restrict__ dH, int D, int e, int e_end, int stride,
-                                         const int (&ci)[KPL], float (&acc)[KPL]) {
-    bool valid1 = e < e_end, valid2 = false;
-    int col1 = 0;
-    float a1 = 0.f, a2 = 0.f;
-    if (valid1) { col1 = colidx[e]; a1 = avals[e]; }
-    e += stride;
-    float v2[KPL];
+__device__ __forceinline__ void load_ci(int (&ci)[KPL], const uint16_t* sIdx, int row, int t) {
 #pragma unroll
-    for (int u = 0; u < KPL; ++u) v2[u] = 0.f;
-    while (__any(valid1 || valid2)) {
-        float vn[KPL];
-        const bool validn = valid1;
-        const float an = a1;
-        if (valid1) {
-            const float* rowp = dH + (size_t)(uint32_t)col1 * (uint32_t)D;
+    for (int u = 0; u < KPL; ++u) ci[u] = sIdx[row * (kLPE * KPL) + t + kLPE * u];
+}
+
+template <int KPL, int EPI, bool STRIDED>
+__device__ __forceinline__ void bwd_issue(BwdBatch<KPL, EPI>& b, Stream& st, int (&ci)[KPL], const WavePlan& plan,
+                                          const uint16_t* sIdx, const float* __restrict__ dH, int D, int t, int g,
+                                          int sa, int npass, int base) {
 #pragma unroll
-            for (int u = 0; u < KPL; ++u) vn[u] = rowp[ci[u]];
+    for (int q = 0; q < EPI; ++q) {
+        const bool valid = !st.done;
+        const int2 rec = plan.sRec[valid ? st.cur : 0];
+        const uint32_t col = valid ? (uint32_t)rec.x : 0u;
+        b.a[q] = __int_as_float(rec.y);
+        const float* rowp = dH + (size_t)col * (uint32_t)D;
+#pragma unroll
+        for (int u = 0; u < KPL; ++u) b.v[q][u] = rowp[ci[u]];
+        unsigned m = 0;
+        if (valid) {
+            m = st.template advance<STRIDED>(plan, g, sa, npass, base);
+            if (!STRIDED && (m & kLast) && !st.done) load_ci<KPL>(ci, sIdx, st.row, t);
         }
-        valid1 = e < e_end;
-        if (valid1) { col1 = colidx[e]; a1 = avals[e]; }
-        e += stride;
-        if (valid2) {
-#pragma unroll
-            for (int u = 0; u < KPL; ++u) acc[u] = fmaf(a2, v2[u], acc[u]);
-        }
-        if (validn) {
-#pragma unroll
-            for (int u = 0; u < KPL; ++u) v2[u] = vn[u];
-        }
-        a2 = an;
-        valid2 = validn;
+        b.meta[q] = m;
     }
 }
 
-template <int KPL>
-__global__ __launch_bounds__(256) void spmm_bwd_kernel(
-    const int32_t* __restrict__ t_rowptr, const int32_t* __restrict__ t_colidx, const float* __restrict__ t_vals,
-    const float* __restrict__ dH, const uint16_t* __restrict__ xs_idx, float* __restrict__ dXs,
-    int N, int D, int k, int n_tiles, int per_xcd, int accumulate) {
-    extern __shared__ float4 smem4[];
-    constexpr int kWin = kLPE * KPL;                                   // compact slots per pass
-    constexpr int kGroups = 256 / kLPE;
-    float* part = reinterpret_cast<float*>(smem4);                     // [kGroups][kWin] long-row partials
-    BlockPlan plan = carve_plan(reinterpret_cast<int*>(part + kGroups * kWin));
-
-    const int tile_id = xcd_contiguous_tile(blockIdx.x, per_xcd);
-    if (tile_id >= n_tiles) return;
-    const int r0 = tile_id * kRowsPerBlock;
-    const int nr = min(kRowsPerBlock, N - r0);
-    const int tid = threadIdx.x;
-    const int g = tid / kLPE, t = tid % kLPE;
-
-    const int n_short = plan_block(plan, t_rowptr, r0, nr);
-    const int n_long = plan.sCnt[0];
-
-    for (int s0 = 0; s0 < k; s0 += kWin) {
-        // ---- long rows ----
-        for (int li = 0; li < n_long; ++li) {
-            const int row = plan.sLong[li];
-            const uint16_t* ridx = xs_idx + (size_t)(r0 + row) * k;
-            int ci[KPL];
-            float acc[KPL];
+template <int KPL, int EPI>
+__device__ __forceinline__ void bwd_consume(const BwdBatch<KPL, EPI>& b, float (&acc)[KPL], float* __restrict__ Gblk,
+                                            int k, int s0, int t, int accumulate) {
 #pragma unroll
-            for (int u = 0; u < KPL; ++u) {
-                const int slot = s0 + t + kLPE * u;
-                ci[u] = (slot < k) ? ridx[slot] : 0;
-                acc[u] = 0.f;
-            }
-            bwd_walk<KPL>(t_colidx, t_vals, dH, D, plan.sRp[row] + g, plan.sRp[row + 1], kGroups, ci, acc);
+    for (int q = 0; q < EPI; ++q) {
+        if (b.meta[q] & kValid) {
 #pragma unroll
-            for (int u = 0; u < KPL; ++u) part[g * kWin + t + kLPE * u] = acc[u];
-            __syncthreads();
-            for (int w = tid; w < kWin; w += 256) {
-                const int slot = s0 + w;
-                if (slot < k) {
-                    float s = 0.f;
-                    for (int q = 0; q < kGroups; ++q) s += part[q * kWin + w];
-                    float* o = dXs + (size_t)(r0 + row) * k + slot;
-                    *o = accumulate ? (*o + s) : s;
-                }
-            }
-            __syncthreads();
-        }
-        // ---- short rows ----
-        for (int slot_r = g; slot_r < n_short + (kWave / kLPE - 1); slot_r += kGroups) {
-            const bool has = slot_r < n_short;
-            if (!__any(has)) break;
-            const int row = has ? plan.sOrder[slot_r] : 0;
-            const int e0 = has ? plan.sRp[row] : 0;
-            const int e1 = has ? plan.sRp[row + 1] : 0;
-            const uint16_t* ridx = xs_idx + (size_t)(r0 + row) * k;
-            int ci[KPL];
-            float acc[KPL];
-#pragma unroll
-            for (int u = 0; u < KPL; ++u) {
-                const int slot = s0 + t + kLPE * u;
-                ci[u] = (has && slot < k) ? ridx[slot] : 0;
-                acc[u] = 0.f;
-            }
-            bwd_walk<KPL>(t_colidx, t_vals, dH, D, e0, e1, 1, ci, acc);
-            if (has) {
-                float* o = dXs + (size_t)(r0 + row) * k;
+            for (int u = 0; u < KPL; ++u) acc[u] = fmaf(b.a[q], b.v[q][u], acc[u]);
+            if (b.meta[q] & kLast) {
+                float* o = Gblk + (size_t)(b.meta[q] & kRowMask) * k;
 #pragma unroll
                 for (int u = 0; u < KPL; ++u) {
                     const int slot = s0 + t + kLPE * u;
                     if (slot < k) o[slot] = accumulate ? (o[slot] + acc[u]) : acc[u];
+                    acc[u] = 0.f;
                 }
             }
+        }
+    }
+}
+
+template <int KPL, int EPI, bool STRIDED>
+__device__ __forceinline__ void bwd_run(Stream& st, int (&ci)[KPL], float (&acc)[KPL], const WavePlan& plan,
+                                        const uint16_t* sIdx, const float* __restrict__ dH, float* __restrict__ Gblk,
+                                        int D, int k, int s0, int t, int g, int sa, int npass, int base,
+                                        int accumulate) {
+    BwdBatch<KPL, EPI> A, B;
+    bwd_issue<KPL, EPI, STRIDED>(A, st, ci, plan, sIdx, dH, D, t, g, sa, npass, base);
+    for (;;) {
+        bwd_issue<KPL, EPI, STRIDED>(B, st, ci, plan, sIdx, dH, D, t, g, sa, npass, base);
+        bwd_consume(A, acc, Gblk, k, s0, t, accumulate);
+        if (!__any(B.meta[0] & kValid)) break;
+        bwd_issue<KPL, EPI, STRIDED>(A, st, ci, plan, sIdx, dH, D, t, g, sa, npass, base);
+        bwd_consume(B, acc, Gblk, k, s0, t, accumulate);
+        if (!__any(A.meta[0] & kValid)) break;
+    }
+}
+
+template <int KPL, int EPI>
+__global__ __launch_bounds__(kWave) void spmm_bwd_kernel(
+    const int32_t* __restrict__ t_rowptr, const int32_t* __restrict__ t_colidx, const float* __restrict__ t_vals,
+    const float* __restrict__ dH, const uint16_t* __restrict__ xs_idx, float* __restrict__ dXs,
+    int N, int D, int k, int n_tiles, int per_xcd, int accumulate) {
+    extern __shared__ float4 smem4[];
+    constexpr int kWin = kLPE * KPL;                                       // compact slots per pass over the block
+    float* part = reinterpret_cast<float*>(smem4);                         // [kNG][kWin] long-row partials
+    uint16_t* sIdx = reinterpret_cast<uint16_t*>(part + kNG * kWin);       // [kRW][kWin] saved columns of the window
+    const int tile_id = xcd_contiguous_tile(blockIdx.x, per_xcd);
+    if (tile_id >= n_tiles) return;
+    const int r0 = tile_id * kRW;
+    const int nr = min(kRW, N - r0);
+    const int lane = threadIdx.x;
+    const int g = lane / kLPE, t = lane % kLPE;
+    float* Gblk = dXs + (size_t)r0 * k;
+
+    WavePlan plan = make_plan(reinterpret_cast<int*>(sIdx + kRW * kWin), t_rowptr, r0, nr);
+
+    for (int s0 = 0; s0 < k; s0 += kWin) {
+        // saved columns of this window for every row of the block (0 beyond k)
+        lds_fence();
+        for (int i = lane; i < nr * kWin; i += kWave) {
+            const int row = i / kWin, w = i % kWin;
+            sIdx[i] = (s0 + w < k) ? xs_idx[(size_t)(r0 + row) * k + s0 + w] : (uint16_t)0;
+        }
+        lds_fence();
+
+        // ---- rows without edges ----
+        if (!accumulate) {
+            for (unsigned long long m = plan.zero_mask; m; m &= m - 1) {
+                float* o = Gblk + (size_t)(__ffsll((long long)m) - 1) * k;
+                for (int w = lane; w < kWin; w += kWave)
+                    if (s0 + w < k) o[s0 + w] = 0.0f;
+            }
+        }
+
+        // ---- long rows ----
+        for (unsigned long long m = plan.coop_mask; m; m &= m - 1) {
+            const int row = __ffsll((long long)m) - 1;
+            const int e0 = plan.sRp[row], e1 = plan.sRp[row + 1];
+            int ci[KPL];
+            float acc[KPL];
+            load_ci<KPL>(ci, sIdx, row, t);
+#pragma unroll
+            for (int u = 0; u < KPL; ++u) acc[u] = 0.f;
+            for (int c0 = e0; c0 < e1; c0 += kCap) {
+                const int n = min(kCap, e1 - c0);
+                lds_fence();
+                stage_chunk(plan, t_colidx, t_vals, c0, n);
+                lds_fence();
+                Stream st{0, g, n, row, g >= n ? 1 : 0};
+                bwd_run<KPL, EPI, true>(st, ci, acc, plan, sIdx, dH, Gblk, D, k, s0, t, g, 0, 0, 0, accumulate);
+            }
+#pragma unroll
+            for (int u = 0; u < KPL; ++u) part[g * kWin + t + kLPE * u] = acc[u];
+            lds_fence();
+            for (int w = lane; w < kWin; w += kWave) {
+                if (s0 + w < k) {
+                    float s = 0.f;
+#pragma unroll
+                    for (int q = 0; q < kNG; ++q) s += part[q * kWin + w];
+                    float* o = Gblk + (size_t)row * k + s0 + w;
+                    *o = accumulate ? (*o + s) : s;
+                }
+            }
+            lds_fence();
+        }
+
+        // ---- all other rows ----
+        for (int sa = 0; sa < plan.n_solo;) {
+            const int sb = pass_end(plan, sa);
+            lds_fence();
+            stage_solo(plan, t_colidx, t_vals, sa, sb);
+            lds_fence();
+            Stream st{-1, 0, 0, 0, 0};
+            st.next_row(plan, g, sa, sb - sa, plan.sStart[sa]);
+            int ci[KPL];
+            float acc[KPL];
+#pragma unroll
+            for (int u = 0; u < KPL; ++u) { ci[u] = 0; acc[u] = 0.f; }
+            if (!st.done) load_ci<KPL>(ci, sIdx, st.row, t);
+            bwd_run<KPL, EPI, false>(st, ci, acc, plan, sIdx, dH, Gblk, D, k, s0, t, g, sa, sb - sa, plan.sStart[sa],
+                                     accumulate);
+            sa = sb;
         }
     }
 }
@@ -399,22 +570,27 @@ __global__ __launch_bounds__(256) void spmm_bwd_kernel(
 int launch_spmm_bwd(const dr_csr* At, const float* dH, const uint16_t* xs_idx, int D, int k, float* dXs,
                     int accumulate, hipStream_t s) {
     const int N = (int)At->n_rows;
-    const int n_tiles = (N + kRowsPerBlock - 1) / kRowsPerBlock;
+    if (At->nnz == 0) {
+        if (accumulate) return DR_OK;
+        return launch_fill_u32(reinterpret_cast<uint32_t*>(dXs), (size_t)N * k, 0u, s);
+    }
+    const int n_tiles = (N + kRW - 1) / kRW;
     const int per_xcd = (n_tiles + kNumXcd - 1) / kNumXcd;
     int kpl = 8;
     if (k <= 8) kpl = 1;
     else if (k <= 16) kpl = 2;
     else if (k <= 32) kpl = 4;
-    dim3 grid((unsigned)(per_xcd * kNumXcd)), block(256);
-    const size_t lds = sizeof(float) * (size_t)(256 / kLPE) * (kLPE * kpl) + sizeof(int) * (size_t)plan_ints();
-#define DRC_LAUNCH_BWD(V)                                                                                       \
-    hipLaunchKernelGGL(spmm_bwd_kernel<V>, grid, block, lds, s, At->rowptr, At->colidx, At->vals, dH, xs_idx, dXs, \
+    dim3 grid((unsigned)(per_xcd * kNumXcd)), block(kWave);
+    const size_t lds = sizeof(float) * (size_t)kNG * (kLPE * kpl) + sizeof(uint16_t) * (size_t)kRW * (kLPE * kpl) +
+                       sizeof(int) * (size_t)plan_ints();
+#define DRC_LAUNCH_BWD(V, E)                                                                                         \
+    hipLaunchKernelGGL((spmm_bwd_kernel<V, E>), grid, block, lds, s, At->rowptr, At->colidx, At->vals, dH, xs_idx, dXs, \
                        N, D, k, n_tiles, per_xcd, accumulate ? 1 : 0)
     switch (kpl) {
-        case 1: DRC_LAUNCH_BWD(1); break;
-        case 2: DRC_LAUNCH_BWD(2); break;
-        case 4: DRC_LAUNCH_BWD(4); break;
-        default: DRC_LAUNCH_BWD(8); break;
+        case 1: DRC_LAUNCH_BWD(1, 4); break;
+        case 2: DRC_LAUNCH_BWD(2, 4); break;
+        case 4: DRC_LAUNCH_BWD(4, 4); break;
+        default: DRC_LAUNCH_BWD(8, 2); break;
     }
 #undef DRC_LAUNCH_BWD
     DRC_HIP(hipGetLastError());
