@@ -48,8 +48,8 @@ def kernel_models(Nc, Nn, E, D, kc, kn):
     m["dr_spmm_fwd.near"] = fwd(Nc, Nc, E["near"], kc)
     m["dr_spmm_fwd.pins"] = fwd(Nn, Nc, E["pins"], kc)
     m["dr_spmm_fwd.pinned"] = fwd(Nc, Nn, E["pinned"], kn)
-    m["proj.near"] = (6 * Nc * kc + 4 * Nc * D + 2 * W + 4 * Nc * D, 2 * Nc * D * (D + kc))
-    m["proj.pins"] = (6 * Nn * kn + 4 * Nn * D + 2 * W + 4 * Nn * D, 2 * Nn * D * (D + kn))
+    m["proj.near"] = (6 * Nc * kc + 4 * Nc * D + 2 * W + 4 * Nc * D, 2 * Nc * D * (D + D))
+    m["proj.pins"] = (6 * Nn * kn + 4 * Nn * D + 2 * W + 4 * Nn * D, 2 * Nn * D * (D + D))
     m["proj.pinned+merge"] = (4 * Nc * D + W + 8 * Nc * D + Nc * D, 2 * Nc * D * D)
     m["dproj.near"] = (5 * Nc * D + W + 4 * Nc * D, 2 * Nc * D * D)
     m["dproj.pins"] = (4 * Nn * D + W + 4 * Nn * D, 2 * Nn * D * D)
@@ -57,15 +57,14 @@ def kernel_models(Nc, Nn, E, D, kc, kn):
     m["dr_spmm_bwd.near"] = bwd(Nc, Nc, E["near"], kc)
     m["dr_spmm_bwd.pins"] = bwd(Nc, Nn, E["pins"], kc)
     m["dr_spmm_bwd.pinned"] = bwd(Nn, Nc, E["pinned"], kn)
-    m["dself.near(sampled)"] = (5 * Nc * D + W + 10 * Nc * kc, 2 * Nc * D * kc)
-    m["dself.pins(sampled)"] = (4 * Nn * D + W + 10 * Nn * kn, 2 * Nn * D * kn)
+    # self-term gradient sampled at the saved indices, added to the compact SpMM gradient, written as dense dX
+    m["dself.near+dX"] = (5 * Nc * D + W + 6 * Nc * kc + 4 * Nc * D, 2 * Nc * D * D)
+    m["dself.pins+dX"] = (4 * Nn * D + W + 6 * Nn * kn + 4 * Nn * D, 2 * Nn * D * D)
     m["wgrad.neigh_near"] = (4 * Nc * D + 5 * Nc * D + W, 2 * Nc * D * D)
-    m["wgrad.self_near"] = (6 * Nc * kc + 5 * Nc * D + W, 2 * Nc * D * kc)
+    m["wgrad.self_near"] = (6 * Nc * kc + 5 * Nc * D + W, 2 * Nc * D * D)
     m["wgrad.neigh_pins"] = (8 * Nn * D + W, 2 * Nn * D * D)
-    m["wgrad.self_pins"] = (6 * Nn * kn + 4 * Nn * D + W, 2 * Nn * D * kn)
+    m["wgrad.self_pins"] = (6 * Nn * kn + 4 * Nn * D + W, 2 * Nn * D * D)
     m["wgrad.pinned"] = (4 * Nc * D + 5 * Nc * D + W, 2 * Nc * D * D)
-    m["scatter.cell"] = (6 * Nc * kc + 4 * Nc * D, 0)
-    m["scatter.net"] = (6 * Nn * kn + 4 * Nn * D, 0)
     return m
 
 

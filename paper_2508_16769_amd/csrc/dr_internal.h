@@ -65,13 +65,13 @@ struct GemmOperand {              // one K-segment of C = sum_seg A_seg * B_seg
     const float* W;               // [D, D]
     int transpose_w;              // 0: B = W, 1: B = W^T
 };
-enum GemmEpilogue { kEpiStore = 0, kEpiMaxMerge = 1, kEpiSampleAdd = 2 };
+enum GemmEpilogue { kEpiStore = 0, kEpiMaxMerge = 1, kEpiSampleDense = 2 };
 // C[rows, D] = sum over segments; epilogue:
-//   kEpiStore     : out[rows,D] = C
-//   kEpiMaxMerge  : mask_out = (out >= C); out = max(out, C)          (out holds the near branch on entry)
-//   kEpiSampleAdd : compact[rows,k] += C[row, idx[row,t]]
+//   kEpiStore       : out[rows,D] = C
+//   kEpiMaxMerge    : mask_out = (out >= C); out = max(out, C)        (out holds the near branch on entry)
+//   kEpiSampleDense : out[row,:] = 0 except out[row, idx[row,t]] = compact[row,t] + C[row, idx[row,t]]
 int launch_gemm(const GemmOperand* segs, int nseg, int64_t rows, int D, GemmEpilogue epi, float* out,
-                uint8_t* mask_out, const uint16_t* sample_idx, int sample_k, float* compact, hipStream_t s);
+                uint8_t* mask_out, const uint16_t* sample_idx, int sample_k, const float* compact, hipStream_t s);
 
 struct WgradOperand {             // dW[D,D] = A^T B over `rows` rows
     const float* a_dense;         // [rows, D] or nullptr
@@ -84,8 +84,5 @@ struct WgradOperand {             // dW[D,D] = A^T B over `rows` rows
 };
 size_t wgrad_scratch_bytes(int64_t rows, int D);
 int launch_wgrad(const WgradOperand& op, int64_t rows, int D, float* dW, void* scratch, hipStream_t s);
-
-int launch_scatter_compact(const float* compact, const uint16_t* idx, int64_t n, int D, int k, float* dense,
-                           hipStream_t s);
 
 }  // namespace drc

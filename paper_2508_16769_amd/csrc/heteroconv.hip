@@ -11,15 +11,15 @@ namespace {
 // kernel ids for the optional per-kernel timing (heteroconv_profile / heteroconv_kernel_times)
 enum KernelId {
     kTopkCell, kTopkNet, kFwdNear, kFwdPins, kFwdPinned, kProjNear, kProjPins, kProjPinnedMerge,
-    kDhNear, kBwdNear, kWgNeighNear, kWgSelfNear, kDhPins, kBwdPins, kSelfNearSample, kScatterCell,
-    kWgNeighPins, kWgSelfPins, kDhPinned, kBwdPinned, kSelfPinsSample, kScatterNet, kWgPinned, kNumKernels
+    kDhNear, kBwdNear, kWgNeighNear, kWgSelfNear, kDhPins, kBwdPins, kSelfNearSample,
+    kWgNeighPins, kWgSelfPins, kDhPinned, kBwdPinned, kSelfPinsSample, kWgPinned, kNumKernels
 };
 const char* const kKernelNames[kNumKernels] = {
     "dr_topk.cell", "dr_topk.net", "dr_spmm_fwd.near", "dr_spmm_fwd.pins", "dr_spmm_fwd.pinned",
     "proj.near", "proj.pins", "proj.pinned+merge",
     "dproj.near", "dr_spmm_bwd.near", "wgrad.neigh_near", "wgrad.self_near", "dproj.pins", "dr_spmm_bwd.pins",
-    "dself.near(sampled)", "scatter.cell", "wgrad.neigh_pins", "wgrad.self_pins", "dproj.pinned",
-    "dr_spmm_bwd.pinned", "dself.pins(sampled)", "scatter.net", "wgrad.pinned"};
+    "dself.near+dX", "wgrad.neigh_pins", "wgrad.self_pins", "dproj.pinned",
+    "dr_spmm_bwd.pinned", "dself.pins+dX", "wgrad.pinned"};
 struct TimedLaunch { int id; hipEvent_t start, stop; };
 }  // namespace
 
@@ -298,7 +298,7 @@ int heteroconv_bwd(dr_heteroconv* c, const float* dY_cell, const float* dY_net, 
                    void* stream) {
     DRC_REQUIRE(c != nullptr, "heteroconv_bwd: null context");
     DRC_REQUIRE(dY_cell && dY_net && dX_cell && dX_net, "heteroconv_bwd: null tensor");
-    DRC_REQUIRE(aligned(dY_cell, 16) && aligned(dY_net, 16) && aligned(dX_cell, 4) && aligned(dX_net, 4),
+    DRC_REQUIRE(aligned(dY_cell, 16) && aligned(dY_net, 16) && aligned(dX_cell, 16) && aligned(dX_net, 16),
                 "heteroconv_bwd: misaligned tensor");
     DRC_TRY(check_weights(W, "heteroconv_bwd"));
     DRC_TRY(check_saved(S, "heteroconv_bwd"));
@@ -343,10 +343,9 @@ int heteroconv_bwd(dr_heteroconv* c, const float* dY_cell, const float* dY_net, 
         GemmOperand seg[1] = {};
         seg[0].dense = dY_cell; seg[0].mask = S->mask; seg[0].mask_keep = 1;
         seg[0].W = W->self_near; seg[0].transpose_w = 1;
-        { ScopedTiming tm(c, kSelfNearSample, s_pins); DRC_TRY(launch_gemm(seg, 1, c->Nc, D, kEpiSampleAdd, nullptr, nullptr, S->idx_cell, c->k_cell, c->dXs_cell,
-                            s_pins)); }
+        { ScopedTiming tm(c, kSelfNearSample, s_pins); DRC_TRY(launch_gemm(seg, 1, c->Nc, D, kEpiSampleDense, dX_cell, nullptr, S->idx_cell, c->k_cell,
+                            c->dXs_cell, s_pins)); }
     }
-    { ScopedTiming tm(c, kScatterCell, s_pins); DRC_TRY(launch_scatter_compact(c->dXs_cell, S->idx_cell, c->Nc, D, c->k_cell, dX_cell, s_pins)); }
     {
         WgradOperand op = {};
         op.a_dense = S->H_pins; op.b = dY_net;
@@ -368,10 +367,9 @@ int heteroconv_bwd(dr_heteroconv* c, const float* dY_cell, const float* dY_net, 
     {
         GemmOperand seg[1] = {};
         seg[0].dense = dY_net; seg[0].W = W->self_pins; seg[0].transpose_w = 1;
-        { ScopedTiming tm(c, kSelfPinsSample, s_pinned); DRC_TRY(launch_gemm(seg, 1, c->Nn, D, kEpiSampleAdd, nullptr, nullptr, S->idx_net, c->k_net, c->dXs_net,
-                            s_pinned)); }
+        { ScopedTiming tm(c, kSelfPinsSample, s_pinned); DRC_TRY(launch_gemm(seg, 1, c->Nn, D, kEpiSampleDense, dX_net, nullptr, S->idx_net, c->k_net,
+                            c->dXs_net, s_pinned)); }
     }
-    { ScopedTiming tm(c, kScatterNet, s_pinned); DRC_TRY(launch_scatter_compact(c->dXs_net, S->idx_net, c->Nn, D, c->k_net, dX_net, s_pinned)); }
     {
         WgradOperand op = {};
         op.a_dense = S->H_pinned; op.b = dY_cell; op.b_mask = S->mask; op.b_mask_keep = 0;
