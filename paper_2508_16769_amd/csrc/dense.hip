@@ -51,7 +51,7 @@ struct GemmParams {
 __device__ __forceinline__ int mfma_row(int lane, int r) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
 
 template <int NT, int NSEG>
-__global__ __launch_bounds__(kPT) void proj_kernel(GemmParams p) {
+__global__ __launch_bounds__(kPT, (NSEG == 1 ? 2 : 1)) void proj_kernel(GemmParams p) {
     using C = ProjCfg<NT>;
     constexpr int D = C::D, KS = C::KS, BM = C::BM, SPW = C::SPW, LDA = C::LDA, F4 = C::F4;
     extern __shared__ float smem[];
@@ -140,17 +140,26 @@ __global__ __launch_bounds__(kPT) void proj_kernel(GemmParams p) {
             }
         }
     };
+    // A operands are read from LDS two k-steps ahead of the MFMAs that consume them (explicit software
+    // pipeline; the scheduling barriers keep the compiler from sinking the reads back next to their use).
     auto multiply = [&](const float* b, auto sg_tag) {
         constexpr int SG = decltype(sg_tag)::value;
         if (!mm) return;
         const float* a0 = b + ((rg * SPW) * 32 + (lane & 31)) * LDA + (lane >> 5);
+        float a[3][SPW];
+#pragma unroll
+        for (int j = 0; j < SPW; ++j) { a[0][j] = a0[j * 32 * LDA]; a[1][j] = a0[j * 32 * LDA + 2]; }
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            float a[SPW];
+            if (s + 2 < KS) {
 #pragma unroll
-            for (int j = 0; j < SPW; ++j) a[j] = a0[j * 32 * LDA + 2 * s];
+                for (int j = 0; j < SPW; ++j) a[(s + 2) % 3][j] = a0[j * 32 * LDA + 2 * (s + 2)];
+            }
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int j = 0; j < SPW; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[j], breg[SG][s], acc[j], 0, 0, 0);
+            for (int j = 0; j < SPW; ++j)
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[s % 3][j], breg[SG][s], acc[j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
@@ -401,15 +410,25 @@ __global__ __launch_bounds__(kPT) void wgrad_partial_kernel(WgradParams p) {
             const float* sB = cur ? sB1 : sB0;
             if (has_next) prefetch(rr + kWgRC);
             if (mm) {
+                // operands of k-step i+1 are read from LDS before the MFMAs of k-step i are issued
+                const float* pa = sA + (lane >> 5) * LD + wave * 32 + (lane & 31);
+                const float* pb = sB + (lane >> 5) * LD + (lane & 31);
+                float av[2], b[2][NT];
+                av[0] = pa[0];
 #pragma unroll
-                for (int kk = 0; kk < kWgRC; kk += 2) {
-                    const int r = kk + (lane >> 5);
-                    const float av = sA[r * LD + wave * 32 + (lane & 31)];
-                    float b[NT];
+                for (int j = 0; j < NT; ++j) b[0][j] = pb[j * 32];
 #pragma unroll
-                    for (int j = 0; j < NT; ++j) b[j] = sB[r * LD + j * 32 + (lane & 31)];
+                for (int i = 0; i < kWgRC / 2; ++i) {
+                    if (i + 1 < kWgRC / 2) {
+                        av[(i + 1) & 1] = pa[(2 * i + 2) * LD];
 #pragma unroll
-                    for (int j = 0; j < NT; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, b[j], acc[j], 0, 0, 0);
+                        for (int j = 0; j < NT; ++j) b[(i + 1) & 1][j] = pb[(2 * i + 2) * LD + j * 32];
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int j = 0; j < NT; ++j)
+                        acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i & 1], b[i & 1][j], acc[j], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
             if (has_next) commit(rr + kWgRC, cur ? sA0 : sA1, cur ? sB0 : sB1);
