@@ -4,8 +4,9 @@
 // One wavefront owns one row at a time.  Lane l holds columns l, 64+l, 128+l, ... (coalesced dword
 // loads).  Values are mapped to order-preserving unsigned keys; the k-th largest key is found by a
 // most-significant-bit-first search in which every step is one v_cmp per register plus a scalar
-// popcount of the ballot; compaction positions come from mbcnt prefix counts of the keep-ballots, which
-// yields ascending column order for free.
+// popcount of the ballot, with an early exit once a probe isolates exactly k elements; compaction
+// positions come from mbcnt prefix counts of the keep-ballots, which yields ascending column order for
+// free.
 #include "dr_internal.h"
 
 namespace drc {
@@ -20,31 +21,39 @@ __device__ __forceinline__ int lanes_below(unsigned long long m) {
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
 }
 
+constexpr int kRowsInFlight = 4;   // rows whose loads are outstanding per wavefront
+
 template <int EPL>
 __global__ __launch_bounds__(256) void topk_rows_kernel(const float* __restrict__ X, int n, int D, int k,
                                                         float* __restrict__ vals, uint16_t* __restrict__ idx) {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
-    const int waves_per_grid = gridDim.x * (blockDim.x >> 6);
-    for (int row = blockIdx.x * (blockDim.x >> 6) + wave; row < n; row += waves_per_grid) {
-        const float* x = X + (size_t)row * D;
-        float v[EPL];
+    const int stride = gridDim.x * (blockDim.x >> 6);        // rows between consecutive rows of one wavefront
+    const int row0 = blockIdx.x * (blockDim.x >> 6) + wave;
+
+    // loads are unconditional (row and column clamped to valid addresses): the next rows stay in flight
+    // while the current one is selected
+    float v[kRowsInFlight][EPL];
+    auto load_row = [&](float (&dst)[EPL], int row) {
+        const float* x = X + (size_t)min(row, n - 1) * D;
+#pragma unroll
+        for (int s = 0; s < EPL; ++s) dst[s] = x[min(s * kWave + lane, D - 1)];
+    };
+    auto select_row = [&](const float (&val)[EPL], int row) {
         uint32_t key[EPL];
 #pragma unroll
-        for (int s = 0; s < EPL; ++s) {
-            int c = s * kWave + lane;
-            v[s] = (c < D) ? x[c] : 0.0f;
-            key[s] = (c < D) ? order_key(v[s]) : 0u;    // padding key 0 is below every real key
-        }
-        // T = largest threshold with count(key >= T) >= k  == the k-th largest key
+        for (int s = 0; s < EPL; ++s) key[s] = (s * kWave + lane < D) ? order_key(val[s]) : 0u;   // padding key 0 < real keys
+        // T = largest threshold with count(key >= T) >= k  == the k-th largest key.  The search stops as
+        // soon as a probe separates exactly k elements: then {key >= T} is already the answer, which on
+        // tie-free data happens after about a dozen of the 32 bits.
         uint32_t T = 0;
-#pragma unroll
         for (int bit = 31; bit >= 0; --bit) {
             uint32_t cand = T | (1u << bit);
             int cnt = 0;
 #pragma unroll
             for (int s = 0; s < EPL; ++s) cnt += __popcll(__ballot(key[s] >= cand));
             if (cnt >= k) T = cand;
+            if (cnt == k) break;
         }
         int n_gt = 0;
 #pragma unroll
@@ -61,11 +70,22 @@ __global__ __launch_bounds__(256) void topk_rows_kernel(const float* __restrict_
             unsigned long long mk = __ballot(keep);
             if (keep) {
                 int pos = kept_before + lanes_below(mk);
-                vals[base + pos] = v[s];
+                vals[base + pos] = val[s];
                 idx[base + pos] = (uint16_t)(s * kWave + lane);
             }
             kept_before += __popcll(mk);
             eq_before += __popcll(meq);
+        }
+    };
+
+#pragma unroll
+    for (int i = 0; i < kRowsInFlight; ++i) load_row(v[i], row0 + i * stride);
+    for (int base = row0; base < n; base += kRowsInFlight * stride) {
+#pragma unroll
+        for (int i = 0; i < kRowsInFlight; ++i) {
+            const int row = base + i * stride;
+            if (row < n) select_row(v[i], row);
+            load_row(v[i], row + kRowsInFlight * stride);
         }
     }
 }
@@ -74,7 +94,7 @@ template <int EPL>
 static void launch_epl(const float* X, int n, int D, int k, float* vals, uint16_t* idx, hipStream_t s) {
     int waves_per_block = 4;
     long blocks = ((long)n + waves_per_block - 1) / waves_per_block;
-    if (blocks > 32768) blocks = 32768;
+    if (blocks > 4096) blocks = 4096;            // two full rounds of 8 waves/SIMD; each wavefront strides over rows
     hipLaunchKernelGGL(topk_rows_kernel<EPL>, dim3((unsigned)blocks), dim3(256), 0, s, X, n, D, k, vals, idx);
 }
 
