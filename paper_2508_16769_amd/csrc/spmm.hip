@@ -32,12 +32,14 @@
 // assignment keeps the 8 lanes of one load inside one 128-byte line of the dH row when 4k = D).
 #include "dr_internal.h"
 
+#include <cstdlib>
+
 namespace drc {
 
 constexpr int kLPE = 8;          // lanes per row group
 constexpr int kNG = kWave / kLPE;  // groups per wavefront
 constexpr int kRW = 32;          // rows per wavefront-workgroup
-constexpr int kSolo = 64;        // rows with more edges are walked by all 8 groups together
+constexpr int kSolo = 32;        // rows with more edges are walked by all 8 groups together
 constexpr int kCap = 512;        // edge records staged in LDS per pass (rows never straddle passes)
 constexpr int kStageIters = kCap / kWave;
 constexpr unsigned kValid = 0x80000000u, kLast = 0x40000000u, kRowMask = 0x0000ffffu;
@@ -47,11 +49,12 @@ struct WavePlan {
     int* sOrder;   // [kRW]     slot -> local row; solo rows by degree, descending
     int* sStart;   // [kRW + 1] slot -> offset of the row's records in sorted-row order
     int2* sRec;    // [kCap]    staged (column, value bits) records
+    int* sNext;    // [1]       next undealt slot of the current pass
     int n_solo;
     unsigned long long coop_mask, zero_mask;
 };
 
-__host__ __device__ constexpr int plan_ints() { return (kRW + 1) + kRW + (kRW + 1) + 2 /*pad*/ + 2 * kCap; }
+__host__ __device__ constexpr int plan_ints() { return (kRW + 1) + kRW + (kRW + 1) + 2 + 2 /*pad*/ + 2 * kCap; }
 
 __device__ __forceinline__ void lds_fence() { __syncthreads(); }   // one wavefront per workgroup: orders LDS traffic
 
@@ -60,7 +63,8 @@ __device__ __forceinline__ WavePlan make_plan(int* base, const int32_t* __restri
     p.sRp = base;
     p.sOrder = p.sRp + (kRW + 1);
     p.sStart = p.sOrder + kRW;
-    int* r = p.sStart + (kRW + 1);
+    p.sNext = p.sStart + (kRW + 1);
+    int* r = p.sNext + 2;
     r += (reinterpret_cast<uintptr_t>(r) & 7) ? 1 : 0;   // 8-byte alignment for int2
     p.sRec = reinterpret_cast<int2*>(r);
 
@@ -152,14 +156,13 @@ __device__ __forceinline__ void stage_chunk(const WavePlan& p, const int32_t* __
     }
 }
 
-// Record stream of one group.  Solo mode: the group's rows of the pass, boustrophedon over the slots
-// (sa + g, sa + 15 - g, sa + 16 + g, ...), one record after the other across row boundaries.
+// Record stream of one group.  Solo mode: the group takes the next undealt row of the pass whenever it
+// finishes one (rows are queued by degree, longest first, so the groups finish together), and consumes
+// the records of its rows one after the other across row boundaries.
 // Strided mode (long rows): records g, g + 8, ... of the staged chunk, no row boundaries.
 struct Stream {
-    int round, cur, row_end, row, done;
-    __device__ __forceinline__ void next_row(const WavePlan& p, int g, int sa, int npass, int base) {
-        ++round;
-        const int li = round * kNG + ((round & 1) ? (kNG - 1 - g) : g);
+    int cur, row_end, row, done;
+    __device__ __forceinline__ void take_slot(const WavePlan& p, int li, int sa, int npass, int base) {
         if (li < npass) {
             const int s = sa + li;
             cur = p.sStart[s] - base;
@@ -169,9 +172,16 @@ struct Stream {
             done = 1;
         }
     }
+    __device__ __forceinline__ void next_row(const WavePlan& p, int sa, int npass, int base) {
+        const int lane = threadIdx.x;
+        int li = 0;
+        if ((lane & (kLPE - 1)) == 0) li = atomicAdd(p.sNext, 1);
+        li = __shfl(li, lane & ~(kLPE - 1), kWave);
+        take_slot(p, li, sa, npass, base);
+    }
     // returns the meta word of the record just taken and advances
     template <bool STRIDED>
-    __device__ __forceinline__ unsigned advance(const WavePlan& p, int g, int sa, int npass, int base) {
+    __device__ __forceinline__ unsigned advance(const WavePlan& p, int sa, int npass, int base) {
         unsigned m = kValid | (unsigned)row;
         if constexpr (STRIDED) {
             cur += kNG;
@@ -179,7 +189,7 @@ struct Stream {
         } else {
             if (++cur == row_end) {
                 m |= kLast;
-                next_row(p, g, sa, npass, base);
+                next_row(p, sa, npass, base);
             }
         }
         return m;
@@ -254,7 +264,7 @@ __device__ __forceinline__ void fwd_issue(FwdBatch<KPL, EPI>& b, Stream& st, con
         const uint32_t col = valid ? (uint32_t)rec.x : 0u;   // exhausted lanes gather source row 0
         b.a[q] = __int_as_float(rec.y);
         b.p[q].load(xs_vals, xs_idx, col * (uint32_t)k + (uint32_t)(t * KPL));
-        b.meta[q] = valid ? st.template advance<STRIDED>(plan, g, sa, npass, base) : 0u;
+        b.meta[q] = valid ? st.template advance<STRIDED>(plan, sa, npass, base) : 0u;
     }
 }
 
@@ -296,7 +306,7 @@ __device__ __forceinline__ void fwd_run(Stream& st, const WavePlan& plan, const 
                     const int c = xs_idx[rb + q];
                     buf[c] = fmaf(a, xs_vals[rb + q], buf[c]);
                 }
-                const unsigned m = st.template advance<STRIDED>(plan, g, sa, npass, base);
+                const unsigned m = st.template advance<STRIDED>(plan, sa, npass, base);
                 if (m & kLast) flush_row(Hblk + (size_t)(m & kRowMask) * D, buf, D, t, vec_store);
             }
         }
@@ -337,7 +347,7 @@ __global__ __launch_bounds__(kWave) void spmm_fwd_kernel(
             lds_fence();
             stage_chunk(plan, colidx, avals, c0, n);
             lds_fence();
-            Stream st{0, g, n, row, g >= n ? 1 : 0};
+            Stream st{g, n, row, g >= n ? 1 : 0};
             fwd_run<KPL, EPI, true>(st, plan, xs_vals, xs_idx, buf, Hblk, D, k, t, g, 0, 0, 0, vec_store);
         }
         lds_fence();
@@ -358,10 +368,11 @@ __global__ __launch_bounds__(kWave) void spmm_fwd_kernel(
     for (int sa = 0; sa < plan.n_solo;) {
         const int sb = pass_end(plan, sa);
         lds_fence();
+        if (lane == 0) *plan.sNext = kNG;
         stage_solo(plan, colidx, avals, sa, sb);
         lds_fence();
-        Stream st{-1, 0, 0, 0, 0};
-        st.next_row(plan, g, sa, sb - sa, plan.sStart[sa]);
+        Stream st{0, 0, 0, 0};
+        st.take_slot(plan, g, sa, sb - sa, plan.sStart[sa]);     // first 8 rows of the pass: one per group
         fwd_run<KPL, EPI, false>(st, plan, xs_vals, xs_idx, buf, Hblk, D, k, t, g, sa, sb - sa, plan.sStart[sa],
                                  vec_store);
         sa = sb;
@@ -387,6 +398,10 @@ int launch_spmm_fwd(const dr_csr* A, const float* xs_vals, const uint16_t* xs_id
 #define DRC_LAUNCH_FWD(V, E)                                                                                       \
     hipLaunchKernelGGL((spmm_fwd_kernel<V, E>), grid, block, lds, s, A->rowptr, A->colidx, A->vals, xs_vals, xs_idx, \
                        H, M, D, k, n_tiles, per_xcd, vec_store)
+    static const int tune_epi = getenv("DRC_TUNE_FWD_EPI") ? atoi(getenv("DRC_TUNE_FWD_EPI")) : 0;
+    if (kpl == 4 && tune_epi == 2) { DRC_LAUNCH_FWD(4, 2); DRC_HIP(hipGetLastError()); return DR_OK; }
+    if (kpl == 4 && tune_epi == 8) { DRC_LAUNCH_FWD(4, 8); DRC_HIP(hipGetLastError()); return DR_OK; }
+    if (kpl == 4 && tune_epi == 1) { DRC_LAUNCH_FWD(4, 1); DRC_HIP(hipGetLastError()); return DR_OK; }
     switch (kpl) {
         case 1: DRC_LAUNCH_FWD(1, 4); break;
         case 2: DRC_LAUNCH_FWD(2, 4); break;
@@ -433,7 +448,7 @@ __device__ __forceinline__ void bwd_issue(BwdBatch<KPL, EPI>& b, Stream& st, int
         for (int u = 0; u < KPL; ++u) b.v[q][u] = rowp[ci[u]];
         unsigned m = 0;
         if (valid) {
-            m = st.template advance<STRIDED>(plan, g, sa, npass, base);
+            m = st.template advance<STRIDED>(plan, sa, npass, base);
             if (!STRIDED && (m & kLast) && !st.done) load_ci<KPL>(ci, sIdx, st.row, t);
         }
         b.meta[q] = m;
@@ -529,7 +544,7 @@ __global__ __launch_bounds__(kWave) void spmm_bwd_kernel(
                 lds_fence();
                 stage_chunk(plan, t_colidx, t_vals, c0, n);
                 lds_fence();
-                Stream st{0, g, n, row, g >= n ? 1 : 0};
+                Stream st{g, n, row, g >= n ? 1 : 0};
                 bwd_run<KPL, EPI, true>(st, ci, acc, plan, sIdx, dH, Gblk, D, k, s0, t, g, 0, 0, 0, accumulate);
             }
 #pragma unroll
@@ -551,10 +566,11 @@ __global__ __launch_bounds__(kWave) void spmm_bwd_kernel(
         for (int sa = 0; sa < plan.n_solo;) {
             const int sb = pass_end(plan, sa);
             lds_fence();
+            if (lane == 0) *plan.sNext = kNG;
             stage_solo(plan, t_colidx, t_vals, sa, sb);
             lds_fence();
-            Stream st{-1, 0, 0, 0, 0};
-            st.next_row(plan, g, sa, sb - sa, plan.sStart[sa]);
+            Stream st{0, 0, 0, 0};
+            st.take_slot(plan, g, sa, sb - sa, plan.sStart[sa]);
             int ci[KPL];
             float acc[KPL];
 #pragma unroll
