@@ -32,8 +32,6 @@
 // assignment keeps the 8 lanes of one load inside one 128-byte line of the dH row when 4k = D).
 #include "dr_internal.h"
 
-#include <cstdlib>
-
 namespace drc {
 
 constexpr int kLPE = 8;          // lanes per row group
@@ -42,6 +40,7 @@ constexpr int kRW = 32;          // rows per wavefront-workgroup
 constexpr int kSolo = 32;        // rows with more edges are walked by all 8 groups together
 constexpr int kCap = 512;        // edge records staged in LDS per pass (rows never straddle passes)
 constexpr int kStageIters = kCap / kWave;
+constexpr int kBufPad = 4;       // row buffers are D + 4 words apart: group g starts 4 banks after group g-1
 constexpr unsigned kValid = 0x80000000u, kLast = 0x40000000u, kRowMask = 0x0000ffffu;
 
 struct WavePlan {
@@ -326,11 +325,12 @@ __global__ __launch_bounds__(kWave) void spmm_fwd_kernel(
     const int nr = min(kRW, M - r0);
     const int lane = threadIdx.x;
     const int g = lane / kLPE, t = lane % kLPE;
-    float* buf = rowbuf + g * D;
+    const int ldb = D + kBufPad;
+    float* buf = rowbuf + g * ldb;
     float* Hblk = H + (size_t)r0 * D;
 
-    for (int i = lane; i < kNG * D; i += kWave) rowbuf[i] = 0.0f;
-    WavePlan plan = make_plan(reinterpret_cast<int*>(rowbuf + kNG * D), rowptr, r0, nr);
+    for (int i = lane; i < kNG * ldb; i += kWave) rowbuf[i] = 0.0f;
+    WavePlan plan = make_plan(reinterpret_cast<int*>(rowbuf + kNG * ldb), rowptr, r0, nr);
 
     // ---- rows without edges: zeros ----
     for (unsigned long long m = plan.zero_mask; m; m &= m - 1) {
@@ -356,8 +356,8 @@ __global__ __launch_bounds__(kWave) void spmm_fwd_kernel(
             float s = 0.0f;
 #pragma unroll
             for (int q = 0; q < kNG; ++q) {
-                s += rowbuf[q * D + c];
-                rowbuf[q * D + c] = 0.0f;
+                s += rowbuf[q * ldb + c];
+                rowbuf[q * ldb + c] = 0.0f;
             }
             out[c] = s;
         }
@@ -393,15 +393,11 @@ int launch_spmm_fwd(const dr_csr* A, const float* xs_vals, const uint16_t* xs_id
         else if (q == 2 && aligned(xs_vals, 8) && aligned(xs_idx, 4)) kpl = 2;
         else if ((q == 4 || q == 8 || q == 16) && aligned(xs_vals, 16) && aligned(xs_idx, 8)) kpl = q;
     }
-    const size_t lds = sizeof(float) * (size_t)kNG * D + sizeof(int) * (size_t)plan_ints();
+    const size_t lds = sizeof(float) * (size_t)kNG * (D + kBufPad) + sizeof(int) * (size_t)plan_ints();
     dim3 grid((unsigned)(per_xcd * kNumXcd)), block(kWave);
 #define DRC_LAUNCH_FWD(V, E)                                                                                       \
     hipLaunchKernelGGL((spmm_fwd_kernel<V, E>), grid, block, lds, s, A->rowptr, A->colidx, A->vals, xs_vals, xs_idx, \
                        H, M, D, k, n_tiles, per_xcd, vec_store)
-    static const int tune_epi = getenv("DRC_TUNE_FWD_EPI") ? atoi(getenv("DRC_TUNE_FWD_EPI")) : 0;
-    if (kpl == 4 && tune_epi == 2) { DRC_LAUNCH_FWD(4, 2); DRC_HIP(hipGetLastError()); return DR_OK; }
-    if (kpl == 4 && tune_epi == 8) { DRC_LAUNCH_FWD(4, 8); DRC_HIP(hipGetLastError()); return DR_OK; }
-    if (kpl == 4 && tune_epi == 1) { DRC_LAUNCH_FWD(4, 1); DRC_HIP(hipGetLastError()); return DR_OK; }
     switch (kpl) {
         case 1: DRC_LAUNCH_FWD(1, 4); break;
         case 2: DRC_LAUNCH_FWD(2, 4); break;
