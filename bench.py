@@ -111,6 +111,11 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-scale", type=int, default=None, help="oracle sample = 1/scale of the workload")
     ap.add_argument("--no-profile-events", action="store_true", help="do not bracket kernels with HIP events")
+    ap.add_argument("--overlap", choices=("auto", "on", "off"), default="auto",
+                    help="relation concurrency: three streams (on), one stream (off), or the library's size rule")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 1 GiB device copy a few times (known traffic, for scaling rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE readings) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (the path is single-GPU; see DESIGN.md for how it "
@@ -126,6 +131,18 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        a = torch.ones(256 * 1024 * 1024, dtype=torch.float32, device="cuda")
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(5):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / 5
+        print(json.dumps({"copy_bytes_read": a.numel() * 4, "copy_bytes_written": a.numel() * 4,
+                          "ms": round(dt * 1e3, 4), "GBs": round(2 * a.numel() * 4 / dt / 1e9, 1)}), flush=True)
+        return 0
     w = workload(args.workload)
     D = w["D"]
     k = args.k if args.k is not None else w["k"]
@@ -145,6 +162,7 @@ def main() -> int:
     t_graph = time.perf_counter()
     layer = P.HeteroConv(near, pins, pinned, D, k, k)     # device transposes + scratch
     t_ctx = time.perf_counter() - t_graph
+    layer.heteroconv_set_overlap({"auto": P.DR_OVERLAP_AUTO, "on": P.DR_OVERLAP_ON, "off": P.DR_OVERLAP_OFF}[args.overlap])
     saved = layer.alloc_saved()
     Wd = {n: dev(T.W[n]) for n in P.WEIGHT_NAMES}
     X_cell, X_net = dev(T.X_cell), dev(T.X_net)
@@ -237,6 +255,7 @@ def main() -> int:
                                f"E_pins={E['pins']}, D={D}, k={k}, one HeteroConv layer fwd+bwd",
                    "step_algorithmic_MB": round(step_bytes / 1e6, 1),
                    "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
+                   "relation_overlap": args.overlap,
                    "setup_s": round(t_setup, 2), "context_create_s": round(t_ctx, 3)},
         "roofline": roofline,
         "dr_spmm_kernels": dr_region,

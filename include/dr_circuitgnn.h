@@ -188,6 +188,18 @@ int heteroconv_get_transpose(const dr_heteroconv* ctx, int which, dr_csr* out);
 int heteroconv_destroy(dr_heteroconv* ctx);
 
 /*
+ * Relation concurrency (paper Section 3.4).  DR_OVERLAP_ON: the near, pins and pinned pipelines are enqueued on
+ * three HIP streams and joined by events only where the data flow demands it.  DR_OVERLAP_OFF: the same kernels,
+ * in the same dependency order, back to back on one stream.  DR_OVERLAP_AUTO (default): separate streams while one
+ * relation's launches leave CUs idle at their tails (max(Nc, Nn) * D < 2^26), one stream beyond that, where
+ * overlapping launches only time-slice the CUs.  Takes effect from the next heteroconv_fwd / heteroconv_bwd.
+ */
+#define DR_OVERLAP_AUTO 0
+#define DR_OVERLAP_ON   1
+#define DR_OVERLAP_OFF  2
+int heteroconv_set_overlap(dr_heteroconv* ctx, int mode);
+
+/*
  * Measurement aid (not part of the method): per-kernel device time of the layer's launches.
  * heteroconv_profile(ctx, 1) makes every later heteroconv_fwd / heteroconv_bwd bracket each of its kernel
  * launches with a pair of HIP events recorded on the stream that launch runs on; heteroconv_profile(ctx, 0)

@@ -23,6 +23,9 @@ DR_ERR_HIP = -3
 DR_ERR_WORKSPACE = -4
 DR_NORM_MEAN = 0
 DR_NORM_SYM = 1
+DR_OVERLAP_AUTO = 0
+DR_OVERLAP_ON = 1
+DR_OVERLAP_OFF = 2
 
 WEIGHT_NAMES = ("self_near", "neigh_near", "self_pins", "neigh_pins", "pinned")
 EXPORTS = (
@@ -31,6 +34,7 @@ EXPORTS = (
     "dr_csr_normalize_workspace_bytes", "dr_csr_normalize",
     "heteroconv_create", "heteroconv_fwd", "heteroconv_bwd", "heteroconv_get_transpose", "heteroconv_destroy",
     "heteroconv_profile", "heteroconv_num_kernels", "heteroconv_kernel_name", "heteroconv_kernel_times",
+    "heteroconv_set_overlap",
 )
 
 
@@ -222,6 +226,9 @@ class HeteroConv:
         out = dr_csr()
         _check(load().heteroconv_get_transpose(self._ctx, ctypes.c_int(which), ctypes.byref(out)))
         return out
+
+    def heteroconv_set_overlap(self, mode: int) -> None:
+        _check(load().heteroconv_set_overlap(self._ctx, ctypes.c_int(mode)))
 
     def heteroconv_profile(self, enable: bool) -> None:
         _check(load().heteroconv_profile(self._ctx, ctypes.c_int(1 if enable else 0)))
