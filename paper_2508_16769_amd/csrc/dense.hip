@@ -7,11 +7,15 @@
 //   - the self-term gradient is sampled at the saved CBSR indices straight out of the accumulators,
 //     added to the compact SpMM gradient and written as the dense, top-k-gated dX rows.
 //
-// Projection kernel.  Persistent workgroups (a few per CU) loop over 64-row tiles.  The weights never
+// Projection kernel.  Persistent workgroups (two per CU) loop over 64-row tiles.  The weights never
 // touch LDS: wavefront w keeps the 32-column slab of W it is responsible for in registers in MFMA
 // B-operand layout for the whole kernel (64 VGPRs per 128x128 weight), so the inner loop is one
-// ds_read_b32 of the A operand per MFMA.  Row tiles are double-buffered through LDS: the global loads
-// of the next tile are in flight while the current one is multiplied; one barrier per tile.
+// ds_read_b128 of the A operand per four MFMAs.  Row tiles are double-buffered through LDS: every global
+// load a tile needs (operand rows, mask bytes, CBSR pairs, the other branch for the max-merge) is issued
+// before the multiply of the previous tile and consumed after it.  The operand kind and the epilogue are
+// template parameters: with a single code path per instantiation every load has exactly one consumer, so
+// the compiler's wait counters are placed at the consumers and not, conservatively, in front of the
+// multiply.
 // These contractions run at the fp32 matrix rate (2*rows*D*D flops per weight); they are bound by the
 // MFMA pipe, not by HBM, once the tiles stream (arithmetic intensity D/4 flop per byte moved).
 #include "dr_internal.h"
@@ -23,6 +27,9 @@ namespace drc {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kPT = 256;  // threads per workgroup (4 wavefronts)
+constexpr int kCP = 8;    // CBSR pairs per thread that are prefetched into registers
+
+enum AKind { kADense = 0, kADenseMasked = 1, kACbsrDense = 2 };   // last: segment 0 CBSR, segment 1 dense
 
 template <int NT> struct ProjCfg {
     static constexpr int D = 32 * NT;
@@ -30,8 +37,10 @@ template <int NT> struct ProjCfg {
     static constexpr int RG = (NT >= 3) ? 1 : (NT == 2 ? 2 : 4);      // wavefront row groups
     static constexpr int BM = (NT == 1) ? 128 : 64;                   // rows per tile
     static constexpr int SPW = (BM / 32) / RG;                        // 32-row sub-tiles per wavefront
-    static constexpr int LDA = D + 1;                                 // LDS row stride (conflict-free column reads)
+    static constexpr int LDA = D + 4;                                 // LDS row stride: rows stay 16-byte aligned
     static constexpr int F4 = BM * D / 4 / kPT;                       // float4 per thread per dense tile
+    static constexpr int TPR = kPT / BM;                              // threads that share one tile row
+    static constexpr int RPW = BM / 4;                                // tile rows staged by one wavefront
     static constexpr size_t kLds = sizeof(float) * 2 * BM * LDA;
 };
 
@@ -47,19 +56,33 @@ struct GemmParams {
     const float* compact;
 };
 
+struct PairRegs {
+    float v[kCP];
+    uint32_t c[kCP];
+};
+
 // C tile element held by (lane, acc register r) of a 32x32 MFMA block
 __device__ __forceinline__ int mfma_row(int lane, int r) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
 
-template <int NT, int NSEG>
-__global__ __launch_bounds__(kPT, (NSEG == 1 ? 2 : 1)) void proj_kernel(GemmParams p) {
+// Contraction index served by MFMA k-step s in lane half h.  Eight consecutive k form a group: half 0
+// takes the first four, half 1 the last four, so a lane fetches the A values of four k-steps with one
+// 16-byte LDS read.  The B registers are loaded in the same order.
+__device__ __forceinline__ int mfma_k(int s, int h) { return 8 * (s >> 2) + 4 * h + (s & 3); }
+
+template <int NT, int AK, int EPI>
+__global__ __launch_bounds__(kPT, (AK == kACbsrDense ? 1 : 2)) void proj_kernel(GemmParams p) {
     using C = ProjCfg<NT>;
     constexpr int D = C::D, KS = C::KS, BM = C::BM, SPW = C::SPW, LDA = C::LDA, F4 = C::F4;
-    extern __shared__ float smem[];
+    constexpr int TPR = C::TPR, RPW = C::RPW;
+    constexpr int NSEG = (AK == kACbsrDense) ? 2 : 1;
+    constexpr bool kMasked = (AK == kADenseMasked);
+    extern __shared__ __align__(16) float smem[];
     float* const buf0 = smem;
     float* const buf1 = smem + BM * LDA;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int ct = wave % NT, rg = wave / NT;
     const bool mm = rg < C::RG;                      // this wavefront multiplies (NT = 3 leaves one idle)
+    const int prow = tid / TPR, ppart = tid % TPR;   // row-owned stagings: tile row and share of it
     const int n_tiles = (p.rows + BM - 1) / BM;
     if ((int)blockIdx.x >= n_tiles) return;
 
@@ -71,7 +94,7 @@ __global__ __launch_bounds__(kPT, (NSEG == 1 ? 2 : 1)) void proj_kernel(GemmPara
         const bool tr = p.seg[sg].transpose_w != 0;
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            const int kk = 2 * s + (lane >> 5), n = 32 * ct + (lane & 31);
+            const int kk = mfma_k(s, lane >> 5), n = 32 * ct + (lane & 31);
             breg[sg][s] = mm ? (tr ? W[(size_t)n * D + kk] : W[(size_t)kk * D + n]) : 0.f;
         }
     }
@@ -82,138 +105,205 @@ __global__ __launch_bounds__(kPT, (NSEG == 1 ? 2 : 1)) void proj_kernel(GemmPara
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[j][r] = 0.0f;
 
-    // Dense operand tile -> registers.  Only loads are issued here (the mask bytes ride along raw and are
-    // applied when the tile is written to LDS), so the whole prefetch stays in flight during the multiply.
+    // ---- dense operand tile: global -> registers -> LDS.  Wavefront w stages tile rows
+    // [w*RPW, (w+1)*RPW); loads are unconditional on clamped rows, masks ride along raw. ----
+    const GemmOperand& od = p.seg[NSEG - 1];
     float4 pre[F4];
     uint32_t prem[F4];
-    auto prefetch = [&](int tile, int sg) {
-        const GemmOperand& o = p.seg[sg];
-        if (!o.dense) return;
+    auto prefetch = [&](int tile) {
 #pragma unroll
         for (int it = 0; it < F4; ++it) {
-            const int q = it * kPT + tid;
-            const int row = q / (D / 4), c4 = (q % (D / 4)) * 4;
-            const int grow = min(tile * BM + row, p.rows - 1);          // clamped: loads are unconditional
-            const size_t off = (size_t)grow * D + c4;
-            pre[it] = *reinterpret_cast<const float4*>(o.dense + off);
-            prem[it] = o.mask ? *reinterpret_cast<const uint32_t*>(o.mask + off) : 0u;
+            const int q = it * kWave + lane;
+            const int row = wave * RPW + q / (D / 4), c4 = (q % (D / 4)) * 4;
+            const size_t off = (size_t)min(tile * BM + row, p.rows - 1) * D + c4;
+            pre[it] = *reinterpret_cast<const float4*>(od.dense + off);
+            if (kMasked) prem[it] = *reinterpret_cast<const uint32_t*>(od.mask + off);
         }
     };
-    auto commit = [&](int tile, int sg, float* b) {  // registers (or CBSR rows) -> LDS tile
-        const GemmOperand& o = p.seg[sg];
-        if (o.dense) {
-            const uint32_t keep = (uint32_t)o.mask_keep;
-            const bool masked = o.mask != nullptr;
+    auto commit = [&](int tile, float* b) {
+        const uint32_t keep = (uint32_t)od.mask_keep;
 #pragma unroll
-            for (int it = 0; it < F4; ++it) {
-                const int q = it * kPT + tid;
-                const int row = q / (D / 4), c4 = (q % (D / 4)) * 4;
-                const bool in = tile * BM + row < p.rows;
+        for (int it = 0; it < F4; ++it) {
+            const int q = it * kWave + lane;
+            const int row = wave * RPW + q / (D / 4), c4 = (q % (D / 4)) * 4;
+            const bool in = tile * BM + row < p.rows;
+            float4 v = pre[it];
+            if (kMasked) {
                 const uint32_t m = prem[it];
-                float* d = b + row * LDA + c4;
-                d[0] = (in && (!masked || ((m >> 0) & 0xffu) == keep)) ? pre[it].x : 0.f;
-                d[1] = (in && (!masked || ((m >> 8) & 0xffu) == keep)) ? pre[it].y : 0.f;
-                d[2] = (in && (!masked || ((m >> 16) & 0xffu) == keep)) ? pre[it].z : 0.f;
-                d[3] = (in && (!masked || ((m >> 24) & 0xffu) == keep)) ? pre[it].w : 0.f;
+                v.x = (((m >> 0) & 0xffu) == keep) ? v.x : 0.f;
+                v.y = (((m >> 8) & 0xffu) == keep) ? v.y : 0.f;
+                v.z = (((m >> 16) & 0xffu) == keep) ? v.z : 0.f;
+                v.w = (((m >> 24) & 0xffu) == keep) ? v.w : 0.f;
             }
-        } else {
-            for (int q = tid; q < BM * LDA; q += kPT) b[q] = 0.0f;
-            __syncthreads();
-            const int k = o.k, total = BM * k;
-            for (int q0 = 0; q0 < total; q0 += 8 * kPT) {      // 8 independent pair loads per thread, then the writes
-                float v[8];
-                int c[8], dst[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const int q = q0 + u * kPT + tid;
-                    const int row = q / k, t = q - row * k;
-                    const int grow = tile * BM + row;
-                    const bool ok = q < total && grow < p.rows;
-                    const size_t off = ok ? (size_t)grow * k + t : 0;
-                    v[u] = o.cbsr_vals[off];
-                    c[u] = o.cbsr_idx[off];
-                    dst[u] = ok ? row * LDA : -1;
-                }
-#pragma unroll
-                for (int u = 0; u < 8; ++u)
-                    if (dst[u] >= 0) b[dst[u] + c[u]] = v[u];
-            }
+            if (!in) v = make_float4(0.f, 0.f, 0.f, 0.f);
+            *reinterpret_cast<float4*>(b + row * LDA + c4) = v;
         }
     };
-    // A operands are read from LDS two k-steps ahead of the MFMAs that consume them (explicit software
-    // pipeline; the scheduling barriers keep the compiler from sinking the reads back next to their use).
+
+    // ---- CBSR pairs of a tile, row-owned: thread (prow, ppart) holds pairs ppart, ppart+TPR, ... of tile
+    // row prow.  The first kCP pairs per thread travel through registers; the rest (k > kCP*TPR) are
+    // fetched when they are placed. ----
+    auto load_pairs = [&](PairRegs& pr, const float* vals, const uint16_t* idx, int k, int tile) {
+        const size_t base = (size_t)min(tile * BM + prow, p.rows - 1) * k;
+#pragma unroll
+        for (int u = 0; u < kCP; ++u) {
+            const int t = min(ppart + TPR * u, k - 1);
+            pr.v[u] = vals[base + t];
+            pr.c[u] = idx[base + t];
+        }
+    };
+    auto zero_own_part = [&](float* rowp) {
+        const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int i = 0; i < D / TPR / 4; ++i) *reinterpret_cast<float4*>(rowp + ppart * (D / TPR) + 4 * i) = z;
+        // The threads of one row sit in one wavefront and LDS executes a wavefront's accesses in order, so
+        // the scattered writes that follow land on the zeroed row without a workgroup barrier.
+        __builtin_amdgcn_wave_barrier();
+    };
+    // D-ReLU rows -> dense LDS tile.  Every write is unconditional: pairs past k go to the padding column,
+    // rows past the end write zeros.
+    auto stage_cbsr = [&](const PairRegs& pr, int tile, float* b) {
+        const GemmOperand& o = p.seg[0];
+        float* rowp = b + prow * LDA;
+        zero_own_part(rowp);
+        const int k = o.k;
+        const bool rin = tile * BM + prow < p.rows;
+#pragma unroll
+        for (int u = 0; u < kCP; ++u) {
+            const int t = ppart + TPR * u;
+            rowp[t < k ? (int)pr.c[u] : D] = rin ? pr.v[u] : 0.f;
+        }
+        const size_t base = (size_t)min(tile * BM + prow, p.rows - 1) * k;
+        for (int u = kCP; u * TPR < k; ++u) {
+            const int t = ppart + TPR * u;
+            const float v = o.cbsr_vals[base + min(t, k - 1)];
+            const int c = o.cbsr_idx[base + min(t, k - 1)];
+            rowp[t < k ? c : D] = rin ? v : 0.f;
+        }
+    };
+
+    // A operands are read from LDS one group of four k-steps ahead of the MFMAs that consume them
+    // (explicit software pipeline; the scheduling barriers keep the reads from sinking next to their use).
     auto multiply = [&](const float* b, auto sg_tag) {
         constexpr int SG = decltype(sg_tag)::value;
         if (!mm) return;
-        const float* a0 = b + ((rg * SPW) * 32 + (lane & 31)) * LDA + (lane >> 5);
-        float a[3][SPW];
+        const float* a0 = b + ((rg * SPW) * 32 + (lane & 31)) * LDA + 4 * (lane >> 5);
+        float4 a[2][SPW];
 #pragma unroll
-        for (int j = 0; j < SPW; ++j) { a[0][j] = a0[j * 32 * LDA]; a[1][j] = a0[j * 32 * LDA + 2]; }
+        for (int j = 0; j < SPW; ++j) a[0][j] = *reinterpret_cast<const float4*>(a0 + j * 32 * LDA);
 #pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            if (s + 2 < KS) {
+        for (int g = 0; g < KS / 4; ++g) {
+            if (g + 1 < KS / 4) {
 #pragma unroll
-                for (int j = 0; j < SPW; ++j) a[(s + 2) % 3][j] = a0[j * 32 * LDA + 2 * (s + 2)];
+                for (int j = 0; j < SPW; ++j)
+                    a[(g + 1) & 1][j] = *reinterpret_cast<const float4*>(a0 + j * 32 * LDA + 8 * (g + 1));
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int j = 0; j < SPW; ++j)
-                acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[s % 3][j], breg[SG][s], acc[j], 0, 0, 0);
+            for (int j = 0; j < SPW; ++j) {
+                const float4 av = a[g & 1][j];
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av.x, breg[SG][4 * g + 0], acc[j], 0, 0, 0);
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av.y, breg[SG][4 * g + 1], acc[j], 0, 0, 0);
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av.z, breg[SG][4 * g + 2], acc[j], 0, 0, 0);
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av.w, breg[SG][4 * g + 3], acc[j], 0, 0, 0);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
     };
+    auto clear_acc = [&]() {
+#pragma unroll
+        for (int j = 0; j < SPW; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[j][r] = 0.0f;
+    };
+    auto store_tile = [&](int tile) {                  // out[rows, D] = C
+        if (!mm) return;
+#pragma unroll
+        for (int j = 0; j < SPW; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = tile * BM + (rg * SPW + j) * 32 + mfma_row(lane, r);
+                if (row < p.rows) p.out[(size_t)row * D + 32 * ct + (lane & 31)] = acc[j][r];
+            }
+    };
 
-    int tile = blockIdx.x, sg = 0, cur = 0;
-    prefetch(tile, sg);
-    commit(tile, sg, buf0);
-    __syncthreads();
-    for (;;) {
-        int ntile = tile, nsg = sg + 1;
-        if (nsg == NSEG) { nsg = 0; ntile = tile + gridDim.x; }
-        const bool has_next = ntile < n_tiles;
-        float* const bcur = cur ? buf1 : buf0;
-        float* const bother = cur ? buf0 : buf1;
-        if (has_next) prefetch(ntile, nsg);
-        if (NSEG == 1 || sg == 0) multiply(bcur, std::integral_constant<int, 0>{});
-        else multiply(bcur, std::integral_constant<int, NSEG - 1>{});
+    if constexpr (AK == kACbsrDense) {
+        // Two segments per row tile: the CBSR operand is multiplied out of buf0, the dense one out of buf1.
+        const GemmOperand& oc = p.seg[0];
+        PairRegs pr;
+        int tile = blockIdx.x;
+        load_pairs(pr, oc.cbsr_vals, oc.cbsr_idx, oc.k, tile);
+        stage_cbsr(pr, tile, buf0);
+        __syncthreads();
+        for (;;) {
+            const int ntile = tile + gridDim.x;
+            const bool has_next = ntile < n_tiles;
+            prefetch(tile);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(buf0, std::integral_constant<int, 0>{});
+            __builtin_amdgcn_sched_barrier(0);
+            commit(tile, buf1);
+            __syncthreads();
+            if (has_next) load_pairs(pr, oc.cbsr_vals, oc.cbsr_idx, oc.k, ntile);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(buf1, std::integral_constant<int, NSEG - 1>{});
+            store_tile(tile);
+            clear_acc();
+            __builtin_amdgcn_sched_barrier(0);
+            if (has_next) stage_cbsr(pr, ntile, buf0);
+            __syncthreads();
+            if (!has_next) break;
+            tile = ntile;
+        }
+    } else {
+        int tile = blockIdx.x, cur = 0;
+        prefetch(tile);
+        commit(tile, buf0);
+        __syncthreads();
+        for (;;) {
+            const int ntile = tile + gridDim.x;
+            const bool has_next = ntile < n_tiles;
+            float* const bcur = cur ? buf1 : buf0;
+            float* const bother = cur ? buf0 : buf1;
+            // what the epilogue of this tile consumes is requested first, then the next tile
+            PairRegs pr;
+            float prev[SPW][16];
+            if constexpr (EPI == kEpiSampleDense) load_pairs(pr, p.compact, p.sample_idx, p.sample_k, tile);
+            if constexpr (EPI == kEpiMaxMerge) {            // the other branch's values (rows clamped, all wavefronts)
+#pragma unroll
+                for (int j = 0; j < SPW; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int row = min(tile * BM + (rg * SPW + j) * 32 + mfma_row(lane, r), p.rows - 1);
+                        prev[j][r] = p.out[(size_t)row * D + 32 * ct + (lane & 31)];
+                    }
+            }
+            if (has_next) prefetch(ntile);
+            __builtin_amdgcn_sched_barrier(0);   // consumers of the registers loaded above stay below the multiply
+            multiply(bcur, std::integral_constant<int, 0>{});
 
-        if (sg == NSEG - 1) {
-            // ---- epilogue of this row tile ----
-            if (p.epi == kEpiStore) {
+            if constexpr (EPI == kEpiStore) {
+                store_tile(tile);
+            } else if constexpr (EPI == kEpiMaxMerge) {
+                // mask = [near >= pinned]; out keeps the near value unless the pinned one is larger
                 if (mm) {
 #pragma unroll
                     for (int j = 0; j < SPW; ++j)
 #pragma unroll
                         for (int r = 0; r < 16; ++r) {
                             const int row = tile * BM + (rg * SPW + j) * 32 + mfma_row(lane, r);
-                            if (row < p.rows) p.out[(size_t)row * D + 32 * ct + (lane & 31)] = acc[j][r];
-                        }
-                }
-            } else if (p.epi == kEpiMaxMerge) {
-                if (mm) {
-#pragma unroll
-                    for (int j = 0; j < SPW; ++j) {
-                        float prev[16];
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) {       // all loads of the other branch first (clamped rows)
-                            const int row = min(tile * BM + (rg * SPW + j) * 32 + mfma_row(lane, r), p.rows - 1);
-                            prev[r] = p.out[(size_t)row * D + 32 * ct + (lane & 31)];
-                        }
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            const int row = tile * BM + (rg * SPW + j) * 32 + mfma_row(lane, r);
+                            const float c = acc[j][r];
+                            const bool near_wins = prev[j][r] >= c;
                             if (row < p.rows) {
                                 const size_t off = (size_t)row * D + 32 * ct + (lane & 31);
-                                const float c = acc[j][r];
-                                const bool near_wins = prev[r] >= c;
                                 p.mask_out[off] = near_wins ? 1 : 0;
                                 if (!near_wins) p.out[off] = c;
                             }
                         }
-                    }
                 }
             } else {
-                // out[row, :] = 0 except out[row, idx[row,t]] = compact[row,t] + C[row, idx[row,t]]
+                // out[row, :] = 0 except out[row, idx[row,t]] = compact[row,t] + C[row, idx[row,t]].
+                // C goes to the free LDS buffer; each wavefront then rebuilds and writes its own rows.
                 if (mm) {
 #pragma unroll
                     for (int j = 0; j < SPW; ++j)
@@ -222,62 +312,74 @@ __global__ __launch_bounds__(kPT, (NSEG == 1 ? 2 : 1)) void proj_kernel(GemmPara
                             bother[((rg * SPW + j) * 32 + mfma_row(lane, r)) * LDA + 32 * ct + (lane & 31)] = acc[j][r];
                 }
                 __syncthreads();                                   // C tile complete; bcur no longer read
-                for (int q = tid; q < BM * LDA; q += kPT) bcur[q] = 0.0f;
-                __syncthreads();
-                const int k = p.sample_k, total = BM * k;
-                for (int q0 = 0; q0 < total; q0 += 8 * kPT) {
-                    float v[8];
-                    int c[8], dst[8];
+                float* orow = bcur + prow * LDA;
+                const float* crow = bother + prow * LDA;
+                zero_own_part(orow);
+                const int k = p.sample_k;
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) {
-                        const int q = q0 + u * kPT + tid;
-                        const int row = q / k, t = q - row * k;
-                        const int grow = tile * BM + row;
-                        const bool ok = q < total && grow < p.rows;
-                        const size_t off = ok ? (size_t)grow * k + t : 0;
-                        v[u] = p.compact[off];
-                        c[u] = p.sample_idx[off];
-                        dst[u] = ok ? row * LDA : -1;
-                    }
-#pragma unroll
-                    for (int u = 0; u < 8; ++u)
-                        if (dst[u] >= 0) bcur[dst[u] + c[u]] = v[u] + bother[dst[u] + c[u]];
+                for (int u = 0; u < kCP; ++u) {
+                    const int t = ppart + TPR * u;
+                    const int col = t < k ? (int)pr.c[u] : D;       // pairs past k land in the padding column
+                    orow[col] = pr.v[u] + crow[col];
                 }
-                __syncthreads();
-                for (int q = tid; q < BM * D; q += kPT) {
-                    const int row = q / D, c = q - row * D;
+                const size_t base = (size_t)min(tile * BM + prow, p.rows - 1) * k;
+                for (int u = kCP; u * TPR < k; ++u) {
+                    const int t = ppart + TPR * u;
+                    const float v = p.compact[base + min(t, k - 1)];
+                    const int c = p.sample_idx[base + min(t, k - 1)];
+                    const int col = t < k ? c : D;
+                    orow[col] = v + crow[col];
+                }
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int it = 0; it < F4; ++it) {
+                    const int q = it * kWave + lane;
+                    const int row = wave * RPW + q / (D / 4), c4 = (q % (D / 4)) * 4;
                     const int grow = tile * BM + row;
-                    if (grow < p.rows) p.out[(size_t)grow * D + c] = bcur[row * LDA + c];
+                    const float4 v = *reinterpret_cast<const float4*>(bcur + row * LDA + c4);
+                    if (grow < p.rows) *reinterpret_cast<float4*>(p.out + (size_t)grow * D + c4) = v;
                 }
-                __syncthreads();
+                __builtin_amdgcn_wave_barrier();
             }
-#pragma unroll
-            for (int j = 0; j < SPW; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[j][r] = 0.0f;
+            clear_acc();
+            __builtin_amdgcn_sched_barrier(0);
+            if (has_next) commit(ntile, bother);    // a wavefront overwrites only the C rows it has just consumed
+            __syncthreads();
+            if (!has_next) break;
+            tile = ntile; cur ^= 1;
         }
-        if (has_next) commit(ntile, nsg, bother);
-        __syncthreads();
-        if (!has_next) break;
-        tile = ntile; sg = nsg; cur ^= 1;
     }
 }
 
-template <int NT, int NSEG>
+template <int NT, int AK, int EPI>
 static int launch_proj(const GemmParams& p, hipStream_t s) {
     using C = ProjCfg<NT>;
     static bool configured = false;
     if (!configured) {
-        DRC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&proj_kernel<NT, NSEG>),
+        DRC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&proj_kernel<NT, AK, EPI>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::kLds));
         configured = true;
     }
     const int n_tiles = (p.rows + C::BM - 1) / C::BM;
-    int grid = 512;                                    // about two resident workgroups per CU
+    int grid = 512;                                    // two resident workgroups per CU
     if (grid > n_tiles) grid = n_tiles;
-    hipLaunchKernelGGL((proj_kernel<NT, NSEG>), dim3((unsigned)grid), dim3(kPT), C::kLds, s, p);
+    hipLaunchKernelGGL((proj_kernel<NT, AK, EPI>), dim3((unsigned)grid), dim3(kPT), C::kLds, s, p);
     DRC_HIP(hipGetLastError());
     return DR_OK;
+}
+
+template <int NT>
+static int launch_proj_nt(const GemmParams& p, int ak, hipStream_t s) {
+    const int key = ak * 10 + p.epi;
+    switch (key) {
+        case kADense * 10 + kEpiStore: return launch_proj<NT, kADense, kEpiStore>(p, s);
+        case kADense * 10 + kEpiMaxMerge: return launch_proj<NT, kADense, kEpiMaxMerge>(p, s);
+        case kADense * 10 + kEpiSampleDense: return launch_proj<NT, kADense, kEpiSampleDense>(p, s);
+        case kADenseMasked * 10 + kEpiStore: return launch_proj<NT, kADenseMasked, kEpiStore>(p, s);
+        case kADenseMasked * 10 + kEpiSampleDense: return launch_proj<NT, kADenseMasked, kEpiSampleDense>(p, s);
+        case kACbsrDense * 10 + kEpiStore: return launch_proj<NT, kACbsrDense, kEpiStore>(p, s);
+        default: return fail(DR_ERR_UNSUPPORTED, "projection operand kind %d with epilogue %d is not built", ak, p.epi);
+    }
 }
 
 int launch_gemm(const GemmOperand* segs, int nseg, int64_t rows, int D, GemmEpilogue epi, float* out,
@@ -293,27 +395,37 @@ int launch_gemm(const GemmOperand* segs, int nseg, int64_t rows, int D, GemmEpil
     p.sample_idx = sample_idx;
     p.sample_k = sample_k;
     p.compact = compact;
-    const int key = (D / 32) * 10 + nseg;
-    switch (key) {
-        case 11: return launch_proj<1, 1>(p, s);
-        case 12: return launch_proj<1, 2>(p, s);
-        case 21: return launch_proj<2, 1>(p, s);
-        case 22: return launch_proj<2, 2>(p, s);
-        case 31: return launch_proj<3, 1>(p, s);
-        case 32: return launch_proj<3, 2>(p, s);
-        case 41: return launch_proj<4, 1>(p, s);
-        case 42: return launch_proj<4, 2>(p, s);
+    int ak;
+    if (nseg == 2) {
+        if (!segs[0].cbsr_vals || !segs[0].cbsr_idx || segs[0].k < 1 || !segs[1].dense || segs[1].mask)
+            return fail(DR_ERR_UNSUPPORTED, "two-segment projection expects (CBSR, unmasked dense) operands");
+        ak = kACbsrDense;
+    } else if (nseg == 1 && segs[0].dense) {
+        ak = segs[0].mask ? kADenseMasked : kADense;
+    } else {
+        return fail(DR_ERR_UNSUPPORTED, "projection with %d segments / a lone CBSR operand is not built", nseg);
+    }
+    if (epi == kEpiSampleDense && (sample_k < 1 || !sample_idx || !compact))
+        return fail(DR_ERR_INVALID_ARG, "sampling epilogue without indices");
+    switch (D / 32) {
+        case 1: return launch_proj_nt<1>(p, ak, s);
+        case 2: return launch_proj_nt<2>(p, ak, s);
+        case 3: return launch_proj_nt<3>(p, ak, s);
+        case 4: return launch_proj_nt<4>(p, ak, s);
         default: return fail(DR_ERR_UNSUPPORTED, "projection width D = %d not in {32,64,96,128}", D);
     }
 }
 
 // ---------------------------------------------------------------------------------------------------
 // weight gradients  dW[D,D] = A^T B  (reduction over the graph's rows).  Persistent workgroups reduce a
-// contiguous slab of rows each: 32-row chunks of A and B are double-buffered through LDS, the full
-// D x D accumulator lives in MFMA registers (wavefront w owns row-tile w of dW), and the per-workgroup
-// partials are summed by a second kernel in a fixed order (deterministic, no atomics).
+// contiguous slab of rows each: 32-row chunks of A and B are double-buffered through LDS (loads of the
+// next chunk in flight during the multiply of the current one), the full D x D accumulator lives in MFMA
+// registers (wavefront w owns row-tile w of dW), and the per-workgroup partials are summed by a second
+// kernel in a fixed order (deterministic, no atomics).
 // ---------------------------------------------------------------------------------------------------
-constexpr int kWgRC = 32;  // rows staged per step
+constexpr int kWgRC = 32;                  // rows staged per step
+constexpr int kWgTPR = kPT / kWgRC;        // threads sharing one chunk row when A arrives as CBSR
+constexpr int kWgCP = 4;                   // CBSR pairs per thread prefetched into registers
 
 struct WgradParams {
     WgradOperand op;
@@ -322,12 +434,12 @@ struct WgradParams {
     float* scratch;
 };
 
-template <int NT>
+template <int NT, bool ACBSR, bool MASKED>
 __global__ __launch_bounds__(kPT) void wgrad_partial_kernel(WgradParams p) {
     constexpr int D = NT * 32;
     constexpr int LD = D + 4;
-    constexpr int F4 = kWgRC * D / 4 / kPT;      // float4 per thread per operand chunk (NT: 1..4)
-    extern __shared__ float smem[];
+    constexpr int F4 = kWgRC * D / 4 / kPT;      // float4 per thread per operand chunk (= NT)
+    extern __shared__ __align__(16) float smem[];
     float* const sA0 = smem;
     float* const sB0 = sA0 + kWgRC * LD;
     float* const sA1 = sB0 + kWgRC * LD;
@@ -336,6 +448,7 @@ __global__ __launch_bounds__(kPT) void wgrad_partial_kernel(WgradParams p) {
     const int rb = blockIdx.x * p.rows_per_block;
     const int re = min(rb + p.rows_per_block, p.rows);
     const bool mm = wave < NT;                   // wavefront w owns dW rows [32w, 32w+32)
+    const int prow = tid / kWgTPR, ppart = tid % kWgTPR;
 
     floatx16 acc[NT];
 #pragma unroll
@@ -346,6 +459,8 @@ __global__ __launch_bounds__(kPT) void wgrad_partial_kernel(WgradParams p) {
     // loads only (mask bytes raw); masking and range checks happen when the chunk is written to LDS
     float4 preA[F4], preB[F4];
     uint32_t prem[F4];
+    float pv[kWgCP];
+    uint32_t pc[kWgCP];
     auto prefetch = [&](int rr) {
 #pragma unroll
         for (int it = 0; it < F4; ++it) {
@@ -353,48 +468,66 @@ __global__ __launch_bounds__(kPT) void wgrad_partial_kernel(WgradParams p) {
             const int row = q / (D / 4), c4 = (q % (D / 4)) * 4;
             const size_t off = (size_t)min(rr + row, re - 1) * D + c4;
             preB[it] = *reinterpret_cast<const float4*>(p.op.b + off);
-            prem[it] = p.op.b_mask ? *reinterpret_cast<const uint32_t*>(p.op.b_mask + off) : 0u;
-            preA[it] = p.op.a_dense ? *reinterpret_cast<const float4*>(p.op.a_dense + off)
-                                    : make_float4(0.f, 0.f, 0.f, 0.f);
+            if (MASKED) prem[it] = *reinterpret_cast<const uint32_t*>(p.op.b_mask + off);
+            if (!ACBSR) preA[it] = *reinterpret_cast<const float4*>(p.op.a_dense + off);
+        }
+        if (ACBSR) {
+            const int k = p.op.k;
+            const size_t base = (size_t)min(rr + prow, re - 1) * k;
+#pragma unroll
+            for (int u = 0; u < kWgCP; ++u) {
+                const int t = min(ppart + kWgTPR * u, k - 1);
+                pv[u] = p.op.a_cbsr_vals[base + t];
+                pc[u] = p.op.a_cbsr_idx[base + t];
+            }
         }
     };
     auto commit = [&](int rr, float* sA, float* sB) {
         const uint32_t keep = (uint32_t)p.op.b_mask_keep;
-        const bool masked = p.op.b_mask != nullptr;
+        const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
         for (int it = 0; it < F4; ++it) {
             const int q = it * kPT + tid;
             const int row = q / (D / 4), c4 = (q % (D / 4)) * 4;
             const bool in = rr + row < re;
-            const uint32_t m = prem[it];
-            float4 vb, va;
-            vb.x = (in && (!masked || ((m >> 0) & 0xffu) == keep)) ? preB[it].x : 0.f;
-            vb.y = (in && (!masked || ((m >> 8) & 0xffu) == keep)) ? preB[it].y : 0.f;
-            vb.z = (in && (!masked || ((m >> 16) & 0xffu) == keep)) ? preB[it].z : 0.f;
-            vb.w = (in && (!masked || ((m >> 24) & 0xffu) == keep)) ? preB[it].w : 0.f;
-            va = in ? preA[it] : make_float4(0.f, 0.f, 0.f, 0.f);           // zeros when A is CBSR
+            float4 vb = preB[it];
+            if (MASKED) {
+                const uint32_t m = prem[it];
+                vb.x = (((m >> 0) & 0xffu) == keep) ? vb.x : 0.f;
+                vb.y = (((m >> 8) & 0xffu) == keep) ? vb.y : 0.f;
+                vb.z = (((m >> 16) & 0xffu) == keep) ? vb.z : 0.f;
+                vb.w = (((m >> 24) & 0xffu) == keep) ? vb.w : 0.f;
+            }
+            if (!in) vb = make_float4(0.f, 0.f, 0.f, 0.f);
             *reinterpret_cast<float4*>(sB + row * LD + c4) = vb;
-            *reinterpret_cast<float4*>(sA + row * LD + c4) = va;
+            if (!ACBSR) {
+                float4 va = preA[it];
+                if (!in) va = make_float4(0.f, 0.f, 0.f, 0.f);
+                *reinterpret_cast<float4*>(sA + row * LD + c4) = va;
+            }
         }
-        if (!p.op.a_dense) {
-            __syncthreads();
-            const int k = p.op.k, total = kWgRC * k;
-            for (int q0 = 0; q0 < total; q0 += 4 * kPT) {
-                float v[4];
-                int c[4], dst[4];
+        if (ACBSR) {
+            // row-owned: the kWgTPR threads of a row share a wavefront, which zeroes the row and then
+            // scatters the pairs into it (LDS keeps a wavefront's accesses in order); every write is
+            // unconditional, pairs past k go to the padding column
+            float* rowp = sA + prow * LD;
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int q = q0 + u * kPT + tid;
-                    const int row = q / k, t = q - row * k;
-                    const bool ok = q < total && rr + row < re;
-                    const size_t off = ok ? (size_t)(rr + row) * k + t : 0;
-                    v[u] = p.op.a_cbsr_vals[off];
-                    c[u] = p.op.a_cbsr_idx[off];
-                    dst[u] = ok ? row * LD : -1;
-                }
+            for (int i = 0; i < D / kWgTPR / 4; ++i)
+                *reinterpret_cast<float4*>(rowp + ppart * (D / kWgTPR) + 4 * i) = z;
+            __builtin_amdgcn_wave_barrier();
+            const int k = p.op.k;
+            const bool rin = rr + prow < re;
 #pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    if (dst[u] >= 0) sA[dst[u] + c[u]] = v[u];
+            for (int u = 0; u < kWgCP; ++u) {
+                const int t = ppart + kWgTPR * u;
+                rowp[t < k ? (int)pc[u] : D] = rin ? pv[u] : 0.f;
+            }
+            const size_t base = (size_t)min(rr + prow, re - 1) * k;
+            for (int u = kWgCP; u * kWgTPR < k; ++u) {
+                const int t = ppart + kWgTPR * u;
+                const float v = p.op.a_cbsr_vals[base + min(t, k - 1)];
+                const int c = p.op.a_cbsr_idx[base + min(t, k - 1)];
+                rowp[t < k ? c : D] = rin ? v : 0.f;
             }
         }
     };
@@ -409,6 +542,7 @@ __global__ __launch_bounds__(kPT) void wgrad_partial_kernel(WgradParams p) {
             const float* sA = cur ? sA1 : sA0;
             const float* sB = cur ? sB1 : sB0;
             if (has_next) prefetch(rr + kWgRC);
+            __builtin_amdgcn_sched_barrier(0);   // consumers of the prefetched registers stay below the multiply
             if (mm) {
                 // operands of k-step i+1 are read from LDS before the MFMAs of k-step i are issued
                 const float* pa = sA + (lane >> 5) * LD + wave * 32 + (lane & 31);
@@ -431,6 +565,7 @@ __global__ __launch_bounds__(kPT) void wgrad_partial_kernel(WgradParams p) {
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
+            __builtin_amdgcn_sched_barrier(0);
             if (has_next) commit(rr + kWgRC, cur ? sA0 : sA1, cur ? sB0 : sB1);
             __syncthreads();
             cur ^= 1;
@@ -476,21 +611,30 @@ static int wgrad_blocks(int64_t rows) {
 
 size_t wgrad_scratch_bytes(int64_t rows, int D) { return sizeof(float) * (size_t)wgrad_blocks(rows) * D * D; }
 
-template <int NT>
-static int launch_wgrad_nt(const WgradParams& p, int nb, hipStream_t s) {
+template <int NT, bool ACBSR, bool MASKED>
+static int launch_wgrad_kernel(const WgradParams& p, int nb, hipStream_t s) {
     constexpr size_t lds = sizeof(float) * 4 * kWgRC * (NT * 32 + 4);
     static bool configured = false;
     if (!configured) {
-        DRC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&wgrad_partial_kernel<NT>),
+        DRC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&wgrad_partial_kernel<NT, ACBSR, MASKED>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         configured = true;
     }
-    hipLaunchKernelGGL(wgrad_partial_kernel<NT>, dim3((unsigned)nb), dim3(kPT), lds, s, p);
+    hipLaunchKernelGGL((wgrad_partial_kernel<NT, ACBSR, MASKED>), dim3((unsigned)nb), dim3(kPT), lds, s, p);
     DRC_HIP(hipGetLastError());
     return DR_OK;
 }
 
+template <int NT>
+static int launch_wgrad_nt(const WgradParams& p, int nb, hipStream_t s) {
+    const bool cbsr = p.op.a_dense == nullptr, masked = p.op.b_mask != nullptr;
+    if (cbsr) return masked ? launch_wgrad_kernel<NT, true, true>(p, nb, s) : launch_wgrad_kernel<NT, true, false>(p, nb, s);
+    return masked ? launch_wgrad_kernel<NT, false, true>(p, nb, s) : launch_wgrad_kernel<NT, false, false>(p, nb, s);
+}
+
 int launch_wgrad(const WgradOperand& op, int64_t rows, int D, float* dW, void* scratch, hipStream_t s) {
+    if (!op.a_dense && (!op.a_cbsr_vals || !op.a_cbsr_idx || op.k < 1))
+        return fail(DR_ERR_INVALID_ARG, "weight gradient without an A operand");
     int nb = wgrad_blocks(rows);
     int rpb = (int)((rows + nb - 1) / nb);
     rpb = (rpb + kWgRC - 1) / kWgRC * kWgRC;
