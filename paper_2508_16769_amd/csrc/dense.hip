@@ -90,13 +90,11 @@ __global__ __launch_bounds__(kPT, (AK == kACbsrDense ? 1 : 2)) void proj_kernel(
     float breg[NSEG][KS];
 #pragma unroll
     for (int sg = 0; sg < NSEG; ++sg) {
-        const float* W = p.seg[sg].W;
-        const bool tr = p.seg[sg].transpose_w != 0;
+        // B[kk][n] = W[kk][n], or W[n][kk] for the transposed use: one strided load per element, no branches
+        const int sk = p.seg[sg].transpose_w ? 1 : D, sn = p.seg[sg].transpose_w ? D : 1;
+        const float* W = p.seg[sg].W + (32 * ct + (lane & 31)) * sn;
 #pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            const int kk = mfma_k(s, lane >> 5), n = 32 * ct + (lane & 31);
-            breg[sg][s] = mm ? (tr ? W[(size_t)n * D + kk] : W[(size_t)kk * D + n]) : 0.f;
-        }
+        for (int s = 0; s < KS; ++s) breg[sg][s] = W[mfma_k(s, lane >> 5) * sk];
     }
 
     floatx16 acc[SPW];
@@ -218,13 +216,23 @@ __global__ __launch_bounds__(kPT, (AK == kACbsrDense ? 1 : 2)) void proj_kernel(
     };
     auto store_tile = [&](int tile) {                  // out[rows, D] = C
         if (!mm) return;
+        // one pointer per sub-tile; the 16 rows a lane holds sit at fixed offsets from it
+        const int row0 = tile * BM + rg * SPW * 32 + 4 * (lane >> 5);
+        float* const o = p.out + (size_t)row0 * D + 32 * ct + (lane & 31);
+        if (tile * BM + BM <= p.rows) {                // whole tile in range (all but the last tile)
 #pragma unroll
-        for (int j = 0; j < SPW; ++j)
+            for (int j = 0; j < SPW; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = tile * BM + (rg * SPW + j) * 32 + mfma_row(lane, r);
-                if (row < p.rows) p.out[(size_t)row * D + 32 * ct + (lane & 31)] = acc[j][r];
-            }
+                for (int r = 0; r < 16; ++r) o[(j * 32 + 8 * (r >> 2) + (r & 3)) * D] = acc[j][r];
+        } else {
+#pragma unroll
+            for (int j = 0; j < SPW; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int dr = j * 32 + 8 * (r >> 2) + (r & 3);
+                    if (row0 + dr < p.rows) o[dr * D] = acc[j][r];
+                }
+        }
     };
 
     if constexpr (AK == kACbsrDense) {
@@ -269,14 +277,26 @@ __global__ __launch_bounds__(kPT, (AK == kACbsrDense ? 1 : 2)) void proj_kernel(
             PairRegs pr;
             float prev[SPW][16];
             if constexpr (EPI == kEpiSampleDense) load_pairs(pr, p.compact, p.sample_idx, p.sample_k, tile);
-            if constexpr (EPI == kEpiMaxMerge) {            // the other branch's values (rows clamped, all wavefronts)
+            // C rows of this lane: row0 + j*32 + 8*(r/4) + r%4, all at fixed offsets from one pointer
+            const int row0 = tile * BM + rg * SPW * 32 + 4 * (lane >> 5);
+            const size_t off0 = (size_t)row0 * D + 32 * ct + (lane & 31);
+            const bool full = tile * BM + BM <= p.rows;     // whole tile in range (all but the last tile)
+            if constexpr (EPI == kEpiMaxMerge) {            // the other branch's values (all wavefronts)
+                const float* po = p.out + off0;
+                if (full) {
 #pragma unroll
-                for (int j = 0; j < SPW; ++j)
+                    for (int j = 0; j < SPW; ++j)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int row = min(tile * BM + (rg * SPW + j) * 32 + mfma_row(lane, r), p.rows - 1);
-                        prev[j][r] = p.out[(size_t)row * D + 32 * ct + (lane & 31)];
-                    }
+                        for (int r = 0; r < 16; ++r) prev[j][r] = po[(j * 32 + 8 * (r >> 2) + (r & 3)) * D];
+                } else {
+#pragma unroll
+                    for (int j = 0; j < SPW; ++j)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const int row = min(row0 + j * 32 + 8 * (r >> 2) + (r & 3), p.rows - 1);
+                            prev[j][r] = p.out[(size_t)row * D + 32 * ct + (lane & 31)];
+                        }
+                }
             }
             if (has_next) prefetch(ntile);
             __builtin_amdgcn_sched_barrier(0);   // consumers of the registers loaded above stay below the multiply
@@ -287,17 +307,18 @@ __global__ __launch_bounds__(kPT, (AK == kACbsrDense ? 1 : 2)) void proj_kernel(
             } else if constexpr (EPI == kEpiMaxMerge) {
                 // mask = [near >= pinned]; out keeps the near value unless the pinned one is larger
                 if (mm) {
+                    float* const o = p.out + off0;
+                    uint8_t* const mo = p.mask_out + off0;
 #pragma unroll
                     for (int j = 0; j < SPW; ++j)
 #pragma unroll
                         for (int r = 0; r < 16; ++r) {
-                            const int row = tile * BM + (rg * SPW + j) * 32 + mfma_row(lane, r);
+                            const int dr = j * 32 + 8 * (r >> 2) + (r & 3);
                             const float c = acc[j][r];
                             const bool near_wins = prev[j][r] >= c;
-                            if (row < p.rows) {
-                                const size_t off = (size_t)row * D + 32 * ct + (lane & 31);
-                                p.mask_out[off] = near_wins ? 1 : 0;
-                                if (!near_wins) p.out[off] = c;
+                            if (full || row0 + dr < p.rows) {
+                                mo[dr * D] = near_wins ? 1 : 0;
+                                if (!near_wins) o[dr * D] = c;
                             }
                         }
                 }
