@@ -1,6 +1,7 @@
-"""Parity at the benchmark's full size (1.2 M cells, 0.9 M nets, D = 128, k = 32, the launch configuration
-bench.py times): the HIP layer runs on the whole graph, the oracle recomputes a random sample of output rows
-one by one from induced sub-problems (every edge of the sampled rows, exact full-graph edge values)."""
+"""Parity at the benchmark's full size (1.2 M cells, 0.9 M nets, D = 128, k swept over 8, 16, 32, 64, the
+launch configuration bench.py times): the HIP layer runs on the whole graph, the oracle recomputes a random
+sample of output rows one by one from induced sub-problems (every edge of the sampled rows, exact full-graph
+edge values)."""
 import numpy as np
 import pytest
 import torch
@@ -37,46 +38,51 @@ def oracle_forward_rows(rel, rows, X_src, k, D):
 
 
 @pytest.fixture(scope="module")
-def large_run():
+def large_inputs():
     w = workload("large")
-    D, k = w["D"], w["k"]
     say("large: generating graph and tensors")
     g = make_graph("large", seed=0)
-    T = make_tensors(g.Nc, g.Nn, D, seed=0)
+    T = make_tensors(g.Nc, g.Nn, w["D"], seed=0)
     say("large: device setup")
-    near = P.device_relation(g.near, P.DR_NORM_MEAN)
-    pins = P.device_relation(g.pins, P.DR_NORM_MEAN)
-    pinned = P.device_relation(g.pinned, P.DR_NORM_SYM)
-    layer = P.HeteroConv(near, pins, pinned, D, k, k)
+    dev_rel = dict(near=P.device_relation(g.near, P.DR_NORM_MEAN), pins=P.device_relation(g.pins, P.DR_NORM_MEAN),
+                   pinned=P.device_relation(g.pinned, P.DR_NORM_SYM))
+    say("large: oracle edge values and transposes")
+    rel = dict(near=oracle.relation(g.near, oracle.NORM_MEAN), pins=oracle.relation(g.pins, oracle.NORM_MEAN),
+               pinned=oracle.relation(g.pinned, oracle.NORM_SYM))
+    tr = {n: oracle.csr_transpose(rel[n].M, rel[n].N, rel[n].rowptr, rel[n].colidx, rel[n].vals) for n in rel}
+    dT = dict(X_cell=dev(T.X_cell), X_net=dev(T.X_net), dY_cell=dev(T.dY_cell), dY_net=dev(T.dY_net),
+              W={n: dev(T.W[n]) for n in P.WEIGHT_NAMES})
+    return dict(g=g, T=T, D=w["D"], rel=rel, tr=tr, dev_rel=dev_rel, dT=dT)
+
+
+@pytest.fixture(scope="module", params=[32, 8, 16, 64], ids=lambda k: f"k{k}")
+def large_run(request, large_inputs):
+    li = large_inputs
+    g, D, k, dT = li["g"], li["D"], request.param, li["dT"]
+    layer = P.HeteroConv(li["dev_rel"]["near"], li["dev_rel"]["pins"], li["dev_rel"]["pinned"], D, k, k)
     saved = layer.alloc_saved()
-    Wd = {n: dev(T.W[n]) for n in P.WEIGHT_NAMES}
     Y_cell = torch.empty((g.Nc, D), dtype=torch.float32, device="cuda")
     Y_net = torch.empty((g.Nn, D), dtype=torch.float32, device="cuda")
     dX_cell, dX_net = torch.empty_like(Y_cell), torch.empty_like(Y_net)
     dW = {n: torch.empty((D, D), dtype=torch.float32, device="cuda") for n in P.WEIGHT_NAMES}
-    say("large: heteroconv_fwd + heteroconv_bwd")
-    layer.heteroconv_fwd(dev(T.X_cell), dev(T.X_net), Wd, Y_cell, Y_net, saved)
-    layer.heteroconv_bwd(dev(T.dY_cell), dev(T.dY_net), Wd, saved, dX_cell, dX_net, dW)
+    say(f"large k={k}: heteroconv_fwd + heteroconv_bwd")
+    layer.heteroconv_fwd(dT["X_cell"], dT["X_net"], dT["W"], Y_cell, Y_net, saved)
+    layer.heteroconv_bwd(dT["dY_cell"], dT["dY_net"], dT["W"], saved, dX_cell, dX_net, dW)
     torch.cuda.synchronize()
-    say("large: oracle edge values and transposes")
-    rel = dict(near=oracle.relation(g.near, oracle.NORM_MEAN), pins=oracle.relation(g.pins, oracle.NORM_MEAN),
-               pinned=oracle.relation(g.pinned, oracle.NORM_SYM))
-    out = dict(g=g, T=T, D=D, k=k, rel=rel, saved=saved, Y_cell=Y_cell, Y_net=Y_net, dX_cell=dX_cell, dX_net=dX_net,
-               dW=dW, dev_rel=dict(near=near, pins=pins, pinned=pinned), layer=layer)
+    out = dict(li, k=k, saved=saved, Y_cell=Y_cell, Y_net=Y_net, dX_cell=dX_cell, dX_net=dX_net, dW=dW, layer=layer)
     yield out
     layer.heteroconv_destroy()
 
 
-def test_large_setup_is_bit_exact(large_run):
-    r = large_run
+def test_large_setup_is_bit_exact(large_inputs):
+    r = large_inputs
     for name in ("near", "pins", "pinned"):
         say(f"large.{name}: edge values")
         assert np.array_equal(r["dev_rel"][name].vals.cpu().numpy().view(np.uint32), r["rel"][name].vals.view(np.uint32))
     # transposes held by the context, compared on sampled rows of A^T through a backward SpMM below; here the
     # row pointers of a device transpose are checked in full (integer-exact)
     At = P.device_transpose(r["dev_rel"]["pins"])
-    rel = r["rel"]["pins"]
-    o_rp, o_ci, o_v = oracle.csr_transpose(rel.M, rel.N, rel.rowptr, rel.colidx, rel.vals)
+    o_rp, o_ci, o_v = r["tr"]["pins"]
     assert np.array_equal(At.rowptr.cpu().numpy(), o_rp)
     assert np.array_equal(At.colidx.cpu().numpy(), o_ci)
     assert np.array_equal(At.vals.cpu().numpy().view(np.uint32), o_v.view(np.uint32))
@@ -145,7 +151,7 @@ def test_large_backward_sampled_rows(large_run):
     rng = np.random.default_rng(321)
     Xc, Xn = T.X_cell, T.X_net
     W = {n: T.W[n].astype(np.float64) for n in T.W}
-    tr = {n: oracle.csr_transpose(rel[n].M, rel[n].N, rel[n].rowptr, rel[n].colidx, rel[n].vals) for n in rel}
+    tr = r["tr"]
 
     def t_rows(name, rows):          # rows of A^T: (sub rowptr, destination ids, values)
         rp, ci, v = tr[name]
