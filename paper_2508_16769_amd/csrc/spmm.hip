@@ -6,9 +6,10 @@
 //     row's edges in storage order, so 8 rows are in flight per wavefront (the wave64 counterpart of the
 //     paper's "partition the warp into parts, one neighbour each") and every row sum has one fixed
 //     order: results are reproducible bit for bit.
-//   * The block's rows are ranked by degree and dealt to the groups in that order, boustrophedon, so the
-//     rows the groups hold at any time have (nearly) equal degree -- the paper's degree classes, resolved
-//     per block -- and the per-group totals come out balanced.
+//   * The block's rows are ranked by degree, longest first, and a group that finishes a row takes the
+//     next undealt one (a counter in LDS): the long rows start early, the short ones fill the gaps, and
+//     the per-group totals come out balanced -- the paper's degree classes, resolved per block at run
+//     time.  Which group sums a row does not change the order of that row's sum.
 //   * Rows with more than kSolo edges are not given to one group: all 8 groups stride over their edges
 //     into per-group partial sums that are then added in a fixed order (high-fanout nets, the tail of
 //     the power-law `near` degrees).
