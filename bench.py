@@ -262,7 +262,7 @@ def main() -> int:
         "kernels": kernels,
     }
     if not args.no_cpu_baseline:
-        scale = args.cpu_scale or max(1, g.Nc // 48000)
+        scale = args.cpu_scale or max(1, g.Nc // 200000)     # about 10-15 s of single-thread oracle work
         out["cpu_baseline"] = cpu_baseline(args.workload, D, k, scale)
     layer.heteroconv_destroy()
     print(json.dumps(out), flush=True)

@@ -230,10 +230,11 @@ LAYER_CASES = [
     ("tiny", 0, {}),                                               # 2048 cells, D=64, k=16
     ("tiny", 1, dict(Nc=1500, Nn=1000, grid=(50, 30), D=128, k=32)),  # ragged against the 128-row tiles
     ("tiny", 2, dict(Nc=333, Nn=90, grid=(37, 9), D=32, k=5)),
+    ("small", 0, {}),                                              # 60 000 cells, 40 000 nets, D=64, k=16
 ]
 
 
-@pytest.mark.parametrize("name,seed,override", LAYER_CASES, ids=["tiny", "ragged128", "odd32"])
+@pytest.mark.parametrize("name,seed,override", LAYER_CASES, ids=["tiny", "ragged128", "odd32", "small"])
 def test_heteroconv_fwd_bwd_parity(name, seed, override):
     w, g, T = _layer_case(name, seed, **override)
     D, k = w["D"], w["k"]
