@@ -37,7 +37,7 @@ __global__ __launch_bounds__(256) void topk_rows_kernel(const float* __restrict_
     auto load_row = [&](float (&dst)[EPL], int row) {
         const float* x = X + (size_t)min(row, n - 1) * D;
 #pragma unroll
-        for (int s = 0; s < EPL; ++s) dst[s] = x[min(s * kWave + lane, D - 1)];
+        for (int s = 0; s < EPL; ++s) dst[s] = __builtin_nontemporal_load(x + min(s * kWave + lane, D - 1));   // read once
     };
     auto select_row = [&](const float (&val)[EPL], int row) {
         uint32_t key[EPL];
