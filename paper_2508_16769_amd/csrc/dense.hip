@@ -69,6 +69,16 @@ __device__ __forceinline__ int mfma_row(int lane, int r) { return 8 * (r >> 2) +
 // 16-byte LDS read.  The B registers are loaded in the same order.
 __device__ __forceinline__ int mfma_k(int s, int h) { return 8 * (s >> 2) + 4 * h + (s & 3); }
 
+// 16-byte load that does not displace cached lines (the four scalar loads merge into one instruction)
+__device__ __forceinline__ float4 nt_load4(const float* p) {
+    float4 v;
+    v.x = __builtin_nontemporal_load(p);
+    v.y = __builtin_nontemporal_load(p + 1);
+    v.z = __builtin_nontemporal_load(p + 2);
+    v.w = __builtin_nontemporal_load(p + 3);
+    return v;
+}
+
 template <int NT, int AK, int EPI>
 __global__ __launch_bounds__(kPT, (AK == kACbsrDense ? 1 : 2)) void proj_kernel(GemmParams p) {
     using C = ProjCfg<NT>;
@@ -114,8 +124,8 @@ __global__ __launch_bounds__(kPT, (AK == kACbsrDense ? 1 : 2)) void proj_kernel(
             const int q = it * kWave + lane;
             const int row = wave * RPW + q / (D / 4), c4 = (q % (D / 4)) * 4;
             const size_t off = (size_t)min(tile * BM + row, p.rows - 1) * D + c4;
-            pre[it] = *reinterpret_cast<const float4*>(od.dense + off);
-            if (kMasked) prem[it] = *reinterpret_cast<const uint32_t*>(od.mask + off);
+            pre[it] = nt_load4(od.dense + off);                         // operand rows are read once: streamed
+            if (kMasked) prem[it] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(od.mask + off));
         }
     };
     auto commit = [&](int tile, float* b) {
@@ -223,7 +233,7 @@ __global__ __launch_bounds__(kPT, (AK == kACbsrDense ? 1 : 2)) void proj_kernel(
 #pragma unroll
             for (int j = 0; j < SPW; ++j)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) o[(j * 32 + 8 * (r >> 2) + (r & 3)) * D] = acc[j][r];
+                for (int r = 0; r < 16; ++r) __builtin_nontemporal_store(acc[j][r], o + (j * 32 + 8 * (r >> 2) + (r & 3)) * D);
         } else {
 #pragma unroll
             for (int j = 0; j < SPW; ++j)
@@ -358,7 +368,7 @@ __global__ __launch_bounds__(kPT, (AK == kACbsrDense ? 1 : 2)) void proj_kernel(
                     const int row = wave * RPW + q / (D / 4), c4 = (q % (D / 4)) * 4;
                     const int grow = tile * BM + row;
                     const float4 v = *reinterpret_cast<const float4*>(bcur + row * LDA + c4);
-                    if (grow < p.rows) *reinterpret_cast<float4*>(p.out + (size_t)grow * D + c4) = v;
+                    if (grow < p.rows) { float* oo = p.out + (size_t)grow * D + c4; __builtin_nontemporal_store(v.x, oo); __builtin_nontemporal_store(v.y, oo + 1); __builtin_nontemporal_store(v.z, oo + 2); __builtin_nontemporal_store(v.w, oo + 3); }
                 }
                 __builtin_amdgcn_wave_barrier();
             }

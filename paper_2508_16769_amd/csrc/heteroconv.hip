@@ -271,14 +271,23 @@ int heteroconv_fwd(dr_heteroconv* c, const float* X_cell, const float* X_net, co
     DRC_HIP(hipEventRecord(c->ev_fork, user));
     for (int i = 0; i < 3; ++i) DRC_HIP(hipStreamWaitEvent(c->st[i], c->ev_fork, 0));
 
-    // D-ReLU of both node types
-    { ScopedTiming tm(c, kTopkCell, s_near); DRC_TRY(launch_topk(X_cell, c->Nc, D, c->k_cell, S->vals_cell, S->idx_cell, s_near)); }
-    DRC_HIP(hipEventRecord(c->ev_topk_cell, s_near));
+    // Enqueue order (it is the execution order when all relations share one stream): every D-ReLU output is
+    // gathered right after it is written, while it is still resident in the memory-side cache; the random
+    // relations (pinned, pins) come before the grid-local one, and the streaming projections last.
+
+    // D-ReLU(net), then pinned: net -> cell
     { ScopedTiming tm(c, kTopkNet, s_pinned); DRC_TRY(launch_topk(X_net, c->Nn, D, c->k_net, S->vals_net, S->idx_net, s_pinned)); }
     DRC_HIP(hipEventRecord(c->ev_topk_net, s_pinned));
+    { ScopedTiming tm(c, kFwdPinned, s_pinned); DRC_TRY(launch_spmm_fwd(&c->A[2], S->vals_net, S->idx_net, D, c->k_net, S->H_pinned, s_pinned)); }
 
-    // near: cell -> cell
+    // D-ReLU(cell), then pins: cell -> net and near: cell -> cell
+    { ScopedTiming tm(c, kTopkCell, s_near); DRC_TRY(launch_topk(X_cell, c->Nc, D, c->k_cell, S->vals_cell, S->idx_cell, s_near)); }
+    DRC_HIP(hipEventRecord(c->ev_topk_cell, s_near));
+    DRC_HIP(hipStreamWaitEvent(s_pins, c->ev_topk_cell, 0));
+    { ScopedTiming tm(c, kFwdPins, s_pins); DRC_TRY(launch_spmm_fwd(&c->A[1], S->vals_cell, S->idx_cell, D, c->k_cell, S->H_pins, s_pins)); }
     { ScopedTiming tm(c, kFwdNear, s_near); DRC_TRY(launch_spmm_fwd(&c->A[0], S->vals_cell, S->idx_cell, D, c->k_cell, S->H_near, s_near)); }
+
+    // projections: near (self + neighbour), pins (self + neighbour), pinned merged into Y_cell by max
     {
         GemmOperand seg[2] = {};
         seg[0].cbsr_vals = S->vals_cell; seg[0].cbsr_idx = S->idx_cell; seg[0].k = c->k_cell; seg[0].W = W->self_near;
@@ -286,10 +295,6 @@ int heteroconv_fwd(dr_heteroconv* c, const float* X_cell, const float* X_net, co
         { ScopedTiming tm(c, kProjNear, s_near); DRC_TRY(launch_gemm(seg, 2, c->Nc, D, kEpiStore, Y_cell, nullptr, nullptr, 0, nullptr, s_near)); }
     }
     DRC_HIP(hipEventRecord(c->ev_near, s_near));
-
-    // pins: cell -> net
-    DRC_HIP(hipStreamWaitEvent(s_pins, c->ev_topk_cell, 0));
-    { ScopedTiming tm(c, kFwdPins, s_pins); DRC_TRY(launch_spmm_fwd(&c->A[1], S->vals_cell, S->idx_cell, D, c->k_cell, S->H_pins, s_pins)); }
     DRC_HIP(hipStreamWaitEvent(s_pins, c->ev_topk_net, 0));
     {
         GemmOperand seg[2] = {};
@@ -298,9 +303,6 @@ int heteroconv_fwd(dr_heteroconv* c, const float* X_cell, const float* X_net, co
         { ScopedTiming tm(c, kProjPins, s_pins); DRC_TRY(launch_gemm(seg, 2, c->Nn, D, kEpiStore, Y_net, nullptr, nullptr, 0, nullptr, s_pins)); }
     }
     DRC_HIP(hipEventRecord(c->ev_pins, s_pins));
-
-    // pinned: net -> cell, merged into Y_cell by max once the near branch is there
-    { ScopedTiming tm(c, kFwdPinned, s_pinned); DRC_TRY(launch_spmm_fwd(&c->A[2], S->vals_net, S->idx_net, D, c->k_net, S->H_pinned, s_pinned)); }
     DRC_HIP(hipStreamWaitEvent(s_pinned, c->ev_near, 0));
     {
         GemmOperand seg[1] = {};

@@ -28,10 +28,9 @@ import os
 # (label, substring the dispatched kernel's name must contain) in single-stream dispatch order of one
 # forward + backward step
 SCHEDULE = (
-    ("dr_topk.cell", "topk_rows"), ("dr_topk.net", "topk_rows"),
-    ("dr_spmm_fwd.near", "spmm_fwd"), ("proj.near", "proj_kernel"),
-    ("dr_spmm_fwd.pins", "spmm_fwd"), ("proj.pins", "proj_kernel"),
-    ("dr_spmm_fwd.pinned", "spmm_fwd"), ("proj.pinned+merge", "proj_kernel"),
+    ("dr_topk.net", "topk_rows"), ("dr_spmm_fwd.pinned", "spmm_fwd"),
+    ("dr_topk.cell", "topk_rows"), ("dr_spmm_fwd.pins", "spmm_fwd"), ("dr_spmm_fwd.near", "spmm_fwd"),
+    ("proj.near", "proj_kernel"), ("proj.pins", "proj_kernel"), ("proj.pinned+merge", "proj_kernel"),
     ("dproj.near", "proj_kernel"), ("dr_spmm_bwd.near", "spmm_bwd"),
     ("wgrad.neigh_near", "wgrad_partial"), ("wgrad.neigh_near.reduce", "wgrad_reduce"),
     ("wgrad.self_near", "wgrad_partial"), ("wgrad.self_near.reduce", "wgrad_reduce"),
