@@ -213,6 +213,63 @@ int heteroconv_num_kernels(void);
 const char* heteroconv_kernel_name(int id);
 int heteroconv_kernel_times(dr_heteroconv* ctx, double* ms_sum, int64_t* launches, int n);
 
+/* ------------------------------------------------------------------------------------------------
+ * Multi-layer training step (paper Section 4.1: stacked HeteroConv layers with ReLU between them, a
+ * per-cell congestion read-out, mean-squared error, Adam with weight decay), over a batch of independent
+ * sub-graphs that share the parameters and are processed concurrently on HIP streams (Section 3.4).
+ *
+ *   X^(0) = input;  (Y_cell, Y_net) = HeteroConv_l(X^(l-1));  X^(l) = ReLU(Y) for l < L,  X^(L) = Y;
+ *   pred_i = X_cell^(L)[i,:] . w_head;   loss = mean over all cells of the batch of (pred_i - target_i)^2.
+ *
+ * Parameters: one flat device vector theta of hgnn_num_params(L, D) = L*5*D*D + D floats,
+ *   [layer 1: self_near, neigh_near, self_pins, neigh_pins, pinned (each [D,D] row-major) | layer 2 | ... | w_head[D]].
+ * ---------------------------------------------------------------------------------------------- */
+
+typedef struct dr_hgnn dr_hgnn;               /* opaque: activations, saved state and gradients of every sub-graph */
+
+typedef struct dr_hgnn_layer_buffers {        /* device pointers owned by the model, for inspection */
+    const float* X_cell;                      /* [Nc,D] input of the layer (caller's X for layer 0)              */
+    const float* X_net;                       /* [Nn,D]                                                          */
+    const float* Y_cell;                      /* [Nc,D] output of the layer, after ReLU unless it is the last    */
+    const float* Y_net;                       /* [Nn,D]                                                          */
+    dr_heteroconv_saved saved;                /* what the layer's forward saved                                  */
+    const float* dY_cell;                     /* [Nc,D] gradient that entered the layer's backward               */
+    const float* dY_net;                      /* [Nn,D]                                                          */
+    const float* dX_cell;                     /* [Nc,D] gradient the layer's backward produced; for layers > 0   */
+    const float* dX_net;                      /* [Nn,D] already gated by the ReLU in front of the layer          */
+    dr_heteroconv_wgrads dW;                  /* this sub-graph's share of the layer's weight gradients          */
+} dr_hgnn_layer_buffers;
+
+int64_t hgnn_num_params(int32_t n_layers, int32_t D);
+
+/*
+ * Build the model state for n_graphs sub-graphs (one heteroconv context each, all with the same D and k)
+ * and n_layers layers: allocates every activation, saved-state and gradient buffer and one stream per
+ * sub-graph.  The contexts stay owned by the caller and must outlive the model.  Synchronises the device.
+ */
+int hgnn_create(dr_hgnn** model, int32_t n_graphs, dr_heteroconv* const* graphs, int32_t n_layers);
+
+/*
+ * One training step.  X_cell[g] / X_net[g] / target[g]: host arrays of n_graphs device pointers
+ * ([Nc_g,D], [Nn_g,D], [Nc_g]).  theta, adam_m, adam_v: device vectors of hgnn_num_params floats, updated in
+ * place (step = 1 for the first update; moments start at zero); the hyper-parameters are doubles so that
+ * 1 - beta and the bias corrections are formed exactly before they are rounded to the fp32 the kernel uses.  grad_out: device vector of the same
+ * length that receives the batch gradient (before weight decay).  loss_out: one device float.
+ * Work is forked from `stream` onto one stream per sub-graph (and the relation streams below them) and
+ * joined back before the parameter update; the host never waits.
+ */
+int hgnn_train_step(dr_hgnn* model, const float* const* X_cell, const float* const* X_net,
+                    const float* const* target, float* theta, float* adam_m, float* adam_v,
+                    double lr, double beta1, double beta2, double eps, double weight_decay, int32_t step,
+                    float* grad_out, float* loss_out, void* stream);
+
+/* Buffers of sub-graph `graph`, layer `layer` (valid after a step).  pred / dpred: [Nc] of that sub-graph
+ * (layer argument ignored), may be NULL. */
+int hgnn_get_layer_buffers(const dr_hgnn* model, int32_t graph, int32_t layer, dr_hgnn_layer_buffers* out,
+                           const float** pred, const float** dpred);
+
+int hgnn_destroy(dr_hgnn* model);
+
 #ifdef __cplusplus
 }
 #endif

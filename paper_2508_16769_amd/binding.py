@@ -10,7 +10,7 @@ from __future__ import annotations
 import ctypes
 import os
 from dataclasses import dataclass
-from typing import Dict, Optional
+from typing import Dict, Optional, Sequence
 
 import torch
 
@@ -35,6 +35,7 @@ EXPORTS = (
     "heteroconv_create", "heteroconv_fwd", "heteroconv_bwd", "heteroconv_get_transpose", "heteroconv_destroy",
     "heteroconv_profile", "heteroconv_num_kernels", "heteroconv_kernel_name", "heteroconv_kernel_times",
     "heteroconv_set_overlap",
+    "hgnn_num_params", "hgnn_create", "hgnn_train_step", "hgnn_get_layer_buffers", "hgnn_destroy",
 )
 
 
@@ -89,6 +90,7 @@ def load() -> ctypes.CDLL:
         lib.dr_csr_transpose_workspace_bytes.restype = ctypes.c_size_t
         lib.dr_csr_normalize_workspace_bytes.restype = ctypes.c_size_t
         lib.heteroconv_kernel_name.restype = ctypes.c_char_p
+        lib.hgnn_num_params.restype = ctypes.c_int64
         _lib = lib
     return _lib
 
@@ -250,5 +252,82 @@ class HeteroConv:
     def __del__(self):
         try:
             self.heteroconv_destroy()
+        except Exception:
+            pass
+
+
+class dr_hgnn_layer_buffers(ctypes.Structure):
+    _fields_ = [("X_cell", ctypes.c_void_p), ("X_net", ctypes.c_void_p), ("Y_cell", ctypes.c_void_p),
+                ("Y_net", ctypes.c_void_p), ("saved", dr_heteroconv_saved), ("dY_cell", ctypes.c_void_p),
+                ("dY_net", ctypes.c_void_p), ("dX_cell", ctypes.c_void_p), ("dX_net", ctypes.c_void_p),
+                ("dW", dr_heteroconv_weights)]
+
+
+def hgnn_num_params(n_layers: int, D: int) -> int:
+    return int(load().hgnn_num_params(ctypes.c_int32(n_layers), ctypes.c_int32(D)))
+
+
+def _view(ptr: int, shape, dtype) -> torch.Tensor:
+    """Copy of a library-owned device buffer as a tensor (device-to-device through the HIP runtime)."""
+    t = torch.empty(shape, dtype=dtype, device="cuda")
+    if t.numel():
+        rc = hip_runtime().hipMemcpy(ctypes.c_void_p(t.data_ptr()), ctypes.c_void_p(ptr),
+                                     ctypes.c_size_t(t.numel() * t.element_size()), ctypes.c_int(3))
+        if rc != 0:
+            raise RuntimeError(f"hipMemcpy failed with {rc}")
+    return t
+
+
+class Hgnn:
+    """Owner of a ``dr_hgnn*`` model state (hgnn_create / hgnn_destroy) over a batch of sub-graph contexts."""
+
+    def __init__(self, graphs: Sequence["HeteroConv"], n_layers: int):
+        self._graphs = list(graphs)
+        self.n_layers, self.D, self.k = n_layers, graphs[0].D, graphs[0].k_cell
+        self._model = ctypes.c_void_p(0)
+        arr = (ctypes.c_void_p * len(graphs))(*[g._ctx.value for g in graphs])
+        _check(load().hgnn_create(ctypes.byref(self._model), ctypes.c_int32(len(graphs)), arr, ctypes.c_int32(n_layers)))
+
+    def hgnn_train_step(self, X_cell, X_net, target, theta, adam_m, adam_v, lr, beta1, beta2, eps, weight_decay, step,
+                        grad_out, loss_out, stream=None) -> None:
+        n = len(self._graphs)
+        tabs = [(ctypes.c_void_p * n)(*[t.data_ptr() for t in lst]) for lst in (X_cell, X_net, target)]
+        _check(load().hgnn_train_step(self._model, tabs[0], tabs[1], tabs[2], _ptr(theta), _ptr(adam_m), _ptr(adam_v),
+                                      ctypes.c_double(lr), ctypes.c_double(beta1), ctypes.c_double(beta2),
+                                      ctypes.c_double(eps), ctypes.c_double(weight_decay), ctypes.c_int32(step),
+                                      _ptr(grad_out), _ptr(loss_out), _stream(stream)))
+
+    def hgnn_get_layer_buffers(self, graph: int, layer: int) -> Dict[str, torch.Tensor]:
+        """Copies of the model's buffers for one sub-graph and layer (synchronises)."""
+        torch.cuda.synchronize()
+        b = dr_hgnn_layer_buffers()
+        pred, dpred = ctypes.c_void_p(0), ctypes.c_void_p(0)
+        _check(load().hgnn_get_layer_buffers(self._model, ctypes.c_int32(graph), ctypes.c_int32(layer), ctypes.byref(b),
+                                             ctypes.byref(pred), ctypes.byref(dpred)))
+        g = self._graphs[graph]
+        Nc, Nn, D, k = g.Nc, g.Nn, self.D, self.k
+        f32 = torch.float32
+        out = dict(
+            X_cell=_view(b.X_cell, (Nc, D), f32), X_net=_view(b.X_net, (Nn, D), f32),
+            Y_cell=_view(b.Y_cell, (Nc, D), f32), Y_net=_view(b.Y_net, (Nn, D), f32),
+            dY_cell=_view(b.dY_cell, (Nc, D), f32), dY_net=_view(b.dY_net, (Nn, D), f32),
+            dX_cell=_view(b.dX_cell, (Nc, D), f32), dX_net=_view(b.dX_net, (Nn, D), f32),
+            pred=_view(pred.value, (Nc,), f32), dpred=_view(dpred.value, (Nc,), f32),
+            vals_cell=_view(b.saved.vals_cell, (Nc, k), f32), idx_cell=_view(b.saved.idx_cell, (Nc, k), torch.int16),
+            vals_net=_view(b.saved.vals_net, (Nn, k), f32), idx_net=_view(b.saved.idx_net, (Nn, k), torch.int16),
+            H_near=_view(b.saved.H_near, (Nc, D), f32), H_pins=_view(b.saved.H_pins, (Nn, D), f32),
+            H_pinned=_view(b.saved.H_pinned, (Nc, D), f32), mask=_view(b.saved.mask, (Nc, D), torch.uint8),
+        )
+        out["dW"] = {n: _view(getattr(b.dW, n), (D, D), f32) for n in WEIGHT_NAMES}
+        return out
+
+    def hgnn_destroy(self) -> None:
+        if self._model:
+            _check(load().hgnn_destroy(self._model))
+            self._model = ctypes.c_void_p(0)
+
+    def __del__(self):
+        try:
+            self.hgnn_destroy()
         except Exception:
             pass

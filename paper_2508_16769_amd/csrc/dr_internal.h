@@ -54,6 +54,13 @@ int launch_csr_normalize(int mode, int64_t n_rows, int64_t n_cols, int64_t nnz, 
                          const int32_t* colidx, float* vals_out, void* ws, hipStream_t s);
 int launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t s);
 
+// shape of a layer context (heteroconv.hip owns the struct)
+struct HeteroDims {
+    int64_t Nc, Nn;
+    int D, k_cell, k_net;
+};
+HeteroDims heteroconv_dims(const dr_heteroconv* c);
+
 // dense part of the layer ------------------------------------------------------------------------------
 struct GemmOperand {              // one K-segment of C = sum_seg A_seg * B_seg
     const float* dense;           // [rows, D] or nullptr

@@ -47,6 +47,8 @@ struct dr_heteroconv {
 
 using namespace drc;
 
+HeteroDims drc::heteroconv_dims(const dr_heteroconv* c) { return HeteroDims{c->Nc, c->Nn, c->D, c->k_cell, c->k_net}; }
+
 namespace {
 
 int dev_alloc(dr_heteroconv* c, void** p, size_t bytes) {

@@ -16,14 +16,14 @@ HEADER = os.path.join(ROOT, "include", "dr_circuitgnn.h")
 def declared_functions():
     text = open(HEADER).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    names = re.findall(r"\b(?:int|size_t|const char\*)\s+((?:dr_|heteroconv_)\w+)\s*\(", text)
+    names = re.findall(r"\b(?:int|int64_t|size_t|const char\*)\s+((?:dr_|heteroconv_|hgnn_)\w+)\s*\(", text)
     return sorted(set(names))
 
 
 def test_header_functions_are_exported_and_bound():
     lib = P.load()
     names = declared_functions()
-    assert len(names) >= 14
+    assert len(names) >= 19
     for n in names:
         assert hasattr(lib, n), f"{n} declared in the header but not exported"
     assert sorted(P.EXPORTS) == names

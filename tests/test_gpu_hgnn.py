@@ -1,0 +1,174 @@
+"""Parity of the multi-layer training step (hgnn_train_step) with the oracle, through the C ABI.
+
+A later layer's discrete decisions (top-k, max-merge, ReLU sign) depend on fp32 values the earlier layers
+produced, so every layer is compared "teacher-forced": the oracle recomputes that layer from the very inputs /
+saved selections the HIP path used (read back through hgnn_get_layer_buffers).  Selections must then match bit
+for bit and values within the row bound; the read-out, the loss, the gradient sums and the Adam update are checked
+the same way, and the loss of the whole step is compared with the free-running oracle as an end-to-end sanity."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import hgnn as ohgnn
+import paper_2508_16769_amd as P
+from circuit_synth import make_graph
+from gpu_util import assert_row_bound, dev, host_idx, say
+
+pytestmark = pytest.mark.gpu
+
+LR, B1, B2, EPS, WD = 2e-4, 0.9, 0.999, 1e-8, 1e-5
+
+
+def _setup(n_graphs, Nc, Nn, grid, D, k, L, seed0=20):
+    rng = np.random.default_rng(seed0)
+    graphs, rels, ctxs, keep = [], [], [], []
+    Xc, Xn, tg = [], [], []
+    for q in range(n_graphs):
+        g = make_graph("small", seed=seed0 + q, Nc=Nc + 64 * q, Nn=Nn + 32 * q, grid=grid)
+        graphs.append(g)
+        rels.append((oracle.relation(g.near, oracle.NORM_MEAN), oracle.relation(g.pins, oracle.NORM_MEAN),
+                     oracle.relation(g.pinned, oracle.NORM_SYM)))
+        d = (P.device_relation(g.near, P.DR_NORM_MEAN), P.device_relation(g.pins, P.DR_NORM_MEAN),
+             P.device_relation(g.pinned, P.DR_NORM_SYM))
+        keep.append(d)
+        ctxs.append(P.HeteroConv(d[0], d[1], d[2], D, k, k))
+        Xc.append(rng.standard_normal((g.Nc, D)).astype(np.float32))
+        Xn.append(rng.standard_normal((g.Nn, D)).astype(np.float32))
+        tg.append(rng.standard_normal(g.Nc).astype(np.float32))
+    bound = np.sqrt(6.0 / (2 * D))
+    theta = rng.uniform(-bound, bound, P.hgnn_num_params(L, D)).astype(np.float32)
+    return graphs, rels, ctxs, keep, Xc, Xn, tg, theta
+
+
+def _wgrad_bounds(saved, Xs_c, Xs_n, dYc, dYn, mask):
+    """Element-wise sum of |terms| for each of the five weight gradients (dW = A^T B)."""
+    dZn, dZq = np.abs(dYc) * (mask == 1), np.abs(dYc) * (mask == 0)
+    return dict(self_near=np.abs(Xs_c).T @ dZn, neigh_near=np.abs(saved["H_near"]).T @ dZn,
+                self_pins=np.abs(Xs_n).T @ np.abs(dYn), neigh_pins=np.abs(saved["H_pins"]).T @ np.abs(dYn),
+                pinned=np.abs(saved["H_pinned"]).T @ dZq)
+
+
+@pytest.mark.parametrize("case", [dict(n_graphs=3, Nc=2400, Nn=1700, grid=(64, 42), D=128, k=32, L=3),
+                                  dict(n_graphs=2, Nc=1500, Nn=900, grid=(52, 32), D=64, k=16, L=2)],
+                         ids=["3x2400_D128_k32_L3", "2x1500_D64_k16_L2"])
+def test_train_step_parity(case):
+    n_graphs, D, k, L = case["n_graphs"], case["D"], case["k"], case["L"]
+    graphs, rels, ctxs, keep, Xc, Xn, tg, theta0 = _setup(**case)
+    say(f"hgnn: {n_graphs} sub-graphs, D={D}, k={k}, L={L}")
+    model = P.Hgnn(ctxs, L)
+    n_par = P.hgnn_num_params(L, D)
+    theta = dev(theta0)
+    m = torch.zeros(n_par, dtype=torch.float32, device="cuda")
+    v = torch.zeros(n_par, dtype=torch.float32, device="cuda")
+    grad = torch.full((n_par,), float("nan"), dtype=torch.float32, device="cuda")
+    loss = torch.full((1,), float("nan"), dtype=torch.float32, device="cuda")
+    dXc, dXn, dtg = [dev(a) for a in Xc], [dev(a) for a in Xn], [dev(a) for a in tg]
+    model.hgnn_train_step(dXc, dXn, dtg, theta, m, v, LR, B1, B2, EPS, WD, 1, grad, loss)
+    torch.cuda.synchronize()
+
+    Ws, w_head = ohgnn.unpack(theta0.astype(np.float64), L, D)
+    n_total = sum(g.Nc for g in graphs)
+    sq_sum = 0.0
+    g_layers = np.zeros(n_par - D)
+    g_head = np.zeros(D)
+    for q in range(n_graphs):
+        last = None
+        for l in range(L):
+            b = {kk: (vv.cpu().numpy() if torch.is_tensor(vv) else {n: t.cpu().numpy() for n, t in vv.items()})
+                 for kk, vv in model.hgnn_get_layer_buffers(q, l).items()}
+            if l == 0:
+                assert np.array_equal(b["X_cell"], Xc[q]) and np.array_equal(b["X_net"], Xn[q])
+            # ---- forward of this layer from the inputs the HIP path used ----
+            of = oracle.heteroconv_fwd(*rels[q], b["X_cell"], b["X_net"], Ws[l], k, k)
+            assert np.array_equal(host_idx(torch.from_numpy(b["idx_cell"])), of["idx_cell"]), (q, l)
+            assert np.array_equal(host_idx(torch.from_numpy(b["idx_net"])), of["idx_net"]), (q, l)
+            assert np.array_equal(b["vals_cell"].astype(np.float64), of["vals_cell"])
+            want_c, want_n = of["Y_cell"], of["Y_net"]
+            if l < L - 1:
+                want_c, want_n = np.maximum(want_c, 0), np.maximum(want_n, 0)
+                assert (b["Y_cell"] >= 0).all() and (b["Y_net"] >= 0).all()
+            assert_row_bound(b["Y_cell"], want_c, of["l1_cell"].sum(axis=1), f"g{q} l{l} Y_cell")
+            assert_row_bound(b["Y_net"], want_n, of["l1_net"].sum(axis=1), f"g{q} l{l} Y_net")
+            decided = np.abs(of["Z_near"] - of["Z_pinned"]) > 2e-5 * of["l1_cell"]
+            assert decided.mean() > 0.98
+            assert np.array_equal(b["mask"][decided], of["mask"][decided])
+            # ---- backward of this layer from the state and the gradient the HIP path used ----
+            saved = {n: b[n] for n in ("vals_cell", "vals_net", "H_near", "H_pins", "H_pinned", "mask")}
+            saved["idx_cell"] = host_idx(torch.from_numpy(b["idx_cell"]))
+            saved["idx_net"] = host_idx(torch.from_numpy(b["idx_net"]))
+            ob = oracle.heteroconv_bwd(*rels[q], Ws[l], saved, b["dY_cell"], b["dY_net"])
+            ic, inn = saved["idx_cell"].astype(np.int64), saved["idx_net"].astype(np.int64)
+            want_gc, want_gn = ob["dXs_cell"].copy(), ob["dXs_net"].copy()
+            if l >= 1:       # the ReLU in front of the layer gates its input gradient
+                want_gc *= np.take_along_axis(b["X_cell"], ic, axis=1) > 0
+                want_gn *= np.take_along_axis(b["X_net"], inn, axis=1) > 0
+            assert_row_bound(np.take_along_axis(b["dX_cell"], ic, axis=1), want_gc, ob["l1_dxs_cell"].sum(axis=1), f"g{q} l{l} dX_cell")
+            assert_row_bound(np.take_along_axis(b["dX_net"], inn, axis=1), want_gn, ob["l1_dxs_net"].sum(axis=1), f"g{q} l{l} dX_net")
+            off = np.ones(b["dX_cell"].shape, bool)
+            np.put_along_axis(off, ic, False, axis=1)
+            assert np.all(b["dX_cell"][off] == 0)
+            Xs_c = oracle.densify(saved["vals_cell"], saved["idx_cell"], D)
+            Xs_n = oracle.densify(saved["vals_net"], saved["idx_net"], D)
+            bounds = _wgrad_bounds({n: np.asarray(saved[n], np.float64) for n in ("H_near", "H_pins", "H_pinned")}, Xs_c, Xs_n,
+                                   b["dY_cell"].astype(np.float64), b["dY_net"].astype(np.float64), saved["mask"])
+            for i, n in enumerate(P.WEIGHT_NAMES):
+                err = np.abs(b["dW"][n].astype(np.float64) - ob["dW"][n])
+                assert np.all(err <= 1e-5 * bounds[n] + 1e-30), (q, l, n, err.max())
+                lo = (l * 5 + i) * D * D
+                g_layers[lo:lo + D * D] += b["dW"][n].astype(np.float64).ravel()
+            last = b
+        # ---- read-out, residual, gradient of the last layer's output ----
+        Y = last["Y_cell"].astype(np.float64)
+        pred = Y @ w_head
+        l1 = np.abs(Y) @ np.abs(w_head)
+        assert np.all(np.abs(last["pred"] - pred) <= 1e-5 * l1 + 1e-30)
+        r = last["pred"].astype(np.float64) - tg[q]
+        sq_sum += float(np.sum(r * r))
+        assert np.allclose(last["dpred"], 2.0 * r / n_total, rtol=2e-6, atol=0)
+        want_dY = np.outer(last["dpred"].astype(np.float64), w_head)
+        assert np.allclose(last["dY_cell"], want_dY, rtol=2e-6, atol=1e-30)
+        assert np.all(last["dY_net"] == 0)
+        g_head += Y.T @ last["dpred"].astype(np.float64)
+    # ---- loss, gradient sums, Adam ----
+    loss_gpu = float(loss.cpu()[0])
+    assert abs(loss_gpu - sq_sum / n_total) <= 1e-5 * (sq_sum / n_total)
+    gg = grad.cpu().numpy().astype(np.float64)
+    assert np.allclose(gg[:n_par - D], g_layers, rtol=1e-5, atol=1e-9)
+    assert np.allclose(gg[n_par - D:], g_head, rtol=1e-4, atol=1e-7)
+    th2, m2, v2 = ohgnn.adam_step(theta0.astype(np.float64), gg, np.zeros(n_par), np.zeros(n_par), LR, B1, B2, EPS, WD, 1)
+    assert np.allclose(theta.cpu().numpy(), th2, rtol=0, atol=2e-7 * max(1.0, np.abs(th2).max()) + LR * 1e-3)
+    assert np.allclose(m.cpu().numpy(), m2, rtol=1e-5, atol=1e-12)
+    assert np.allclose(v.cpu().numpy(), v2, rtol=1e-5, atol=1e-20)
+    # ---- the free-running oracle agrees on the loss (discrete flips, if any, are rare and local) ----
+    free = ohgnn.train_step(rels, Xc, Xn, tg, theta0.astype(np.float64), np.zeros(n_par), np.zeros(n_par), L, D, k,
+                            LR, B1, B2, EPS, WD, 1)
+    assert abs(loss_gpu - free["loss"]) <= 1e-3 * free["loss"], (loss_gpu, free["loss"])
+    cos = float(gg @ free["grad"] / (np.linalg.norm(gg) * np.linalg.norm(free["grad"])))
+    assert cos > 0.999, cos
+    # a second step runs from the updated state and lowers nothing it should not touch
+    model.hgnn_train_step(dXc, dXn, dtg, theta, m, v, LR, B1, B2, EPS, WD, 2, grad, loss)
+    torch.cuda.synchronize()
+    assert np.isfinite(float(loss.cpu()[0])) and np.isfinite(theta.cpu().numpy()).all()
+    model.hgnn_destroy()
+    for c in ctxs:
+        c.heteroconv_destroy()
+
+
+def test_rejects_bad_arguments():
+    g = make_graph("tiny", seed=0)
+    d = (P.device_relation(g.near, P.DR_NORM_MEAN), P.device_relation(g.pins, P.DR_NORM_MEAN),
+         P.device_relation(g.pinned, P.DR_NORM_SYM))
+    ctx = P.HeteroConv(d[0], d[1], d[2], 64, 16, 16)
+    with pytest.raises(P.DrError):
+        P.Hgnn([ctx, ctx], 2)                 # one context cannot serve two sub-graphs of a batch
+    with pytest.raises(P.DrError):
+        P.Hgnn([ctx], 0)
+    model = P.Hgnn([ctx], 1)
+    n = P.hgnn_num_params(1, 64)
+    z = torch.zeros(n, dtype=torch.float32, device="cuda")
+    x = [torch.zeros((g.Nc, 64), device="cuda")], [torch.zeros((g.Nn, 64), device="cuda")], [torch.zeros(g.Nc, device="cuda")]
+    with pytest.raises(P.DrError):
+        model.hgnn_train_step(x[0], x[1], x[2], z, z.clone(), z.clone(), LR, B1, B2, EPS, WD, 0, z.clone(), z[:1].clone())
+    model.hgnn_destroy()
+    ctx.heteroconv_destroy()
