@@ -49,6 +49,51 @@ def _wgrad_bounds(saved, Xs_c, Xs_n, dYc, dYn, mask):
                 pinned=np.abs(saved["H_pinned"]).T @ dZq)
 
 
+def _check_layer(model, rels, Ws, q, l, L, D, k, X0=None):
+    """Teacher-forced comparison of sub-graph q, layer l; returns the buffers (numpy) of that layer."""
+    b = {kk: (vv.cpu().numpy() if torch.is_tensor(vv) else {n: t.cpu().numpy() for n, t in vv.items()})
+         for kk, vv in model.hgnn_get_layer_buffers(q, l).items()}
+    if l == 0 and X0 is not None:
+        assert np.array_equal(b["X_cell"], X0[0]) and np.array_equal(b["X_net"], X0[1])
+    # ---- forward of this layer from the inputs the HIP path used ----
+    of = oracle.heteroconv_fwd(*rels[q], b["X_cell"], b["X_net"], Ws[l], k, k)
+    assert np.array_equal(host_idx(torch.from_numpy(b["idx_cell"])), of["idx_cell"]), (q, l)
+    assert np.array_equal(host_idx(torch.from_numpy(b["idx_net"])), of["idx_net"]), (q, l)
+    assert np.array_equal(b["vals_cell"].astype(np.float64), of["vals_cell"])
+    want_c, want_n = of["Y_cell"], of["Y_net"]
+    if l < L - 1:
+        want_c, want_n = np.maximum(want_c, 0), np.maximum(want_n, 0)
+        assert (b["Y_cell"] >= 0).all() and (b["Y_net"] >= 0).all()
+    assert_row_bound(b["Y_cell"], want_c, of["l1_cell"].sum(axis=1), f"g{q} l{l} Y_cell")
+    assert_row_bound(b["Y_net"], want_n, of["l1_net"].sum(axis=1), f"g{q} l{l} Y_net")
+    decided = np.abs(of["Z_near"] - of["Z_pinned"]) > 2e-5 * of["l1_cell"]
+    assert decided.mean() > 0.98
+    assert np.array_equal(b["mask"][decided], of["mask"][decided])
+    # ---- backward of this layer from the state and the gradient the HIP path used ----
+    saved = {n: b[n] for n in ("vals_cell", "vals_net", "H_near", "H_pins", "H_pinned", "mask")}
+    saved["idx_cell"] = host_idx(torch.from_numpy(b["idx_cell"]))
+    saved["idx_net"] = host_idx(torch.from_numpy(b["idx_net"]))
+    ob = oracle.heteroconv_bwd(*rels[q], Ws[l], saved, b["dY_cell"], b["dY_net"])
+    ic, inn = saved["idx_cell"].astype(np.int64), saved["idx_net"].astype(np.int64)
+    want_gc, want_gn = ob["dXs_cell"].copy(), ob["dXs_net"].copy()
+    if l >= 1:       # the ReLU in front of the layer gates its input gradient
+        want_gc *= np.take_along_axis(b["X_cell"], ic, axis=1) > 0
+        want_gn *= np.take_along_axis(b["X_net"], inn, axis=1) > 0
+    assert_row_bound(np.take_along_axis(b["dX_cell"], ic, axis=1), want_gc, ob["l1_dxs_cell"].sum(axis=1), f"g{q} l{l} dX_cell")
+    assert_row_bound(np.take_along_axis(b["dX_net"], inn, axis=1), want_gn, ob["l1_dxs_net"].sum(axis=1), f"g{q} l{l} dX_net")
+    off = np.ones(b["dX_cell"].shape, bool)
+    np.put_along_axis(off, ic, False, axis=1)
+    assert np.all(b["dX_cell"][off] == 0)
+    Xs_c = oracle.densify(saved["vals_cell"], saved["idx_cell"], D)
+    Xs_n = oracle.densify(saved["vals_net"], saved["idx_net"], D)
+    bounds = _wgrad_bounds({n: np.asarray(saved[n], np.float64) for n in ("H_near", "H_pins", "H_pinned")}, Xs_c, Xs_n,
+                           b["dY_cell"].astype(np.float64), b["dY_net"].astype(np.float64), saved["mask"])
+    for i, n in enumerate(P.WEIGHT_NAMES):
+        err = np.abs(b["dW"][n].astype(np.float64) - ob["dW"][n])
+        assert np.all(err <= 1e-5 * bounds[n] + 1e-30), (q, l, n, err.max())
+    return b
+
+
 @pytest.mark.parametrize("case", [dict(n_graphs=3, Nc=2400, Nn=1700, grid=(64, 42), D=128, k=32, L=3),
                                   dict(n_graphs=2, Nc=1500, Nn=900, grid=(52, 32), D=64, k=16, L=2)],
                          ids=["3x2400_D128_k32_L3", "2x1500_D64_k16_L2"])
@@ -75,46 +120,8 @@ def test_train_step_parity(case):
     for q in range(n_graphs):
         last = None
         for l in range(L):
-            b = {kk: (vv.cpu().numpy() if torch.is_tensor(vv) else {n: t.cpu().numpy() for n, t in vv.items()})
-                 for kk, vv in model.hgnn_get_layer_buffers(q, l).items()}
-            if l == 0:
-                assert np.array_equal(b["X_cell"], Xc[q]) and np.array_equal(b["X_net"], Xn[q])
-            # ---- forward of this layer from the inputs the HIP path used ----
-            of = oracle.heteroconv_fwd(*rels[q], b["X_cell"], b["X_net"], Ws[l], k, k)
-            assert np.array_equal(host_idx(torch.from_numpy(b["idx_cell"])), of["idx_cell"]), (q, l)
-            assert np.array_equal(host_idx(torch.from_numpy(b["idx_net"])), of["idx_net"]), (q, l)
-            assert np.array_equal(b["vals_cell"].astype(np.float64), of["vals_cell"])
-            want_c, want_n = of["Y_cell"], of["Y_net"]
-            if l < L - 1:
-                want_c, want_n = np.maximum(want_c, 0), np.maximum(want_n, 0)
-                assert (b["Y_cell"] >= 0).all() and (b["Y_net"] >= 0).all()
-            assert_row_bound(b["Y_cell"], want_c, of["l1_cell"].sum(axis=1), f"g{q} l{l} Y_cell")
-            assert_row_bound(b["Y_net"], want_n, of["l1_net"].sum(axis=1), f"g{q} l{l} Y_net")
-            decided = np.abs(of["Z_near"] - of["Z_pinned"]) > 2e-5 * of["l1_cell"]
-            assert decided.mean() > 0.98
-            assert np.array_equal(b["mask"][decided], of["mask"][decided])
-            # ---- backward of this layer from the state and the gradient the HIP path used ----
-            saved = {n: b[n] for n in ("vals_cell", "vals_net", "H_near", "H_pins", "H_pinned", "mask")}
-            saved["idx_cell"] = host_idx(torch.from_numpy(b["idx_cell"]))
-            saved["idx_net"] = host_idx(torch.from_numpy(b["idx_net"]))
-            ob = oracle.heteroconv_bwd(*rels[q], Ws[l], saved, b["dY_cell"], b["dY_net"])
-            ic, inn = saved["idx_cell"].astype(np.int64), saved["idx_net"].astype(np.int64)
-            want_gc, want_gn = ob["dXs_cell"].copy(), ob["dXs_net"].copy()
-            if l >= 1:       # the ReLU in front of the layer gates its input gradient
-                want_gc *= np.take_along_axis(b["X_cell"], ic, axis=1) > 0
-                want_gn *= np.take_along_axis(b["X_net"], inn, axis=1) > 0
-            assert_row_bound(np.take_along_axis(b["dX_cell"], ic, axis=1), want_gc, ob["l1_dxs_cell"].sum(axis=1), f"g{q} l{l} dX_cell")
-            assert_row_bound(np.take_along_axis(b["dX_net"], inn, axis=1), want_gn, ob["l1_dxs_net"].sum(axis=1), f"g{q} l{l} dX_net")
-            off = np.ones(b["dX_cell"].shape, bool)
-            np.put_along_axis(off, ic, False, axis=1)
-            assert np.all(b["dX_cell"][off] == 0)
-            Xs_c = oracle.densify(saved["vals_cell"], saved["idx_cell"], D)
-            Xs_n = oracle.densify(saved["vals_net"], saved["idx_net"], D)
-            bounds = _wgrad_bounds({n: np.asarray(saved[n], np.float64) for n in ("H_near", "H_pins", "H_pinned")}, Xs_c, Xs_n,
-                                   b["dY_cell"].astype(np.float64), b["dY_net"].astype(np.float64), saved["mask"])
+            b = _check_layer(model, rels, Ws, q, l, L, D, k, X0=(Xc[q], Xn[q]))
             for i, n in enumerate(P.WEIGHT_NAMES):
-                err = np.abs(b["dW"][n].astype(np.float64) - ob["dW"][n])
-                assert np.all(err <= 1e-5 * bounds[n] + 1e-30), (q, l, n, err.max())
                 lo = (l * 5 + i) * D * D
                 g_layers[lo:lo + D * D] += b["dW"][n].astype(np.float64).ravel()
             last = b
@@ -150,6 +157,80 @@ def test_train_step_parity(case):
     model.hgnn_train_step(dXc, dXn, dtg, theta, m, v, LR, B1, B2, EPS, WD, 2, grad, loss)
     torch.cuda.synchronize()
     assert np.isfinite(float(loss.cpu()[0])) and np.isfinite(theta.cpu().numpy()).all()
+    model.hgnn_destroy()
+    for c in ctxs:
+        c.heteroconv_destroy()
+
+
+def test_full_size_step_of_eight_subgraphs():
+    """The batch of the training-step configuration: 8 independent sub-graphs of 20 000 cells / 14 000 nets,
+    3 layers, D = 128, k = 32.  Two (sub-graph, layer) pairs are recomputed by the oracle; the loss, the gradient
+    sums and the update are checked for the whole batch."""
+    from circuit_synth import workload
+    import time
+    w = workload("subgraph")
+    D, k, L, n_graphs = w["D"], w["k"], 3, 8
+    rng = np.random.default_rng(77)
+    graphs, rels, ctxs, keep, dXc, dXn, dtg, tgs = [], {}, [], [], [], [], [], []
+    for q in range(n_graphs):
+        g = make_graph("subgraph", seed=q)
+        graphs.append(g)
+        d = (P.device_relation(g.near, P.DR_NORM_MEAN), P.device_relation(g.pins, P.DR_NORM_MEAN),
+             P.device_relation(g.pinned, P.DR_NORM_SYM))
+        keep.append(d)
+        ctxs.append(P.HeteroConv(d[0], d[1], d[2], D, k, k))
+        dXc.append(dev(rng.standard_normal((g.Nc, D)).astype(np.float32)))
+        dXn.append(dev(rng.standard_normal((g.Nn, D)).astype(np.float32)))
+        tgs.append(rng.standard_normal(g.Nc).astype(np.float32))
+        dtg.append(dev(tgs[-1]))
+    say(f"hgnn full size: {n_graphs} x ({graphs[0].Nc} cells, {graphs[0].Nn} nets), D={D}, k={k}, L={L}")
+    model = P.Hgnn(ctxs, L)
+    n_par = P.hgnn_num_params(L, D)
+    bound = np.sqrt(6.0 / (2 * D))
+    theta0 = rng.uniform(-bound, bound, n_par).astype(np.float32)
+    theta = dev(theta0)
+    m = torch.zeros(n_par, dtype=torch.float32, device="cuda")
+    v = torch.zeros(n_par, dtype=torch.float32, device="cuda")
+    grad = torch.empty(n_par, dtype=torch.float32, device="cuda")
+    loss = torch.empty(1, dtype=torch.float32, device="cuda")
+    model.hgnn_train_step(dXc, dXn, dtg, theta, m, v, LR, B1, B2, EPS, WD, 1, grad, loss)
+    torch.cuda.synchronize()
+    Ws, w_head = ohgnn.unpack(theta0.astype(np.float64), L, D)
+    for q, l in ((5, 2), (2, 1)):
+        g = graphs[q]
+        rels[q] = (oracle.relation(g.near, oracle.NORM_MEAN), oracle.relation(g.pins, oracle.NORM_MEAN),
+                   oracle.relation(g.pinned, oracle.NORM_SYM))
+        say(f"hgnn full size: oracle on sub-graph {q}, layer {l}")
+        _check_layer(model, rels, Ws, q, l, L, D, k)
+    n_total = sum(g.Nc for g in graphs)
+    sq, g_layers, g_head = 0.0, np.zeros(n_par - D), np.zeros(D)
+    for q in range(n_graphs):
+        for l in range(L):
+            b = model.hgnn_get_layer_buffers(q, l)
+            for i, n in enumerate(P.WEIGHT_NAMES):
+                lo = (l * 5 + i) * D * D
+                g_layers[lo:lo + D * D] += b["dW"][n].cpu().numpy().astype(np.float64).ravel()
+        Y = b["Y_cell"].cpu().numpy().astype(np.float64)
+        pred = b["pred"].cpu().numpy().astype(np.float64)
+        assert np.all(np.abs(pred - Y @ w_head) <= 1e-5 * (np.abs(Y) @ np.abs(w_head)))
+        r = pred - tgs[q]
+        sq += float(np.sum(r * r))
+        g_head += Y.T @ b["dpred"].cpu().numpy().astype(np.float64)
+    assert abs(float(loss.cpu()[0]) - sq / n_total) <= 1e-5 * sq / n_total
+    gg = grad.cpu().numpy().astype(np.float64)
+    assert np.allclose(gg[:n_par - D], g_layers, rtol=1e-5, atol=1e-9)
+    assert np.allclose(gg[n_par - D:], g_head, rtol=1e-4, atol=1e-7)
+    th2, m2, v2 = ohgnn.adam_step(theta0.astype(np.float64), gg, np.zeros(n_par), np.zeros(n_par), LR, B1, B2, EPS, WD, 1)
+    assert np.allclose(theta.cpu().numpy(), th2, rtol=0, atol=2e-7 + LR * 1e-3)
+    # timing of the step (reported, not asserted)
+    for _ in range(2):
+        model.hgnn_train_step(dXc, dXn, dtg, theta, m, v, LR, B1, B2, EPS, WD, 2, grad, loss)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(10):
+        model.hgnn_train_step(dXc, dXn, dtg, theta, m, v, LR, B1, B2, EPS, WD, 3 + i, grad, loss)
+    torch.cuda.synchronize()
+    say(f"hgnn full size: {(time.perf_counter() - t0) * 100:.3f} ms per training step, loss {float(loss.cpu()[0]):.5f}")
     model.hgnn_destroy()
     for c in ctxs:
         c.heteroconv_destroy()
