@@ -9,6 +9,7 @@ from .generate import (  # noqa: F401
     WORKLOADS,
     CircuitGraph,
     LayerTensors,
+    block_diagonal,
     make_graph,
     make_tensors,
     workload,

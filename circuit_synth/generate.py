@@ -242,6 +242,29 @@ def permute_cells(g: CircuitGraph, seed: int = 0) -> CircuitGraph:
                         relabel(g.pinned, True, False))
 
 
+def block_diagonal(graphs) -> CircuitGraph:
+    """One graph whose relations are the block-diagonal stack of the given independent sub-graphs (cell and net
+    ids of sub-graph q are shifted by the sizes of the sub-graphs before it).  A layer on this graph computes
+    exactly what the layers on the sub-graphs compute, in one launch per kernel instead of one per sub-graph."""
+    c_off = np.concatenate([[0], np.cumsum([g.Nc for g in graphs])]).astype(np.int64)
+    n_off = np.concatenate([[0], np.cumsum([g.Nn for g in graphs])]).astype(np.int64)
+
+    def stack(pats, col_off, n_cols):
+        rp, ci, e = [np.zeros(1, np.int64)], [], 0
+        for p, co in zip(pats, col_off):
+            rp.append(p.rowptr[1:].astype(np.int64) + e)
+            ci.append(p.colidx.astype(np.int64) + co)
+            e += p.nnz
+        assert e < 2 ** 31
+        return Pattern(int(sum(p.n_rows for p in pats)), int(n_cols), np.concatenate(rp).astype(np.int32),
+                       (np.concatenate(ci) if ci else np.zeros(0)).astype(np.int32))
+
+    Nc, Nn = int(c_off[-1]), int(n_off[-1])
+    return CircuitGraph(name="+".join(g.name for g in graphs), seed=graphs[0].seed, Nc=Nc, Nn=Nn,
+                        near=stack([g.near for g in graphs], c_off, Nc), pins=stack([g.pins for g in graphs], c_off, Nc),
+                        pinned=stack([g.pinned for g in graphs], n_off, Nn))
+
+
 def make_graph(name: str, seed: int = 0, **override) -> CircuitGraph:
     """Build the three relation patterns of the named workload (see ``WORKLOADS``).
     Keyword overrides (e.g. ``Nc=..., Nn=..., grid=...``) derive scaled variants."""

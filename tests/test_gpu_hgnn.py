@@ -236,6 +236,51 @@ def test_full_size_step_of_eight_subgraphs():
         c.heteroconv_destroy()
 
 
+def test_block_diagonal_batch_equals_separate_subgraphs():
+    """Independent sub-graphs stacked into one block-diagonal graph give the same step (one launch per kernel
+    for the whole batch instead of one per sub-graph): same selections, same loss and gradient up to the order
+    of the fp32 sums over rows."""
+    from circuit_synth import block_diagonal
+    D, k, L, n_graphs = 64, 16, 2, 3
+    rng = np.random.default_rng(5)
+    gs = [make_graph("small", seed=40 + q, Nc=1800 + 100 * q, Nn=1100 + 50 * q, grid=(50, 40)) for q in range(n_graphs)]
+    Xc = [rng.standard_normal((g.Nc, D)).astype(np.float32) for g in gs]
+    Xn = [rng.standard_normal((g.Nn, D)).astype(np.float32) for g in gs]
+    tg = [rng.standard_normal(g.Nc).astype(np.float32) for g in gs]
+    n_par = P.hgnn_num_params(L, D)
+    theta0 = rng.uniform(-0.2, 0.2, n_par).astype(np.float32)
+
+    def step(graph_list, xc, xn, t):
+        keep, ctxs = [], []
+        for g in graph_list:
+            d = (P.device_relation(g.near, P.DR_NORM_MEAN), P.device_relation(g.pins, P.DR_NORM_MEAN),
+                 P.device_relation(g.pinned, P.DR_NORM_SYM))
+            keep.append(d)
+            ctxs.append(P.HeteroConv(d[0], d[1], d[2], D, k, k))
+        model = P.Hgnn(ctxs, L)
+        th = dev(theta0)
+        m = torch.zeros(n_par, dtype=torch.float32, device="cuda")
+        v = torch.zeros(n_par, dtype=torch.float32, device="cuda")
+        gr = torch.empty(n_par, dtype=torch.float32, device="cuda")
+        ls = torch.empty(1, dtype=torch.float32, device="cuda")
+        model.hgnn_train_step([dev(a) for a in xc], [dev(a) for a in xn], [dev(a) for a in t], th, m, v, LR, B1, B2, EPS, WD, 1, gr, ls)
+        torch.cuda.synchronize()
+        idx = [host_idx(model.hgnn_get_layer_buffers(q, L - 1)["idx_cell"]) for q in range(len(graph_list))]
+        out = float(ls.cpu()[0]), gr.cpu().numpy().astype(np.float64), np.concatenate(idx)
+        model.hgnn_destroy()
+        for c in ctxs:
+            c.heteroconv_destroy()
+        return out
+
+    loss_a, grad_a, idx_a = step(gs, Xc, Xn, tg)
+    big = block_diagonal(gs)
+    assert big.Nc == sum(g.Nc for g in gs) and big.near.nnz == sum(g.near.nnz for g in gs)
+    loss_b, grad_b, idx_b = step([big], [np.concatenate(Xc)], [np.concatenate(Xn)], [np.concatenate(tg)])
+    assert np.array_equal(idx_a, idx_b)                      # last layer's selections: bit-identical inputs reached it
+    assert abs(loss_a - loss_b) <= 1e-6 * abs(loss_a)
+    assert np.allclose(grad_a, grad_b, rtol=1e-4, atol=1e-6 * np.abs(grad_a).max())
+
+
 def test_rejects_bad_arguments():
     g = make_graph("tiny", seed=0)
     d = (P.device_relation(g.near, P.DR_NORM_MEAN), P.device_relation(g.pins, P.DR_NORM_MEAN),
