@@ -231,6 +231,9 @@ def main() -> int:
             roofline = dict(bound="hbm", achieved=round(ach, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                             frac=round(ach / HBM_PEAK_GBS, 4), traffic=traffic, kernel=dom,
                             avg_ms=kernels[dom]["ms"])
+        if traffic:   # measured HBM bytes of the same kernel over the same duration (context for `frac`)
+            roofline["measured_hbm_GBs"] = round(traffic / avg_s / 1e9, 1)
+            roofline["measured_hbm_frac"] = round(traffic / avg_s / 1e9 / HBM_PEAK_GBS, 4)
         dr_ms = sum(kernels[n]["ms"] for n in DR_KERNELS if n in kernels)
         dr_flops = sum(models[n][1] for n in DR_KERNELS if n.startswith("dr_spmm"))
         dr_region = dict(kernels="D-ReLU x2 + DR-SpMM fwd x3 + bwd x3", sum_ms=round(dr_ms, 4),
