@@ -113,6 +113,8 @@ def main() -> int:
     ap.add_argument("--no-profile-events", action="store_true", help="do not bracket kernels with HIP events")
     ap.add_argument("--overlap", choices=("auto", "on", "off"), default="auto",
                     help="relation concurrency: three streams (on), one stream (off), or the library's size rule")
+    ap.add_argument("--permute-cells", action="store_true",
+                    help="sensitivity run: relabel the cells at random (removes the grid locality of `near`)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy a few times (known traffic, for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings) and exit")
@@ -149,6 +151,9 @@ def main() -> int:
 
     t_setup = time.perf_counter()
     g = make_graph(args.workload, seed=0)
+    if args.permute_cells:
+        from circuit_synth.generate import permute_cells
+        g = permute_cells(g, seed=0)
     T = make_tensors(g.Nc, g.Nn, D, seed=0)
     E = dict(near=g.near.nnz, pins=g.pins.nnz, pinned=g.pinned.nnz)
 
@@ -255,7 +260,8 @@ def main() -> int:
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": f"{args.workload}: {g.Nc} cells, {g.Nn} nets, E_near={E['near']}, "
-                               f"E_pins={E['pins']}, D={D}, k={k}, one HeteroConv layer fwd+bwd",
+                               f"E_pins={E['pins']}, D={D}, k={k}, one HeteroConv layer fwd+bwd"
+                               + (" (cell ids randomly permuted)" if args.permute_cells else ""),
                    "step_algorithmic_MB": round(step_bytes / 1e6, 1),
                    "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
                    "relation_overlap": args.overlap,
