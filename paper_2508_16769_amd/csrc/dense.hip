@@ -7,7 +7,8 @@
 //   - the self-term gradient is sampled at the saved CBSR indices straight out of the accumulators,
 //     added to the compact SpMM gradient and written as the dense, top-k-gated dX rows.
 //
-// Projection kernel.  Persistent workgroups (two per CU) loop over 64-row tiles.  The weights never
+// Projection kernel.  Persistent workgroups (as many as fit the chip at once: two to four per CU) loop over
+// 32-row tiles (D >= 96; 64 or 128 rows for narrower D).  The weights never
 // touch LDS: wavefront w keeps the 32-column slab of W it is responsible for in registers in MFMA
 // B-operand layout for the whole kernel (64 VGPRs per 128x128 weight), so the inner loop is one
 // ds_read_b128 of the A operand per four MFMAs.  Row tiles are double-buffered through LDS: every global
@@ -35,7 +36,7 @@ template <int NT> struct ProjCfg {
     static constexpr int D = 32 * NT;
     static constexpr int KS = D / 2;                                  // MFMA k-steps per segment
     static constexpr int RG = (NT >= 3) ? 1 : (NT == 2 ? 2 : 4);      // wavefront row groups
-    static constexpr int BM = (NT == 1) ? 128 : 64;                   // rows per tile
+    static constexpr int BM = (NT == 1) ? 128 : (NT == 2 ? 64 : 32);  // rows per tile
     static constexpr int SPW = (BM / 32) / RG;                        // 32-row sub-tiles per wavefront
     static constexpr int LDA = D + 4;                                 // LDS row stride: rows stay 16-byte aligned
     static constexpr int F4 = BM * D / 4 / kPT;                       // float4 per thread per dense tile
@@ -79,8 +80,11 @@ __device__ __forceinline__ float4 nt_load4(const float* p) {
     return v;
 }
 
+
 template <int NT, int AK, int EPI>
-__global__ __launch_bounds__(kPT, (AK == kACbsrDense ? 1 : 2)) void proj_kernel(GemmParams p) {
+// wavefronts per SIMD the register budget is set for: 4 for the one-operand store kernels, 3 with the merge or
+// sampling epilogue (they hold the other branch / the pairs as well), 2 with two resident weight slabs
+__global__ __launch_bounds__(kPT, (EPI == kEpiStore ? (AK == kACbsrDense ? 2 : 4) : 3)) void proj_kernel(GemmParams p) {
     using C = ProjCfg<NT>;
     constexpr int D = C::D, KS = C::KS, BM = C::BM, SPW = C::SPW, LDA = C::LDA, F4 = C::F4;
     constexpr int TPR = C::TPR, RPW = C::RPW;
@@ -385,14 +389,19 @@ __global__ __launch_bounds__(kPT, (AK == kACbsrDense ? 1 : 2)) void proj_kernel(
 template <int NT, int AK, int EPI>
 static int launch_proj(const GemmParams& p, hipStream_t s) {
     using C = ProjCfg<NT>;
-    static bool configured = false;
-    if (!configured) {
+    static int resident = 0;                           // persistent workgroups = what fits the chip at once
+    if (!resident) {
         DRC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&proj_kernel<NT, AK, EPI>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::kLds));
-        configured = true;
+        int per_cu = 0, dev = 0;
+        hipDeviceProp_t prop;
+        DRC_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, proj_kernel<NT, AK, EPI>, kPT, C::kLds));
+        DRC_HIP(hipGetDevice(&dev));
+        DRC_HIP(hipGetDeviceProperties(&prop, dev));
+        resident = (per_cu < 1 ? 1 : per_cu) * prop.multiProcessorCount;
     }
     const int n_tiles = (p.rows + C::BM - 1) / C::BM;
-    int grid = 512;                                    // two resident workgroups per CU
+    int grid = resident;
     if (grid > n_tiles) grid = n_tiles;
     hipLaunchKernelGGL((proj_kernel<NT, AK, EPI>), dim3((unsigned)grid), dim3(kPT), C::kLds, s, p);
     DRC_HIP(hipGetLastError());
