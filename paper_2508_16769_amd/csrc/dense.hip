@@ -458,13 +458,14 @@ int launch_gemm(const GemmOperand* segs, int nseg, int64_t rows, int D, GemmEpil
 
 // ---------------------------------------------------------------------------------------------------
 // weight gradients  dW[D,D] = A^T B  (reduction over the graph's rows).  Persistent workgroups reduce a
-// contiguous slab of rows each: 32-row chunks of A and B are double-buffered through LDS (loads of the
+// contiguous slab of rows each: 16- or 32-row chunks of A and B are double-buffered through LDS (loads of the
 // next chunk in flight during the multiply of the current one), the full D x D accumulator lives in MFMA
 // registers (wavefront w owns row-tile w of dW), and the per-workgroup partials are summed by a second
 // kernel in a fixed order (deterministic, no atomics).
 // ---------------------------------------------------------------------------------------------------
-constexpr int kWgRC = 32;                  // rows staged per step
-constexpr int kWgTPR = kPT / kWgRC;        // threads sharing one chunk row when A arrives as CBSR
+// rows staged per step: 16 at D = 128 (smaller staging registers: three wavefronts per SIMD), 32 below
+__host__ __device__ constexpr int wg_rows(int nt) { return nt == 4 ? 16 : 32; }
+constexpr int kWgRC = 32;                  // row slabs of the workgroups are multiples of this
 constexpr int kWgCP = 4;                   // CBSR pairs per thread prefetched into registers
 
 struct WgradParams {
@@ -475,10 +476,12 @@ struct WgradParams {
 };
 
 template <int NT, bool ACBSR, bool MASKED>
-__global__ __launch_bounds__(kPT) void wgrad_partial_kernel(WgradParams p) {
+__global__ __launch_bounds__(kPT, (NT == 4 ? 3 : 2)) void wgrad_partial_kernel(WgradParams p) {
+    constexpr int kWgRC = wg_rows(NT);           // shadows the slab granule: rows per staged chunk here
+    constexpr int kWgTPR = kPT / kWgRC;          // threads sharing one chunk row when A arrives as CBSR
     constexpr int D = NT * 32;
     constexpr int LD = D + 4;
-    constexpr int F4 = kWgRC * D / 4 / kPT;      // float4 per thread per operand chunk (= NT)
+    constexpr int F4 = kWgRC * D / 4 / kPT;      // float4 per thread per operand chunk
     extern __shared__ __align__(16) float smem[];
     float* const sA0 = smem;
     float* const sB0 = sA0 + kWgRC * LD;
@@ -653,7 +656,7 @@ size_t wgrad_scratch_bytes(int64_t rows, int D) { return sizeof(float) * (size_t
 
 template <int NT, bool ACBSR, bool MASKED>
 static int launch_wgrad_kernel(const WgradParams& p, int nb, hipStream_t s) {
-    constexpr size_t lds = sizeof(float) * 4 * kWgRC * (NT * 32 + 4);
+    constexpr size_t lds = sizeof(float) * 4 * wg_rows(NT) * (NT * 32 + 4);
     static bool configured = false;
     if (!configured) {
         DRC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&wgrad_partial_kernel<NT, ACBSR, MASKED>),
