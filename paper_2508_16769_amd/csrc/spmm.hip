@@ -16,9 +16,13 @@
 //   * Edge records (source column, edge value) are staged into LDS in sorted-row order with independent
 //     coalesced loads.  A group then consumes its rows as ONE stream of records across row boundaries,
 //     so the gather pipeline never drains between rows (rows have only a handful of edges).
-//   * Gathers are issued in two ping-pong batches of several edges per group: while one batch is being
+//   * Gathers are issued in two ping-pong batches of a few edges per group: while one batch is being
 //     accumulated the other is in flight, and no load in the loop is conditional (exhausted lanes gather
-//     a valid dummy row), which lets the compiler wait on exactly the older batch.
+//     a valid dummy row), which lets the compiler wait on exactly the older batch.  The batch depth is
+//     chosen per k so that a wavefront stays within about 80 VGPRs and six wavefronts fit a SIMD: these
+//     kernels wait on memory most of the time, and the number of wavefronts that can take turns matters
+//     more than the depth of one wavefront's own pipeline (measured: 4 -> 6 wavefronts per SIMD, -3 %
+//     of the whole layer step).
 //   * Workgroup ids are remapped so each XCD walks a contiguous range of row blocks: neighbouring rows of
 //     the spatially local `near` relation gather overlapping source rows, which then hit in that XCD's L2.
 //
@@ -44,7 +48,8 @@ constexpr int kLPE = 8;          // lanes per row group
 constexpr int kNG = kWave / kLPE;  // groups per wavefront
 constexpr int kRW = 32;          // rows per wavefront-workgroup
 constexpr int kSolo = 32;        // rows with more edges are walked by all 8 groups together
-constexpr int kCap = 512;        // edge records staged in LDS per pass (rows never straddle passes)
+constexpr int kCap = 256;        // edge records staged in LDS per pass (rows never straddle passes); 2 KB keeps
+                                 // a forward workgroup below 7 KB of LDS, i.e. 23 workgroups per CU
 constexpr int kStageIters = kCap / kWave;
 constexpr int kBufPad = 4;       // row buffers are D + 4 words apart: group g starts 4 banks after group g-1
 constexpr unsigned kValid = 0x80000000u, kLast = 0x40000000u, kRowMask = 0x0000ffffu;
@@ -409,9 +414,9 @@ int launch_spmm_fwd(const dr_csr* A, const float* xs_vals, const uint16_t* xs_id
                        H, M, D, k, n_tiles, per_xcd, vec_store)
     switch (kpl) {
         case 1: DRC_LAUNCH_FWD(1, 4); break;
-        case 2: DRC_LAUNCH_FWD(2, 4); break;
-        case 4: DRC_LAUNCH_FWD(4, 4); break;
-        case 8: DRC_LAUNCH_FWD(8, 2); break;
+        case 2: DRC_LAUNCH_FWD(2, 3); break;
+        case 4: DRC_LAUNCH_FWD(4, 2); break;
+        case 8: DRC_LAUNCH_FWD(8, 1); break;
         case 16: DRC_LAUNCH_FWD(16, 1); break;
         default: DRC_LAUNCH_FWD(0, 1); break;
     }
@@ -610,8 +615,8 @@ int launch_spmm_bwd(const dr_csr* At, const float* dH, const uint16_t* xs_idx, i
     switch (kpl) {
         case 1: DRC_LAUNCH_BWD(1, 4); break;
         case 2: DRC_LAUNCH_BWD(2, 4); break;
-        case 4: DRC_LAUNCH_BWD(4, 4); break;
-        default: DRC_LAUNCH_BWD(8, 2); break;
+        case 4: DRC_LAUNCH_BWD(4, 2); break;
+        default: DRC_LAUNCH_BWD(8, 1); break;
     }
 #undef DRC_LAUNCH_BWD
     DRC_HIP(hipGetLastError());
