@@ -4,7 +4,8 @@
 // One wavefront owns one row at a time.  Lane l holds columns l, 64+l, 128+l, ... (coalesced dword
 // loads).  Values are mapped to order-preserving unsigned keys; the k-th largest key is found by a
 // most-significant-bit-first search in which every step is one v_cmp per register plus a scalar
-// popcount of the ballot, with an early exit once a probe isolates exactly k elements; compaction
+// popcount of the ballot, started below the previous row's sign and exponent bits when two probes confirm
+// them, and with an early exit once a probe isolates exactly k elements; compaction
 // positions come from mbcnt prefix counts of the keep-ballots, which yields ascending column order for
 // free.
 #include "dr_internal.h"
@@ -39,6 +40,7 @@ __global__ __launch_bounds__(256) void topk_rows_kernel(const float* __restrict_
 #pragma unroll
         for (int s = 0; s < EPL; ++s) dst[s] = __builtin_nontemporal_load(x + min(s * kWave + lane, D - 1));   // read once
     };
+    uint32_t t_hint = 0;                                      // threshold of the previous row of this wavefront
     auto select_row = [&](const float (&val)[EPL], int row) {
         uint32_t key[EPL];
 #pragma unroll
@@ -46,8 +48,24 @@ __global__ __launch_bounds__(256) void topk_rows_kernel(const float* __restrict_
         // T = largest threshold with count(key >= T) >= k  == the k-th largest key.  The search stops as
         // soon as a probe separates exactly k elements: then {key >= T} is already the answer, which on
         // tie-free data happens after about a dozen of the 32 bits.
+        // The sign and exponent bits of T rarely change from one row to the next: probe the previous row's
+        // leading nine bits first (two counts) and, if T does lie in that binade, search only below them.
         uint32_t T = 0;
-        for (int bit = 31; bit >= 0; --bit) {
+        int top = 31;
+        {
+            const uint32_t lo = t_hint & 0xff800000u, hi = lo + 0x00800000u;     // hi wraps to 0 in the last binade
+            int c_lo = 0, c_hi = 0;
+#pragma unroll
+            for (int s = 0; s < EPL; ++s) {
+                c_lo += __popcll(__ballot(key[s] >= lo));
+                c_hi += hi ? __popcll(__ballot(key[s] >= hi)) : 0;
+            }
+            if (c_lo >= k && c_hi < k) {
+                T = lo;
+                top = (c_lo == k) ? -1 : 22;          // exactly k at or above the binade's floor: done
+            }
+        }
+        for (int bit = top; bit >= 0; --bit) {
             uint32_t cand = T | (1u << bit);
             int cnt = 0;
 #pragma unroll
@@ -55,6 +73,7 @@ __global__ __launch_bounds__(256) void topk_rows_kernel(const float* __restrict_
             if (cnt >= k) T = cand;
             if (cnt == k) break;
         }
+        t_hint = T;
         int n_gt = 0;
 #pragma unroll
         for (int s = 0; s < EPL; ++s) n_gt += __popcll(__ballot(key[s] > T));
