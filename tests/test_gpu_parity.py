@@ -231,10 +231,12 @@ LAYER_CASES = [
     ("tiny", 1, dict(Nc=1500, Nn=1000, grid=(50, 30), D=128, k=32)),  # ragged against the 128-row tiles
     ("tiny", 2, dict(Nc=333, Nn=90, grid=(37, 9), D=32, k=5)),
     ("small", 0, {}),                                              # 60 000 cells, 40 000 nets, D=64, k=16
+    ("tiny", 3, dict(Nc=700, Nn=450, grid=(35, 20), D=96, k=24)),     # three column slabs, one idle wavefront
+    ("tiny", 4, dict(Nc=513, Nn=300, grid=(27, 19), D=64, k=64)),     # k = D: D-ReLU is the identity
 ]
 
 
-@pytest.mark.parametrize("name,seed,override", LAYER_CASES, ids=["tiny", "ragged128", "odd32", "small"])
+@pytest.mark.parametrize("name,seed,override", LAYER_CASES, ids=["tiny", "ragged128", "odd32", "small", "D96_k24", "D64_kD"])
 def test_heteroconv_fwd_bwd_parity(name, seed, override):
     w, g, T = _layer_case(name, seed, **override)
     D, k = w["D"], w["k"]
@@ -342,4 +344,38 @@ def test_heteroconv_transposes_match_oracle():
             ctypes.c_void_p(got_ci.data_ptr()), ctypes.c_void_p(t.colidx), ctypes.c_size_t(4 * pat.nnz), 3)
         torch.cuda.synchronize()
         assert np.array_equal(got_ci.cpu().numpy(), o_ci)
+    layer.heteroconv_destroy()
+
+
+def test_heteroconv_is_bit_reproducible_and_stream_agnostic():
+    """No atomics on results and fixed summation orders: two runs, with the relations on one stream or on three,
+    launched from the default or from a side stream, give bit-identical outputs."""
+    w, g, T = _layer_case("tiny", 5, Nc=3000, Nn=2000, grid=(60, 50), D=128, k=32)
+    D, k = w["D"], w["k"]
+    near = P.device_relation(g.near, P.DR_NORM_MEAN)
+    pins = P.device_relation(g.pins, P.DR_NORM_MEAN)
+    pinned = P.device_relation(g.pinned, P.DR_NORM_SYM)
+    layer = P.HeteroConv(near, pins, pinned, D, k, k)
+    Wd = {n: dev(T.W[n]) for n in P.WEIGHT_NAMES}
+    Xc, Xn, dYc, dYn = dev(T.X_cell), dev(T.X_net), dev(T.dY_cell), dev(T.dY_net)
+
+    def run(mode, stream):
+        layer.heteroconv_set_overlap(mode)
+        saved = layer.alloc_saved()
+        Yc = torch.full((g.Nc, D), float("nan"), dtype=torch.float32, device="cuda")
+        Yn = torch.full((g.Nn, D), float("nan"), dtype=torch.float32, device="cuda")
+        dXc, dXn = torch.empty_like(Yc), torch.empty_like(Yn)
+        dW = {n: torch.empty((D, D), dtype=torch.float32, device="cuda") for n in P.WEIGHT_NAMES}
+        torch.cuda.synchronize()
+        layer.heteroconv_fwd(Xc, Xn, Wd, Yc, Yn, saved, stream=stream)
+        layer.heteroconv_bwd(dYc, dYn, Wd, saved, dXc, dXn, dW, stream=stream)
+        torch.cuda.synchronize()
+        return [Yc, Yn, dXc, dXn, saved["mask"], saved["H_near"]] + [dW[n] for n in P.WEIGHT_NAMES]
+
+    side = torch.cuda.Stream()
+    ref = run(P.DR_OVERLAP_OFF, None)
+    for mode, stream in ((P.DR_OVERLAP_OFF, None), (P.DR_OVERLAP_ON, None), (P.DR_OVERLAP_ON, side), (P.DR_OVERLAP_OFF, side)):
+        out = run(mode, stream)
+        for a, b in zip(ref, out):
+            assert torch.equal(a, b), (mode, stream is side)
     layer.heteroconv_destroy()
