@@ -16,7 +16,6 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950",
     # keep the compiler from forming packed-fp32 VALU ops
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-munsafe-fp-atomics",          # LDS float adds become ds_add_f32
     "-Wall", "-Wno-unused-command-line-argument",
 ]
 

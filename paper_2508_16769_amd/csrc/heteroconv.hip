@@ -271,7 +271,7 @@ int heteroconv_fwd(dr_heteroconv* c, const float* X_cell, const float* X_net, co
     const int D = c->D;
 
     DRC_HIP(hipEventRecord(c->ev_fork, user));
-    for (int i = 0; i < 3; ++i) DRC_HIP(hipStreamWaitEvent(c->st[i], c->ev_fork, 0));
+    for (int i = 0; i < (ov ? 3 : 1); ++i) DRC_HIP(hipStreamWaitEvent(c->st[i], c->ev_fork, 0));   // only the streams that get work
 
     // Enqueue order (it is the execution order when all relations share one stream): every D-ReLU output is
     // gathered right after it is written, while it is still resident in the memory-side cache; the random
@@ -335,7 +335,7 @@ int heteroconv_bwd(dr_heteroconv* c, const float* dY_cell, const float* dY_net, 
     const int D = c->D;
 
     DRC_HIP(hipEventRecord(c->ev_fork, user));
-    for (int i = 0; i < 3; ++i) DRC_HIP(hipStreamWaitEvent(c->st[i], c->ev_fork, 0));
+    for (int i = 0; i < (ov ? 3 : 1); ++i) DRC_HIP(hipStreamWaitEvent(c->st[i], c->ev_fork, 0));   // only the streams that get work
 
     // ---- near stream: dH_near, its transposed SpMM (first piece of dXs_cell), near weight gradients ----
     {
