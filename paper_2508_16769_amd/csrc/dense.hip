@@ -21,6 +21,7 @@
 // MFMA pipe, not by HBM, once the tiles stream (arithmetic intensity D/4 flop per byte moved).
 #include "dr_internal.h"
 
+#include <atomic>
 #include <type_traits>
 
 namespace drc {
@@ -389,8 +390,9 @@ __global__ __launch_bounds__(kPT, (EPI == kEpiStore ? (AK == kACbsrDense ? 2 : 4
 template <int NT, int AK, int EPI>
 static int launch_proj(const GemmParams& p, hipStream_t s) {
     using C = ProjCfg<NT>;
-    static int resident = 0;                           // persistent workgroups = what fits the chip at once
-    if (!resident) {
+    static std::atomic<int> resident_cache{0};         // persistent workgroups = what fits the chip at once
+    int resident = resident_cache.load(std::memory_order_acquire);
+    if (!resident) {                                   // concurrent first calls repeat the query: same answer
         DRC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&proj_kernel<NT, AK, EPI>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::kLds));
         int per_cu = 0, dev = 0;
@@ -399,6 +401,7 @@ static int launch_proj(const GemmParams& p, hipStream_t s) {
         DRC_HIP(hipGetDevice(&dev));
         DRC_HIP(hipGetDeviceProperties(&prop, dev));
         resident = (per_cu < 1 ? 1 : per_cu) * prop.multiProcessorCount;
+        resident_cache.store(resident, std::memory_order_release);
     }
     const int n_tiles = (p.rows + C::BM - 1) / C::BM;
     int grid = resident;
@@ -657,11 +660,11 @@ size_t wgrad_scratch_bytes(int64_t rows, int D) { return sizeof(float) * (size_t
 template <int NT, bool ACBSR, bool MASKED>
 static int launch_wgrad_kernel(const WgradParams& p, int nb, hipStream_t s) {
     constexpr size_t lds = sizeof(float) * 4 * wg_rows(NT) * (NT * 32 + 4);
-    static bool configured = false;
-    if (!configured) {
+    static std::atomic<bool> configured{false};
+    if (!configured.load(std::memory_order_acquire)) {
         DRC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&wgrad_partial_kernel<NT, ACBSR, MASKED>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        configured = true;
+        configured.store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL((wgrad_partial_kernel<NT, ACBSR, MASKED>), dim3((unsigned)nb), dim3(kPT), lds, s, p);
     DRC_HIP(hipGetLastError());

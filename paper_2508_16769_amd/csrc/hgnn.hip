@@ -14,11 +14,14 @@
 
 #include <cmath>
 #include <new>
+#include <string>
+#include <thread>
 #include <vector>
 
 namespace drc {
 
 constexpr int kHeadBlocks = 64;   // workgroups (partials) per sub-graph in the read-out kernels
+constexpr int kMaxWorkers = 8;    // host threads that enqueue sub-graphs side by side
 
 __global__ __launch_bounds__(256) void relu_inplace(float4* __restrict__ y, size_t n4) {
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (size_t)gridDim.x * 256) {
@@ -313,7 +316,9 @@ int hgnn_train_step(dr_hgnn* m, const float* const* X_cell, const float* const* 
     const float scale = (float)(2.0 / (double)m->n_cells_total);
 
     DRC_HIP(hipEventRecord(m->fork, user));
-    for (int q = 0; q < m->n_graphs; ++q) {
+    // One sub-graph = one stream = one host thread: a step of small sub-graphs issues several hundred launches
+    // and event operations, and a single host thread cannot enqueue them as fast as the GPU drains them.
+    auto enqueue_graph = [&](int q) -> int {
         GraphState& gs = m->g[q];
         hipStream_t s = gs.stream;
         DRC_HIP(hipStreamWaitEvent(s, m->fork, 0));
@@ -353,6 +358,25 @@ int hgnn_train_step(dr_hgnn* m, const float* const* X_cell, const float* const* 
         }
         DRC_HIP(hipGetLastError());
         DRC_HIP(hipEventRecord(gs.done, s));
+        return DR_OK;
+    };
+    if (m->n_graphs == 1) {
+        DRC_TRY(enqueue_graph(0));
+    } else {
+        const int n_workers = m->n_graphs < kMaxWorkers ? m->n_graphs : kMaxWorkers;
+        std::vector<int> rcs(n_workers, DR_OK);
+        std::vector<std::string> errs(n_workers);
+        std::vector<std::thread> workers;
+        workers.reserve(n_workers);
+        for (int w = 0; w < n_workers; ++w)
+            workers.emplace_back([&, w]() {
+                if (hipSetDevice(m->device) != hipSuccess) { rcs[w] = DR_ERR_HIP; errs[w] = "hipSetDevice failed in a worker thread"; return; }
+                for (int q = w; q < m->n_graphs && rcs[w] == DR_OK; q += n_workers) rcs[w] = enqueue_graph(q);
+                if (rcs[w] != DR_OK) errs[w] = dr_last_error();      // the error text is per thread: hand it over
+            });
+        for (auto& t : workers) t.join();
+        for (int w = 0; w < n_workers; ++w)
+            if (rcs[w] != DR_OK) return fail(rcs[w], "%s", errs[w].c_str());
     }
     for (int q = 0; q < m->n_graphs; ++q) DRC_HIP(hipStreamWaitEvent(user, m->g[q].done, 0));
 
