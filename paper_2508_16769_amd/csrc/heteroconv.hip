@@ -20,7 +20,7 @@ const char* const kKernelNames[kNumKernels] = {
     "dproj.near", "dr_spmm_bwd.near", "wgrad.neigh_near", "wgrad.self_near", "dproj.pins", "dr_spmm_bwd.pins",
     "dself.near+dX", "wgrad.neigh_pins", "wgrad.self_pins", "dproj.pinned",
     "dr_spmm_bwd.pinned", "dself.pins+dX", "wgrad.pinned"};
-struct TimedLaunch { int id; hipEvent_t start, stop; };
+struct TimedLaunch { int id; hipEvent_t start, stop; bool start_shared; };   // start_shared: start is the previous launch's stop
 }  // namespace
 
 struct dr_heteroconv {
@@ -43,6 +43,9 @@ struct dr_heteroconv {
     bool profile;
     std::vector<TimedLaunch>* timed;      // launches recorded since the last heteroconv_kernel_times
     std::vector<hipEvent_t>* event_pool;  // idle timing events
+    hipEvent_t chain_stop;                // stop event of the previous timed launch of this call, when it can serve
+    hipStream_t chain_stream;             //   as the start of the next one (same stream, nothing but launches between)
+    bool chain_ok;                        // all relations on one stream: consecutive launches run back to back
 };
 
 using namespace drc;
@@ -69,7 +72,7 @@ void release(dr_heteroconv* c) {
     for (hipEvent_t* e : evs)
         if (*e) (void)hipEventDestroy(*e);
     if (c->timed) {
-        for (TimedLaunch& t : *c->timed) { (void)hipEventDestroy(t.start); (void)hipEventDestroy(t.stop); }
+        for (TimedLaunch& t : *c->timed) { if (!t.start_shared) (void)hipEventDestroy(t.start); (void)hipEventDestroy(t.stop); }
         delete c->timed;
     }
     if (c->event_pool) {
@@ -79,21 +82,36 @@ void release(dr_heteroconv* c) {
     delete c;
 }
 
-// Brackets one launch with timing events on its own stream when profiling is on.
+// Brackets one launch with timing events on its own stream when profiling is on.  With all relations on one
+// stream the launches of a call run back to back, so the stop event of one launch also serves as the start of
+// the next: one event record per launch instead of two (each record is a packet the GPU has to process).
 struct ScopedTiming {
     dr_heteroconv* c; hipStream_t s; TimedLaunch t; bool on;
-    ScopedTiming(dr_heteroconv* c_, int id, hipStream_t s_) : c(c_), s(s_), t{id, nullptr, nullptr}, on(false) {
+    hipEvent_t take() {
+        hipEvent_t e = nullptr;
+        if (!c->event_pool->empty()) { e = c->event_pool->back(); c->event_pool->pop_back(); }
+        else if (hipEventCreate(&e) != hipSuccess) e = nullptr;
+        return e;
+    }
+    ScopedTiming(dr_heteroconv* c_, int id, hipStream_t s_) : c(c_), s(s_), t{id, nullptr, nullptr, false}, on(false) {
         if (!c->profile) return;
-        for (hipEvent_t* e : {&t.start, &t.stop}) {
-            if (!c->event_pool->empty()) { *e = c->event_pool->back(); c->event_pool->pop_back(); }
-            else if (hipEventCreate(e) != hipSuccess) { *e = nullptr; }
+        if (c->chain_ok && c->chain_stop && c->chain_stream == s) {
+            t.start = c->chain_stop;
+            t.start_shared = true;
+            t.stop = take();
+            on = t.stop != nullptr;
+        } else {
+            t.start = take();
+            t.stop = take();
+            if (t.start && t.stop && hipEventRecord(t.start, s) == hipSuccess) on = true;
         }
-        if (t.start && t.stop && hipEventRecord(t.start, s) == hipSuccess) on = true;
     }
     ~ScopedTiming() {
         if (!on) return;
         (void)hipEventRecord(t.stop, s);
         c->timed->push_back(t);
+        c->chain_stop = t.stop;
+        c->chain_stream = s;
     }
 };
 
@@ -223,7 +241,7 @@ int heteroconv_kernel_times(dr_heteroconv* ctx, double* ms_sum, int64_t* launche
     for (TimedLaunch& t : *ctx->timed) {
         float ms = 0.f;
         if (hipEventElapsedTime(&ms, t.start, t.stop) == hipSuccess) { ms_sum[t.id] += ms; launches[t.id] += 1; }
-        ctx->event_pool->push_back(t.start);
+        if (!t.start_shared) ctx->event_pool->push_back(t.start);
         ctx->event_pool->push_back(t.stop);
     }
     ctx->timed->clear();
@@ -268,6 +286,7 @@ int heteroconv_fwd(dr_heteroconv* c, const float* X_cell, const float* X_net, co
     hipStream_t user = as_stream(stream);
     const bool ov = relations_overlap(c);
     hipStream_t s_near = c->st[0], s_pins = ov ? c->st[1] : c->st[0], s_pinned = ov ? c->st[2] : c->st[0];
+    c->chain_stop = nullptr; c->chain_ok = !ov;
     const int D = c->D;
 
     DRC_HIP(hipEventRecord(c->ev_fork, user));
@@ -332,6 +351,7 @@ int heteroconv_bwd(dr_heteroconv* c, const float* dY_cell, const float* dY_net, 
     hipStream_t user = as_stream(stream);
     const bool ov = relations_overlap(c);
     hipStream_t s_near = c->st[0], s_pins = ov ? c->st[1] : c->st[0], s_pinned = ov ? c->st[2] : c->st[0];
+    c->chain_stop = nullptr; c->chain_ok = !ov;
     const int D = c->D;
 
     DRC_HIP(hipEventRecord(c->ev_fork, user));
