@@ -142,14 +142,19 @@ typedef struct dr_heteroconv_wgrads {         /* device pointers, each [D,D]; ov
 } dr_heteroconv_wgrads;
 
 typedef struct dr_heteroconv_saved {          /* caller-owned device buffers written by fwd, read by bwd */
-    float*    vals_cell;  /* [Nc,k_cell] CBSR of the cell embeddings  */
-    uint16_t* idx_cell;   /* [Nc,k_cell]                              */
-    float*    vals_net;   /* [Nn,k_net]  CBSR of the net embeddings   */
-    uint16_t* idx_net;    /* [Nn,k_net]                               */
+    float*    vals_cell;  /* [Nc,k_cell] CBSR of the cell embeddings (k_near with one K per relation)  */
+    uint16_t* idx_cell;   /* [Nc,k_cell]                                                               */
+    float*    vals_net;   /* [Nn,k_net]  CBSR of the net embeddings (k_pinned with one K per relation) */
+    uint16_t* idx_net;    /* [Nn,k_net]                                                                */
     float*    H_near;     /* [Nc,D] aggregated messages per relation  */
     float*    H_pins;     /* [Nn,D]                                   */
     float*    H_pinned;   /* [Nc,D]                                   */
     uint8_t*  mask;       /* [Nc,D] 1 where the near branch won the max-merge */
+    /* Only for contexts of heteroconv_create_per_relation; ignored (may be NULL) where the widths coincide: */
+    float*    vals_cell_pins;  /* [Nc,k_pins] CBSR of the cells as the pins module reads them, if k_pins != k_near   */
+    uint16_t* idx_cell_pins;   /* [Nc,k_pins]                                                                         */
+    float*    vals_net_self;   /* [Nn,k_pins] CBSR of the nets as the pins self term reads them, if k_pins != k_pinned */
+    uint16_t* idx_net_self;    /* [Nn,k_pins]                                                                         */
 } dr_heteroconv_saved;
 
 /*
@@ -162,6 +167,21 @@ typedef struct dr_heteroconv_saved {          /* caller-owned device buffers wri
  */
 int heteroconv_create(dr_heteroconv** ctx, const dr_csr* near, const dr_csr* pins, const dr_csr* pinned,
                       int32_t D, int32_t k_cell, int32_t k_net);
+
+/*
+ * The same context with one K per edge type (paper Section 4.3: graph-specific k_near, k_pins, k_pinned).  D-ReLU
+ * belongs to the module that reads the embedding, so every input of a module is sparsified with that module's K:
+ *     Z_near   = f_{k_near}(X_cell) Wself_near + (A_near   f_{k_near}(X_cell))  Wneigh_near
+ *     Y_net    = f_{k_pins}(X_net)  Wself_pins + (A_pins   f_{k_pins}(X_cell))  Wneigh_pins
+ *     Z_pinned =                                 (A_pinned f_{k_pinned}(X_net)) W_pinned
+ * A node type read with two different K gets two CBSRs (the extra buffers of dr_heteroconv_saved); in the backward
+ * every use sends its gradient through its own selection and the pieces add up in the dense dX.
+ * heteroconv_get_k reports the four widths a context uses: cells for near, cells for pins, nets for the pins self
+ * term, nets for pinned (k_cell, k_cell, k_net, k_net for heteroconv_create).
+ */
+int heteroconv_create_per_relation(dr_heteroconv** ctx, const dr_csr* near, const dr_csr* pins, const dr_csr* pinned,
+                                   int32_t D, int32_t k_near, int32_t k_pins, int32_t k_pinned);
+int heteroconv_get_k(const dr_heteroconv* ctx, int32_t* k_near, int32_t* k_pins, int32_t* k_self, int32_t* k_pinned);
 
 /*
  * Forward of one layer.  Inputs X_cell[Nc,D], X_net[Nn,D]; outputs Y_cell[Nc,D], Y_net[Nn,D] and every
@@ -243,8 +263,8 @@ typedef struct dr_hgnn_layer_buffers {        /* device pointers owned by the mo
 int64_t hgnn_num_params(int32_t n_layers, int32_t D);
 
 /*
- * Build the model state for n_graphs sub-graphs (one heteroconv context each, all with the same D and k)
- * and n_layers layers: allocates every activation, saved-state and gradient buffer and one stream per
+ * Build the model state for n_graphs sub-graphs (one heteroconv context each, all with the same D; every
+ * sub-graph keeps the K its context was created with, per node type or per relation) and n_layers layers: allocates every activation, saved-state and gradient buffer and one stream per
  * sub-graph.  The contexts stay owned by the caller and must outlive the model.  Synchronises the device.
  */
 int hgnn_create(dr_hgnn** model, int32_t n_graphs, dr_heteroconv* const* graphs, int32_t n_layers);

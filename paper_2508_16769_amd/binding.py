@@ -32,7 +32,7 @@ EXPORTS = (
     "dr_last_error", "dr_abi_version", "dr_topk", "dr_spmm_fwd", "dr_spmm_bwd",
     "dr_csr_transpose_workspace_bytes", "dr_csr_transpose",
     "dr_csr_normalize_workspace_bytes", "dr_csr_normalize",
-    "heteroconv_create", "heteroconv_fwd", "heteroconv_bwd", "heteroconv_get_transpose", "heteroconv_destroy",
+    "heteroconv_create", "heteroconv_create_per_relation", "heteroconv_get_k", "heteroconv_fwd", "heteroconv_bwd", "heteroconv_get_transpose", "heteroconv_destroy",
     "heteroconv_profile", "heteroconv_num_kernels", "heteroconv_kernel_name", "heteroconv_kernel_times",
     "heteroconv_set_overlap",
     "hgnn_num_params", "hgnn_create", "hgnn_train_step", "hgnn_get_layer_buffers", "hgnn_destroy",
@@ -56,7 +56,8 @@ class dr_heteroconv_weights(ctypes.Structure):
 
 class dr_heteroconv_saved(ctypes.Structure):
     _fields_ = [(n, ctypes.c_void_p) for n in
-                ("vals_cell", "idx_cell", "vals_net", "idx_net", "H_near", "H_pins", "H_pinned", "mask")]
+                ("vals_cell", "idx_cell", "vals_net", "idx_net", "H_near", "H_pins", "H_pinned", "mask",
+                 "vals_cell_pins", "idx_cell_pins", "vals_net_self", "idx_net_self")]
 
 
 _lib = None
@@ -184,31 +185,57 @@ def dr_csr_normalize(mode: int, n_rows: int, n_cols: int, rowptr: torch.Tensor, 
 class HeteroConv:
     """Owner of a ``dr_heteroconv*`` context (heteroconv_create / heteroconv_destroy)."""
 
-    def __init__(self, near: Csr, pins: Csr, pinned: Csr, D: int, k_cell: int, k_net: int):
+    def __init__(self, near: Csr, pins: Csr, pinned: Csr, D: int, k_cell: Optional[int] = None,
+                 k_net: Optional[int] = None, per_relation: Optional[Sequence[int]] = None):
+        """Either (k_cell, k_net) -> heteroconv_create, or per_relation = (k_near, k_pins, k_pinned) ->
+        heteroconv_create_per_relation."""
         self._keep = (near, pins, pinned)
-        self.Nc, self.Nn, self.D, self.k_cell, self.k_net = near.n_rows, pins.n_rows, D, k_cell, k_net
+        self.Nc, self.Nn, self.D = near.n_rows, pins.n_rows, D
         self._ctx = ctypes.c_void_p(0)
         a, b, c = near.c(), pins.c(), pinned.c()
-        _check(load().heteroconv_create(ctypes.byref(self._ctx), ctypes.byref(a), ctypes.byref(b), ctypes.byref(c),
-                                        ctypes.c_int32(D), ctypes.c_int32(k_cell), ctypes.c_int32(k_net)))
+        if per_relation is not None:
+            if k_cell is not None or k_net is not None:
+                raise ValueError("give either (k_cell, k_net) or per_relation")
+            kn, kp, kq = (int(v) for v in per_relation)
+            _check(load().heteroconv_create_per_relation(
+                ctypes.byref(self._ctx), ctypes.byref(a), ctypes.byref(b), ctypes.byref(c), ctypes.c_int32(D),
+                ctypes.c_int32(kn), ctypes.c_int32(kp), ctypes.c_int32(kq)))
+        else:
+            _check(load().heteroconv_create(ctypes.byref(self._ctx), ctypes.byref(a), ctypes.byref(b), ctypes.byref(c),
+                                            ctypes.c_int32(D), ctypes.c_int32(k_cell), ctypes.c_int32(k_net)))
+        self.k_near, self.k_pins, self.k_self, self.k_pinned = self.heteroconv_get_k()
+        self.k_cell, self.k_net = self.k_near, self.k_pinned
+
+    def heteroconv_get_k(self):
+        ks = [ctypes.c_int32(0) for _ in range(4)]
+        _check(load().heteroconv_get_k(self._ctx, *[ctypes.byref(v) for v in ks]))
+        return tuple(int(v.value) for v in ks)
 
     def alloc_saved(self, device="cuda") -> Dict[str, torch.Tensor]:
         Nc, Nn, D = self.Nc, self.Nn, self.D
         f32, dev = torch.float32, device
-        return dict(
-            vals_cell=torch.empty((Nc, self.k_cell), dtype=f32, device=dev),
-            idx_cell=torch.empty((Nc, self.k_cell), dtype=torch.int16, device=dev),
-            vals_net=torch.empty((Nn, self.k_net), dtype=f32, device=dev),
-            idx_net=torch.empty((Nn, self.k_net), dtype=torch.int16, device=dev),
+        out = dict(
+            vals_cell=torch.empty((Nc, self.k_near), dtype=f32, device=dev),
+            idx_cell=torch.empty((Nc, self.k_near), dtype=torch.int16, device=dev),
+            vals_net=torch.empty((Nn, self.k_pinned), dtype=f32, device=dev),
+            idx_net=torch.empty((Nn, self.k_pinned), dtype=torch.int16, device=dev),
             H_near=torch.empty((Nc, D), dtype=f32, device=dev),
             H_pins=torch.empty((Nn, D), dtype=f32, device=dev),
             H_pinned=torch.empty((Nc, D), dtype=f32, device=dev),
             mask=torch.empty((Nc, D), dtype=torch.uint8, device=dev),
         )
+        if self.k_pins != self.k_near:
+            out["vals_cell_pins"] = torch.empty((Nc, self.k_pins), dtype=f32, device=dev)
+            out["idx_cell_pins"] = torch.empty((Nc, self.k_pins), dtype=torch.int16, device=dev)
+        if self.k_self != self.k_pinned:
+            out["vals_net_self"] = torch.empty((Nn, self.k_self), dtype=f32, device=dev)
+            out["idx_net_self"] = torch.empty((Nn, self.k_self), dtype=torch.int16, device=dev)
+        return out
 
     @staticmethod
     def _saved(saved: Dict[str, torch.Tensor]) -> dr_heteroconv_saved:
-        return dr_heteroconv_saved(*[saved[n].data_ptr() for n, _ in dr_heteroconv_saved._fields_])
+        return dr_heteroconv_saved(*[saved[n].data_ptr() if saved.get(n) is not None else 0
+                                     for n, _ in dr_heteroconv_saved._fields_])
 
     @staticmethod
     def _weights(W: Dict[str, torch.Tensor]) -> dr_heteroconv_weights:
@@ -283,7 +310,7 @@ class Hgnn:
 
     def __init__(self, graphs: Sequence["HeteroConv"], n_layers: int):
         self._graphs = list(graphs)
-        self.n_layers, self.D, self.k = n_layers, graphs[0].D, graphs[0].k_cell
+        self.n_layers, self.D = n_layers, graphs[0].D
         self._model = ctypes.c_void_p(0)
         arr = (ctypes.c_void_p * len(graphs))(*[g._ctx.value for g in graphs])
         _check(load().hgnn_create(ctypes.byref(self._model), ctypes.c_int32(len(graphs)), arr, ctypes.c_int32(n_layers)))
@@ -305,7 +332,7 @@ class Hgnn:
         _check(load().hgnn_get_layer_buffers(self._model, ctypes.c_int32(graph), ctypes.c_int32(layer), ctypes.byref(b),
                                              ctypes.byref(pred), ctypes.byref(dpred)))
         g = self._graphs[graph]
-        Nc, Nn, D, k = g.Nc, g.Nn, self.D, self.k
+        Nc, Nn, D = g.Nc, g.Nn, self.D
         f32 = torch.float32
         out = dict(
             X_cell=_view(b.X_cell, (Nc, D), f32), X_net=_view(b.X_net, (Nn, D), f32),
@@ -313,11 +340,19 @@ class Hgnn:
             dY_cell=_view(b.dY_cell, (Nc, D), f32), dY_net=_view(b.dY_net, (Nn, D), f32),
             dX_cell=_view(b.dX_cell, (Nc, D), f32), dX_net=_view(b.dX_net, (Nn, D), f32),
             pred=_view(pred.value, (Nc,), f32), dpred=_view(dpred.value, (Nc,), f32),
-            vals_cell=_view(b.saved.vals_cell, (Nc, k), f32), idx_cell=_view(b.saved.idx_cell, (Nc, k), torch.int16),
-            vals_net=_view(b.saved.vals_net, (Nn, k), f32), idx_net=_view(b.saved.idx_net, (Nn, k), torch.int16),
+            vals_cell=_view(b.saved.vals_cell, (Nc, g.k_near), f32),
+            idx_cell=_view(b.saved.idx_cell, (Nc, g.k_near), torch.int16),
+            vals_net=_view(b.saved.vals_net, (Nn, g.k_pinned), f32),
+            idx_net=_view(b.saved.idx_net, (Nn, g.k_pinned), torch.int16),
             H_near=_view(b.saved.H_near, (Nc, D), f32), H_pins=_view(b.saved.H_pins, (Nn, D), f32),
             H_pinned=_view(b.saved.H_pinned, (Nc, D), f32), mask=_view(b.saved.mask, (Nc, D), torch.uint8),
         )
+        if g.k_pins != g.k_near:
+            out["vals_cell_pins"] = _view(b.saved.vals_cell_pins, (Nc, g.k_pins), f32)
+            out["idx_cell_pins"] = _view(b.saved.idx_cell_pins, (Nc, g.k_pins), torch.int16)
+        if g.k_self != g.k_pinned:
+            out["vals_net_self"] = _view(b.saved.vals_net_self, (Nn, g.k_self), f32)
+            out["idx_net_self"] = _view(b.saved.idx_net_self, (Nn, g.k_self), torch.int16)
         out["dW"] = {n: _view(getattr(b.dW, n), (D, D), f32) for n in WEIGHT_NAMES}
         return out
 

@@ -56,7 +56,7 @@ extern "C" {
 
 const char* dr_last_error(void) { return g_err; }
 
-int dr_abi_version(void) { return 1; }
+int dr_abi_version(void) { return 2; }
 
 int dr_topk(const float* X, int64_t n, int32_t D, int32_t k, float* vals, uint16_t* idx, void* stream) {
     if (int rc = check_dk(D, k, "dr_topk")) return rc;

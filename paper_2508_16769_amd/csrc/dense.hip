@@ -53,10 +53,9 @@ struct GemmParams {
     int epi;
     float* out;
     uint8_t* mask_out;
-    const uint16_t* sample_idx;
-    int sample_k;
-    const float* compact;
+    SampleSet first, second;      // kEpiSampleDense(2): selections and compact gradients of the write-out
 };
+constexpr int kEpiSampleDense2 = 3;   // kEpiSampleDense with a second selection and/or no compact on the first
 
 struct PairRegs {
     float v[kCP];
@@ -86,6 +85,7 @@ template <int NT, int AK, int EPI>
 // wavefronts per SIMD the register budget is set for: 4 for the one-operand store kernels, 3 with the merge or
 // sampling epilogue (they hold the other branch / the pairs as well), 2 with two resident weight slabs
 __global__ __launch_bounds__(kPT, (EPI == kEpiStore ? (AK == kACbsrDense ? 2 : 4) : 3)) void proj_kernel(GemmParams p) {
+    constexpr bool kSample2 = (EPI == kEpiSampleDense2);
     using C = ProjCfg<NT>;
     constexpr int D = C::D, KS = C::KS, BM = C::BM, SPW = C::SPW, LDA = C::LDA, F4 = C::F4;
     constexpr int TPR = C::TPR, RPW = C::RPW;
@@ -163,6 +163,14 @@ __global__ __launch_bounds__(kPT, (EPI == kEpiStore ? (AK == kACbsrDense ? 2 : 4
             const int t = min(ppart + TPR * u, k - 1);
             pr.v[u] = vals[base + t];
             pr.c[u] = idx[base + t];
+        }
+    };
+    auto load_cols = [&](PairRegs& pr, const uint16_t* idx, int k, int tile) {       // columns only, values zero
+        const size_t base = (size_t)min(tile * BM + prow, p.rows - 1) * k;
+#pragma unroll
+        for (int u = 0; u < kCP; ++u) {
+            pr.v[u] = 0.f;
+            pr.c[u] = idx[base + min(ppart + TPR * u, k - 1)];
         }
     };
     auto zero_own_part = [&](float* rowp) {
@@ -291,7 +299,11 @@ __global__ __launch_bounds__(kPT, (EPI == kEpiStore ? (AK == kACbsrDense ? 2 : 4
             // what the epilogue of this tile consumes is requested first, then the next tile
             PairRegs pr;
             float prev[SPW][16];
-            if constexpr (EPI == kEpiSampleDense) load_pairs(pr, p.compact, p.sample_idx, p.sample_k, tile);
+            if constexpr (EPI == kEpiSampleDense) load_pairs(pr, p.first.compact, p.first.idx, p.first.k, tile);
+            if constexpr (kSample2) {
+                if (p.first.compact) load_pairs(pr, p.first.compact, p.first.idx, p.first.k, tile);
+                else load_cols(pr, p.first.idx, p.first.k, tile);
+            }
             // C rows of this lane: row0 + j*32 + 8*(r/4) + r%4, all at fixed offsets from one pointer
             const int row0 = tile * BM + rg * SPW * 32 + 4 * (lane >> 5);
             const size_t off0 = (size_t)row0 * D + 32 * ct + (lane & 31);
@@ -351,7 +363,7 @@ __global__ __launch_bounds__(kPT, (EPI == kEpiStore ? (AK == kACbsrDense ? 2 : 4
                 float* orow = bcur + prow * LDA;
                 const float* crow = bother + prow * LDA;
                 zero_own_part(orow);
-                const int k = p.sample_k;
+                const int k = p.first.k;
 #pragma unroll
                 for (int u = 0; u < kCP; ++u) {
                     const int t = ppart + TPR * u;
@@ -361,10 +373,26 @@ __global__ __launch_bounds__(kPT, (EPI == kEpiStore ? (AK == kACbsrDense ? 2 : 4
                 const size_t base = (size_t)min(tile * BM + prow, p.rows - 1) * k;
                 for (int u = kCP; u * TPR < k; ++u) {
                     const int t = ppart + TPR * u;
-                    const float v = p.compact[base + min(t, k - 1)];
-                    const int c = p.sample_idx[base + min(t, k - 1)];
+                    float v = 0.f;
+                    if (!kSample2 || p.first.compact) v = p.first.compact[base + min(t, k - 1)];
+                    const int c = p.first.idx[base + min(t, k - 1)];
                     const int col = t < k ? c : D;
                     orow[col] = v + crow[col];
+                }
+                if constexpr (kSample2) {
+                    // second selection: its compact gradient is added at its own columns (the columns of one row
+                    // are distinct, and a row's threads share a wavefront, so the updates do not collide)
+                    if (p.second.idx) {
+                        __builtin_amdgcn_wave_barrier();
+                        const int k2 = p.second.k;
+                        const size_t base2 = (size_t)min(tile * BM + prow, p.rows - 1) * k2;
+                        for (int u = 0; u * TPR < k2; ++u) {           // fetched here: no registers held across the multiply
+                            const int t = ppart + TPR * u;
+                            const float v = p.second.compact[base2 + min(t, k2 - 1)];
+                            const int c = p.second.idx[base2 + min(t, k2 - 1)];
+                            orow[t < k2 ? c : D] += v;
+                        }
+                    }
                 }
                 __builtin_amdgcn_wave_barrier();
 #pragma unroll
@@ -420,13 +448,15 @@ static int launch_proj_nt(const GemmParams& p, int ak, hipStream_t s) {
         case kADense * 10 + kEpiSampleDense: return launch_proj<NT, kADense, kEpiSampleDense>(p, s);
         case kADenseMasked * 10 + kEpiStore: return launch_proj<NT, kADenseMasked, kEpiStore>(p, s);
         case kADenseMasked * 10 + kEpiSampleDense: return launch_proj<NT, kADenseMasked, kEpiSampleDense>(p, s);
+        case kADense * 10 + kEpiSampleDense2: return launch_proj<NT, kADense, kEpiSampleDense2>(p, s);
+        case kADenseMasked * 10 + kEpiSampleDense2: return launch_proj<NT, kADenseMasked, kEpiSampleDense2>(p, s);
         case kACbsrDense * 10 + kEpiStore: return launch_proj<NT, kACbsrDense, kEpiStore>(p, s);
         default: return fail(DR_ERR_UNSUPPORTED, "projection operand kind %d with epilogue %d is not built", ak, p.epi);
     }
 }
 
 int launch_gemm(const GemmOperand* segs, int nseg, int64_t rows, int D, GemmEpilogue epi, float* out,
-                uint8_t* mask_out, const uint16_t* sample_idx, int sample_k, const float* compact, hipStream_t s) {
+                uint8_t* mask_out, SampleSet first, SampleSet second, hipStream_t s) {
     if (rows == 0) return DR_OK;
     GemmParams p{};
     for (int i = 0; i < nseg; ++i) p.seg[i] = segs[i];
@@ -435,9 +465,14 @@ int launch_gemm(const GemmOperand* segs, int nseg, int64_t rows, int D, GemmEpil
     p.epi = (int)epi;
     p.out = out;
     p.mask_out = mask_out;
-    p.sample_idx = sample_idx;
-    p.sample_k = sample_k;
-    p.compact = compact;
+    p.first = first;
+    p.second = second;
+    if (epi == kEpiSampleDense) {
+        if (first.k < 1 || !first.idx) return fail(DR_ERR_INVALID_ARG, "sampling epilogue without indices");
+        if (second.idx && (second.k < 1 || !second.compact))
+            return fail(DR_ERR_INVALID_ARG, "sampling epilogue: second selection without its compact gradient");
+        if (second.idx || !first.compact) p.epi = kEpiSampleDense2;
+    }
     int ak;
     if (nseg == 2) {
         if (!segs[0].cbsr_vals || !segs[0].cbsr_idx || segs[0].k < 1 || !segs[1].dense || segs[1].mask)
@@ -448,8 +483,6 @@ int launch_gemm(const GemmOperand* segs, int nseg, int64_t rows, int D, GemmEpil
     } else {
         return fail(DR_ERR_UNSUPPORTED, "projection with %d segments / a lone CBSR operand is not built", nseg);
     }
-    if (epi == kEpiSampleDense && (sample_k < 1 || !sample_idx || !compact))
-        return fail(DR_ERR_INVALID_ARG, "sampling epilogue without indices");
     switch (D / 32) {
         case 1: return launch_proj_nt<1>(p, ak, s);
         case 2: return launch_proj_nt<2>(p, ak, s);

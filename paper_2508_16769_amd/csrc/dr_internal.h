@@ -57,7 +57,8 @@ int launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t s);
 // shape of a layer context (heteroconv.hip owns the struct)
 struct HeteroDims {
     int64_t Nc, Nn;
-    int D, k_cell, k_net;
+    int D;
+    int k_near, k_pins, k_self, k_pinned;   // D-ReLU widths: cells for near / for pins, nets for the pins self term / for pinned
 };
 HeteroDims heteroconv_dims(const dr_heteroconv* c);
 
@@ -73,12 +74,18 @@ struct GemmOperand {              // one K-segment of C = sum_seg A_seg * B_seg
     int transpose_w;              // 0: B = W, 1: B = W^T
 };
 enum GemmEpilogue { kEpiStore = 0, kEpiMaxMerge = 1, kEpiSampleDense = 2 };
+struct SampleSet {                // a top-k selection [rows, k] and a compact gradient that lives on it
+    const uint16_t* idx;
+    int k;
+    const float* compact;         // [rows, k]; may be null in `first` (nothing to add to the sampled C)
+};
 // C[rows, D] = sum over segments; epilogue:
 //   kEpiStore       : out[rows,D] = C
 //   kEpiMaxMerge    : mask_out = (out >= C); out = max(out, C)        (out holds the near branch on entry)
-//   kEpiSampleDense : out[row,:] = 0 except out[row, idx[row,t]] = compact[row,t] + C[row, idx[row,t]]
+//   kEpiSampleDense : out[row,:] = 0, then out[row, first.idx[row,t]] = C[row, first.idx[row,t]] + first.compact[row,t],
+//                     then (if second.idx) out[row, second.idx[row,t]] += second.compact[row,t]
 int launch_gemm(const GemmOperand* segs, int nseg, int64_t rows, int D, GemmEpilogue epi, float* out,
-                uint8_t* mask_out, const uint16_t* sample_idx, int sample_k, const float* compact, hipStream_t s);
+                uint8_t* mask_out, SampleSet first, SampleSet second, hipStream_t s);
 
 struct WgradOperand {             // dW[D,D] = A^T B over `rows` rows
     const float* a_dense;         // [rows, D] or nullptr

@@ -10,12 +10,12 @@
 namespace {
 // kernel ids for the optional per-kernel timing (heteroconv_profile / heteroconv_kernel_times)
 enum KernelId {
-    kTopkCell, kTopkNet, kFwdNear, kFwdPins, kFwdPinned, kProjNear, kProjPins, kProjPinnedMerge,
+    kTopkCell, kTopkNet, kTopkCellPins, kTopkNetSelf, kFwdNear, kFwdPins, kFwdPinned, kProjNear, kProjPins, kProjPinnedMerge,
     kDhNear, kBwdNear, kWgNeighNear, kWgSelfNear, kDhPins, kBwdPins, kSelfNearSample,
     kWgNeighPins, kWgSelfPins, kDhPinned, kBwdPinned, kSelfPinsSample, kWgPinned, kNumKernels
 };
 const char* const kKernelNames[kNumKernels] = {
-    "dr_topk.cell", "dr_topk.net", "dr_spmm_fwd.near", "dr_spmm_fwd.pins", "dr_spmm_fwd.pinned",
+    "dr_topk.cell", "dr_topk.net", "dr_topk.cell.pins", "dr_topk.net.self", "dr_spmm_fwd.near", "dr_spmm_fwd.pins", "dr_spmm_fwd.pinned",
     "proj.near", "proj.pins", "proj.pinned+merge",
     "dproj.near", "dr_spmm_bwd.near", "wgrad.neigh_near", "wgrad.self_near", "dproj.pins", "dr_spmm_bwd.pins",
     "dself.near+dX", "wgrad.neigh_pins", "wgrad.self_pins", "dproj.pinned",
@@ -25,7 +25,10 @@ struct TimedLaunch { int id; hipEvent_t start, stop; bool start_shared; };   // 
 
 struct dr_heteroconv {
     int64_t Nc, Nn;
-    int D, k_cell, k_net;
+    int D;
+    // D-ReLU widths: k_near (cells, source and self term of near), k_pins (cells, source of pins), k_self (nets,
+    // self term of pins), k_pinned (nets, source of pinned).  Equal widths on one node type share one CBSR.
+    int k_near, k_pins, k_self, k_pinned;
     dr_csr A[3];        // near, pins, pinned (borrowed)
     dr_csr At[3];       // transposes (owned)
     void* owned[32];
@@ -34,8 +37,9 @@ struct dr_heteroconv {
     hipEvent_t ev_fork, ev_topk_cell, ev_topk_net, ev_near, ev_pins, ev_pinned, ev_gnear, ev_gpins;
     // backward scratch
     float* dH[3];       // [Nc,D], [Nn,D], [Nc,D]
-    float* dXs_cell;    // [Nc,k_cell]
-    float* dXs_net;     // [Nn,k_net]
+    float* dXs_cell;    // [Nc,k_near]  compact gradient at the near selection (both cell pieces when k_pins == k_near)
+    float* dXs_cell_b;  // [Nc,k_pins]  pins piece at its own selection (only when k_pins != k_near)
+    float* dXs_net;     // [Nn,k_pinned]
     float* wg_scratch[3];
     int device;
     int overlap;        // DR_OVERLAP_*: whether the relation pipelines run on separate streams
@@ -50,7 +54,9 @@ struct dr_heteroconv {
 
 using namespace drc;
 
-HeteroDims drc::heteroconv_dims(const dr_heteroconv* c) { return HeteroDims{c->Nc, c->Nn, c->D, c->k_cell, c->k_net}; }
+HeteroDims drc::heteroconv_dims(const dr_heteroconv* c) {
+    return HeteroDims{c->Nc, c->Nn, c->D, c->k_near, c->k_pins, c->k_self, c->k_pinned};
+}
 
 namespace {
 
@@ -117,10 +123,8 @@ struct ScopedTiming {
 
 }  // namespace
 
-extern "C" {
-
-int heteroconv_create(dr_heteroconv** ctx, const dr_csr* near, const dr_csr* pins, const dr_csr* pinned,
-                      int32_t D, int32_t k_cell, int32_t k_net) {
+static int create_impl(dr_heteroconv** ctx, const dr_csr* near, const dr_csr* pins, const dr_csr* pinned, int32_t D,
+                       int32_t k_near, int32_t k_pins, int32_t k_self, int32_t k_pinned) {
     DRC_REQUIRE(ctx != nullptr, "heteroconv_create: null ctx");
     *ctx = nullptr;
     if (int rc = check_csr(near, "heteroconv_create: near", true)) return rc;
@@ -130,8 +134,8 @@ int heteroconv_create(dr_heteroconv** ctx, const dr_csr* near, const dr_csr* pin
     const int64_t Nc = near->n_rows, Nn = pins->n_rows;
     DRC_REQUIRE(pins->n_cols == Nc, "heteroconv_create: pins must be Nn x Nc");
     DRC_REQUIRE(pinned->n_rows == Nc && pinned->n_cols == Nn, "heteroconv_create: pinned must be Nc x Nn");
-    DRC_REQUIRE(k_cell >= 1 && k_net >= 1, "heteroconv_create: k must be >= 1");
-    DRC_REQUIRE(k_cell <= D && k_net <= D, "heteroconv_create: k exceeds D");
+    DRC_REQUIRE(k_near >= 1 && k_pins >= 1 && k_self >= 1 && k_pinned >= 1, "heteroconv_create: k must be >= 1");
+    DRC_REQUIRE(k_near <= D && k_pins <= D && k_self <= D && k_pinned <= D, "heteroconv_create: k exceeds D");
     if (!(D == 32 || D == 64 || D == 96 || D == 128))
         return fail(DR_ERR_UNSUPPORTED, "heteroconv_create: D = %d not in {32,64,96,128}", D);
     DRC_REQUIRE(Nc * (int64_t)D < (int64_t(1) << 31) * 2 && Nn * (int64_t)D < (int64_t(1) << 31) * 2,
@@ -139,7 +143,8 @@ int heteroconv_create(dr_heteroconv** ctx, const dr_csr* near, const dr_csr* pin
 
     dr_heteroconv* c = new (std::nothrow) dr_heteroconv();
     DRC_REQUIRE(c != nullptr, "heteroconv_create: out of host memory");
-    c->Nc = Nc; c->Nn = Nn; c->D = D; c->k_cell = k_cell; c->k_net = k_net;
+    c->Nc = Nc; c->Nn = Nn; c->D = D;
+    c->k_near = k_near; c->k_pins = k_pins; c->k_self = k_self; c->k_pinned = k_pinned;
     c->A[0] = *near; c->A[1] = *pins; c->A[2] = *pinned;
     c->timed = new (std::nothrow) std::vector<TimedLaunch>();
     c->event_pool = new (std::nothrow) std::vector<hipEvent_t>();
@@ -182,10 +187,29 @@ int heteroconv_create(dr_heteroconv** ctx, const dr_csr* near, const dr_csr* pin
         if ((rc = dev_alloc(c, (void**)&c->dH[i], 4 * (size_t)drows[i] * D))) return bail(rc);
         if ((rc = dev_alloc(c, (void**)&c->wg_scratch[i], wgrad_scratch_bytes(Nc > Nn ? Nc : Nn, D)))) return bail(rc);
     }
-    if ((rc = dev_alloc(c, (void**)&c->dXs_cell, 4 * (size_t)Nc * k_cell))) return bail(rc);
-    if ((rc = dev_alloc(c, (void**)&c->dXs_net, 4 * (size_t)Nn * k_net))) return bail(rc);
+    if ((rc = dev_alloc(c, (void**)&c->dXs_cell, 4 * (size_t)Nc * k_near))) return bail(rc);
+    if (k_pins != k_near && (rc = dev_alloc(c, (void**)&c->dXs_cell_b, 4 * (size_t)Nc * k_pins))) return bail(rc);
+    if ((rc = dev_alloc(c, (void**)&c->dXs_net, 4 * (size_t)Nn * k_pinned))) return bail(rc);
     if (hipDeviceSynchronize() != hipSuccess) return bail(hip_fail(hipGetLastError(), "hipDeviceSynchronize"));
     *ctx = c;
+    return DR_OK;
+}
+
+extern "C" {
+
+int heteroconv_create(dr_heteroconv** ctx, const dr_csr* near, const dr_csr* pins, const dr_csr* pinned,
+                      int32_t D, int32_t k_cell, int32_t k_net) {
+    return create_impl(ctx, near, pins, pinned, D, k_cell, k_cell, k_net, k_net);
+}
+
+int heteroconv_create_per_relation(dr_heteroconv** ctx, const dr_csr* near, const dr_csr* pins, const dr_csr* pinned,
+                                   int32_t D, int32_t k_near, int32_t k_pins, int32_t k_pinned) {
+    return create_impl(ctx, near, pins, pinned, D, k_near, k_pins, k_pins, k_pinned);
+}
+
+int heteroconv_get_k(const dr_heteroconv* ctx, int32_t* k_near, int32_t* k_pins, int32_t* k_self, int32_t* k_pinned) {
+    DRC_REQUIRE(ctx && k_near && k_pins && k_self && k_pinned, "heteroconv_get_k: null argument");
+    *k_near = ctx->k_near; *k_pins = ctx->k_pins; *k_self = ctx->k_self; *k_pinned = ctx->k_pinned;
     return DR_OK;
 }
 
@@ -258,7 +282,7 @@ static int check_weights(const dr_heteroconv_weights* W, const char* fn) {
     return DR_OK;
 }
 
-static int check_saved(const dr_heteroconv_saved* S, const char* fn) {
+static int check_saved(const dr_heteroconv* c, const dr_heteroconv_saved* S, const char* fn) {
     DRC_REQUIRE(S != nullptr, "%s: null saved", fn);
     DRC_REQUIRE(S->vals_cell && S->idx_cell && S->vals_net && S->idx_net && S->H_near && S->H_pins &&
                     S->H_pinned && S->mask,
@@ -266,7 +290,32 @@ static int check_saved(const dr_heteroconv_saved* S, const char* fn) {
     DRC_REQUIRE(aligned(S->H_near, 16) && aligned(S->H_pins, 16) && aligned(S->H_pinned, 16) &&
                     aligned(S->mask, 4) && aligned(S->vals_cell, 4) && aligned(S->vals_net, 4),
                 "%s: misaligned buffer in saved", fn);
+    if (c->k_pins != c->k_near)
+        DRC_REQUIRE(S->vals_cell_pins && S->idx_cell_pins && aligned(S->vals_cell_pins, 4),
+                    "%s: k_pins != k_near needs saved.vals_cell_pins / idx_cell_pins", fn);
+    if (c->k_self != c->k_pinned)
+        DRC_REQUIRE(S->vals_net_self && S->idx_net_self && aligned(S->vals_net_self, 4),
+                    "%s: k_pins != k_pinned needs saved.vals_net_self / idx_net_self", fn);
     return DR_OK;
+}
+
+// The CBSR each use of an embedding reads: a width shared by both uses of a node type shares the buffers.
+struct CbsrSets {
+    const float *v_near, *v_pins, *v_self, *v_pinned;
+    const uint16_t *i_near, *i_pins, *i_self, *i_pinned;
+    bool cell_split, net_split;
+};
+static CbsrSets cbsr_sets(const dr_heteroconv* c, const dr_heteroconv_saved* S) {
+    CbsrSets q;
+    q.cell_split = c->k_pins != c->k_near;
+    q.net_split = c->k_self != c->k_pinned;
+    q.v_near = S->vals_cell; q.i_near = S->idx_cell;
+    q.v_pinned = S->vals_net; q.i_pinned = S->idx_net;
+    q.v_pins = q.cell_split ? S->vals_cell_pins : S->vals_cell;
+    q.i_pins = q.cell_split ? S->idx_cell_pins : S->idx_cell;
+    q.v_self = q.net_split ? S->vals_net_self : S->vals_net;
+    q.i_self = q.net_split ? S->idx_net_self : S->idx_net;
+    return q;
 }
 
 #define DRC_TRY(expr)            \
@@ -282,7 +331,7 @@ int heteroconv_fwd(dr_heteroconv* c, const float* X_cell, const float* X_net, co
     DRC_REQUIRE(aligned(X_cell, 16) && aligned(X_net, 16) && aligned(Y_cell, 16) && aligned(Y_net, 16),
                 "heteroconv_fwd: tensors must be 16-byte aligned");
     DRC_TRY(check_weights(W, "heteroconv_fwd"));
-    DRC_TRY(check_saved(S, "heteroconv_fwd"));
+    DRC_TRY(check_saved(c, S, "heteroconv_fwd"));
     hipStream_t user = as_stream(stream);
     const bool ov = relations_overlap(c);
     hipStream_t s_near = c->st[0], s_pins = ov ? c->st[1] : c->st[0], s_pinned = ov ? c->st[2] : c->st[0];
@@ -295,40 +344,52 @@ int heteroconv_fwd(dr_heteroconv* c, const float* X_cell, const float* X_net, co
     // Enqueue order (it is the execution order when all relations share one stream): every D-ReLU output is
     // gathered right after it is written, while it is still resident in the memory-side cache; the random
     // relations (pinned, pins) come before the grid-local one, and the streaming projections last.
+    const CbsrSets q = cbsr_sets(c, S);
 
-    // D-ReLU(net), then pinned: net -> cell
-    { ScopedTiming tm(c, kTopkNet, s_pinned); DRC_TRY(launch_topk(X_net, c->Nn, D, c->k_net, S->vals_net, S->idx_net, s_pinned)); }
+    // D-ReLU(net) at k_pinned, then pinned: net -> cell
+    { ScopedTiming tm(c, kTopkNet, s_pinned); DRC_TRY(launch_topk(X_net, c->Nn, D, c->k_pinned, S->vals_net, S->idx_net, s_pinned)); }
     DRC_HIP(hipEventRecord(c->ev_topk_net, s_pinned));
-    { ScopedTiming tm(c, kFwdPinned, s_pinned); DRC_TRY(launch_spmm_fwd(&c->A[2], S->vals_net, S->idx_net, D, c->k_net, S->H_pinned, s_pinned)); }
+    { ScopedTiming tm(c, kFwdPinned, s_pinned); DRC_TRY(launch_spmm_fwd(&c->A[2], q.v_pinned, q.i_pinned, D, c->k_pinned, S->H_pinned, s_pinned)); }
 
     // D-ReLU(cell), then pins: cell -> net and near: cell -> cell
-    { ScopedTiming tm(c, kTopkCell, s_near); DRC_TRY(launch_topk(X_cell, c->Nc, D, c->k_cell, S->vals_cell, S->idx_cell, s_near)); }
-    DRC_HIP(hipEventRecord(c->ev_topk_cell, s_near));
-    DRC_HIP(hipStreamWaitEvent(s_pins, c->ev_topk_cell, 0));
-    { ScopedTiming tm(c, kFwdPins, s_pins); DRC_TRY(launch_spmm_fwd(&c->A[1], S->vals_cell, S->idx_cell, D, c->k_cell, S->H_pins, s_pins)); }
-    { ScopedTiming tm(c, kFwdNear, s_near); DRC_TRY(launch_spmm_fwd(&c->A[0], S->vals_cell, S->idx_cell, D, c->k_cell, S->H_near, s_near)); }
+    if (q.cell_split) {
+        { ScopedTiming tm(c, kTopkCellPins, s_pins); DRC_TRY(launch_topk(X_cell, c->Nc, D, c->k_pins, S->vals_cell_pins, S->idx_cell_pins, s_pins)); }
+        { ScopedTiming tm(c, kFwdPins, s_pins); DRC_TRY(launch_spmm_fwd(&c->A[1], q.v_pins, q.i_pins, D, c->k_pins, S->H_pins, s_pins)); }
+        { ScopedTiming tm(c, kTopkCell, s_near); DRC_TRY(launch_topk(X_cell, c->Nc, D, c->k_near, S->vals_cell, S->idx_cell, s_near)); }
+    } else {
+        { ScopedTiming tm(c, kTopkCell, s_near); DRC_TRY(launch_topk(X_cell, c->Nc, D, c->k_near, S->vals_cell, S->idx_cell, s_near)); }
+        DRC_HIP(hipEventRecord(c->ev_topk_cell, s_near));
+        DRC_HIP(hipStreamWaitEvent(s_pins, c->ev_topk_cell, 0));
+        { ScopedTiming tm(c, kFwdPins, s_pins); DRC_TRY(launch_spmm_fwd(&c->A[1], q.v_pins, q.i_pins, D, c->k_pins, S->H_pins, s_pins)); }
+    }
+    { ScopedTiming tm(c, kFwdNear, s_near); DRC_TRY(launch_spmm_fwd(&c->A[0], q.v_near, q.i_near, D, c->k_near, S->H_near, s_near)); }
 
     // projections: near (self + neighbour), pins (self + neighbour), pinned merged into Y_cell by max
     {
         GemmOperand seg[2] = {};
-        seg[0].cbsr_vals = S->vals_cell; seg[0].cbsr_idx = S->idx_cell; seg[0].k = c->k_cell; seg[0].W = W->self_near;
+        seg[0].cbsr_vals = q.v_near; seg[0].cbsr_idx = q.i_near; seg[0].k = c->k_near; seg[0].W = W->self_near;
         seg[1].dense = S->H_near; seg[1].W = W->neigh_near;
-        { ScopedTiming tm(c, kProjNear, s_near); DRC_TRY(launch_gemm(seg, 2, c->Nc, D, kEpiStore, Y_cell, nullptr, nullptr, 0, nullptr, s_near)); }
+        { ScopedTiming tm(c, kProjNear, s_near); DRC_TRY(launch_gemm(seg, 2, c->Nc, D, kEpiStore, Y_cell, nullptr, SampleSet{}, SampleSet{}, s_near)); }
     }
     DRC_HIP(hipEventRecord(c->ev_near, s_near));
-    DRC_HIP(hipStreamWaitEvent(s_pins, c->ev_topk_net, 0));
+    if (q.net_split) {   // the self term of the pins module has its own width: selected on the pins stream itself
+        ScopedTiming tm(c, kTopkNetSelf, s_pins);
+        DRC_TRY(launch_topk(X_net, c->Nn, D, c->k_self, S->vals_net_self, S->idx_net_self, s_pins));
+    } else {
+        DRC_HIP(hipStreamWaitEvent(s_pins, c->ev_topk_net, 0));
+    }
     {
         GemmOperand seg[2] = {};
-        seg[0].cbsr_vals = S->vals_net; seg[0].cbsr_idx = S->idx_net; seg[0].k = c->k_net; seg[0].W = W->self_pins;
+        seg[0].cbsr_vals = q.v_self; seg[0].cbsr_idx = q.i_self; seg[0].k = c->k_self; seg[0].W = W->self_pins;
         seg[1].dense = S->H_pins; seg[1].W = W->neigh_pins;
-        { ScopedTiming tm(c, kProjPins, s_pins); DRC_TRY(launch_gemm(seg, 2, c->Nn, D, kEpiStore, Y_net, nullptr, nullptr, 0, nullptr, s_pins)); }
+        { ScopedTiming tm(c, kProjPins, s_pins); DRC_TRY(launch_gemm(seg, 2, c->Nn, D, kEpiStore, Y_net, nullptr, SampleSet{}, SampleSet{}, s_pins)); }
     }
     DRC_HIP(hipEventRecord(c->ev_pins, s_pins));
     DRC_HIP(hipStreamWaitEvent(s_pinned, c->ev_near, 0));
     {
         GemmOperand seg[1] = {};
         seg[0].dense = S->H_pinned; seg[0].W = W->pinned;
-        { ScopedTiming tm(c, kProjPinnedMerge, s_pinned); DRC_TRY(launch_gemm(seg, 1, c->Nc, D, kEpiMaxMerge, Y_cell, S->mask, nullptr, 0, nullptr, s_pinned)); }
+        { ScopedTiming tm(c, kProjPinnedMerge, s_pinned); DRC_TRY(launch_gemm(seg, 1, c->Nc, D, kEpiMaxMerge, Y_cell, S->mask, SampleSet{}, SampleSet{}, s_pinned)); }
     }
     DRC_HIP(hipEventRecord(c->ev_pinned, s_pinned));
 
@@ -345,7 +406,7 @@ int heteroconv_bwd(dr_heteroconv* c, const float* dY_cell, const float* dY_net, 
     DRC_REQUIRE(aligned(dY_cell, 16) && aligned(dY_net, 16) && aligned(dX_cell, 16) && aligned(dX_net, 16),
                 "heteroconv_bwd: misaligned tensor");
     DRC_TRY(check_weights(W, "heteroconv_bwd"));
-    DRC_TRY(check_saved(S, "heteroconv_bwd"));
+    DRC_TRY(check_saved(c, S, "heteroconv_bwd"));
     DRC_REQUIRE(dW && dW->self_near && dW->neigh_near && dW->self_pins && dW->neigh_pins && dW->pinned,
                 "heteroconv_bwd: null weight gradient");
     hipStream_t user = as_stream(stream);
@@ -357,64 +418,73 @@ int heteroconv_bwd(dr_heteroconv* c, const float* dY_cell, const float* dY_net, 
     DRC_HIP(hipEventRecord(c->ev_fork, user));
     for (int i = 0; i < (ov ? 3 : 1); ++i) DRC_HIP(hipStreamWaitEvent(c->st[i], c->ev_fork, 0));   // only the streams that get work
 
+    const CbsrSets q = cbsr_sets(c, S);
+
     // ---- near stream: dH_near, its transposed SpMM (first piece of dXs_cell), near weight gradients ----
     {
         GemmOperand seg[1] = {};
         seg[0].dense = dY_cell; seg[0].mask = S->mask; seg[0].mask_keep = 1;
         seg[0].W = W->neigh_near; seg[0].transpose_w = 1;
-        { ScopedTiming tm(c, kDhNear, s_near); DRC_TRY(launch_gemm(seg, 1, c->Nc, D, kEpiStore, c->dH[0], nullptr, nullptr, 0, nullptr, s_near)); }
+        { ScopedTiming tm(c, kDhNear, s_near); DRC_TRY(launch_gemm(seg, 1, c->Nc, D, kEpiStore, c->dH[0], nullptr, SampleSet{}, SampleSet{}, s_near)); }
     }
-    { ScopedTiming tm(c, kBwdNear, s_near); DRC_TRY(launch_spmm_bwd(&c->At[0], c->dH[0], S->idx_cell, D, c->k_cell, c->dXs_cell, 0, s_near)); }
+    { ScopedTiming tm(c, kBwdNear, s_near); DRC_TRY(launch_spmm_bwd(&c->At[0], c->dH[0], q.i_near, D, c->k_near, c->dXs_cell, 0, s_near)); }
     DRC_HIP(hipEventRecord(c->ev_gnear, s_near));
     {
         WgradOperand op = {};
         op.a_dense = S->H_near; op.b = dY_cell; op.b_mask = S->mask; op.b_mask_keep = 1;
         { ScopedTiming tm(c, kWgNeighNear, s_near); DRC_TRY(launch_wgrad(op, c->Nc, D, dW->neigh_near, c->wg_scratch[0], s_near)); }
         WgradOperand os = {};
-        os.a_cbsr_vals = S->vals_cell; os.a_cbsr_idx = S->idx_cell; os.k = c->k_cell;
+        os.a_cbsr_vals = q.v_near; os.a_cbsr_idx = q.i_near; os.k = c->k_near;
         os.b = dY_cell; os.b_mask = S->mask; os.b_mask_keep = 1;
         { ScopedTiming tm(c, kWgSelfNear, s_near); DRC_TRY(launch_wgrad(os, c->Nc, D, dW->self_near, c->wg_scratch[0], s_near)); }
     }
     DRC_HIP(hipEventRecord(c->ev_near, s_near));
 
-    // ---- pins stream: dH_pins, second piece of dXs_cell, near self term, dense dX_cell, pins weight gradients ----
+    // ---- pins stream: dH_pins, second piece of the cell gradient, near self term, dense dX_cell, pins weight gradients.
+    // With one width for the cells the pins piece is added into dXs_cell; with two it keeps its own buffer and
+    // the write-out kernel adds it at its own positions. ----
     {
         GemmOperand seg[1] = {};
         seg[0].dense = dY_net; seg[0].W = W->neigh_pins; seg[0].transpose_w = 1;
-        { ScopedTiming tm(c, kDhPins, s_pins); DRC_TRY(launch_gemm(seg, 1, c->Nn, D, kEpiStore, c->dH[1], nullptr, nullptr, 0, nullptr, s_pins)); }
+        { ScopedTiming tm(c, kDhPins, s_pins); DRC_TRY(launch_gemm(seg, 1, c->Nn, D, kEpiStore, c->dH[1], nullptr, SampleSet{}, SampleSet{}, s_pins)); }
     }
-    DRC_HIP(hipStreamWaitEvent(s_pins, c->ev_gnear, 0));
-    { ScopedTiming tm(c, kBwdPins, s_pins); DRC_TRY(launch_spmm_bwd(&c->At[1], c->dH[1], S->idx_cell, D, c->k_cell, c->dXs_cell, 1, s_pins)); }
+    if (!q.cell_split) DRC_HIP(hipStreamWaitEvent(s_pins, c->ev_gnear, 0));
+    { ScopedTiming tm(c, kBwdPins, s_pins); DRC_TRY(launch_spmm_bwd(&c->At[1], c->dH[1], q.i_pins, D, c->k_pins, q.cell_split ? c->dXs_cell_b : c->dXs_cell,
+                                                                    q.cell_split ? 0 : 1, s_pins)); }
+    if (q.cell_split) DRC_HIP(hipStreamWaitEvent(s_pins, c->ev_gnear, 0));
     {
         GemmOperand seg[1] = {};
         seg[0].dense = dY_cell; seg[0].mask = S->mask; seg[0].mask_keep = 1;
         seg[0].W = W->self_near; seg[0].transpose_w = 1;
-        { ScopedTiming tm(c, kSelfNearSample, s_pins); DRC_TRY(launch_gemm(seg, 1, c->Nc, D, kEpiSampleDense, dX_cell, nullptr, S->idx_cell, c->k_cell,
-                            c->dXs_cell, s_pins)); }
+        const SampleSet first{q.i_near, c->k_near, c->dXs_cell};
+        const SampleSet second = q.cell_split ? SampleSet{q.i_pins, c->k_pins, c->dXs_cell_b} : SampleSet{};
+        { ScopedTiming tm(c, kSelfNearSample, s_pins); DRC_TRY(launch_gemm(seg, 1, c->Nc, D, kEpiSampleDense, dX_cell, nullptr, first, second, s_pins)); }
     }
     {
         WgradOperand op = {};
         op.a_dense = S->H_pins; op.b = dY_net;
         { ScopedTiming tm(c, kWgNeighPins, s_pins); DRC_TRY(launch_wgrad(op, c->Nn, D, dW->neigh_pins, c->wg_scratch[1], s_pins)); }
         WgradOperand os = {};
-        os.a_cbsr_vals = S->vals_net; os.a_cbsr_idx = S->idx_net; os.k = c->k_net; os.b = dY_net;
+        os.a_cbsr_vals = q.v_self; os.a_cbsr_idx = q.i_self; os.k = c->k_self; os.b = dY_net;
         { ScopedTiming tm(c, kWgSelfPins, s_pins); DRC_TRY(launch_wgrad(os, c->Nn, D, dW->self_pins, c->wg_scratch[1], s_pins)); }
     }
     DRC_HIP(hipEventRecord(c->ev_pins, s_pins));
 
-    // ---- pinned stream: dH_pinned, dXs_net, pins self term, dense dX_net, pinned weight gradient ----
+    // ---- pinned stream: dH_pinned, dXs_net, pins self term, dense dX_net, pinned weight gradient.  With two widths
+    // for the nets the self term is sampled at its own selection and the pinned piece added at the other. ----
     {
         GemmOperand seg[1] = {};
         seg[0].dense = dY_cell; seg[0].mask = S->mask; seg[0].mask_keep = 0;
         seg[0].W = W->pinned; seg[0].transpose_w = 1;
-        { ScopedTiming tm(c, kDhPinned, s_pinned); DRC_TRY(launch_gemm(seg, 1, c->Nc, D, kEpiStore, c->dH[2], nullptr, nullptr, 0, nullptr, s_pinned)); }
+        { ScopedTiming tm(c, kDhPinned, s_pinned); DRC_TRY(launch_gemm(seg, 1, c->Nc, D, kEpiStore, c->dH[2], nullptr, SampleSet{}, SampleSet{}, s_pinned)); }
     }
-    { ScopedTiming tm(c, kBwdPinned, s_pinned); DRC_TRY(launch_spmm_bwd(&c->At[2], c->dH[2], S->idx_net, D, c->k_net, c->dXs_net, 0, s_pinned)); }
+    { ScopedTiming tm(c, kBwdPinned, s_pinned); DRC_TRY(launch_spmm_bwd(&c->At[2], c->dH[2], q.i_pinned, D, c->k_pinned, c->dXs_net, 0, s_pinned)); }
     {
         GemmOperand seg[1] = {};
         seg[0].dense = dY_net; seg[0].W = W->self_pins; seg[0].transpose_w = 1;
-        { ScopedTiming tm(c, kSelfPinsSample, s_pinned); DRC_TRY(launch_gemm(seg, 1, c->Nn, D, kEpiSampleDense, dX_net, nullptr, S->idx_net, c->k_net,
-                            c->dXs_net, s_pinned)); }
+        const SampleSet first = q.net_split ? SampleSet{q.i_self, c->k_self, nullptr} : SampleSet{q.i_pinned, c->k_pinned, c->dXs_net};
+        const SampleSet second = q.net_split ? SampleSet{q.i_pinned, c->k_pinned, c->dXs_net} : SampleSet{};
+        { ScopedTiming tm(c, kSelfPinsSample, s_pinned); DRC_TRY(launch_gemm(seg, 1, c->Nn, D, kEpiSampleDense, dX_net, nullptr, first, second, s_pinned)); }
     }
     {
         WgradOperand op = {};

@@ -149,7 +149,7 @@ struct GraphState {
 }  // namespace drc
 
 struct dr_hgnn {
-    int n_graphs, L, D, k;
+    int n_graphs, L, D;
     int64_t PL;                                // layer parameters: L*5*D*D
     int64_t n_cells_total;
     std::vector<drc::GraphState> g;
@@ -228,16 +228,13 @@ int hgnn_create(dr_hgnn** model, int32_t n_graphs, dr_heteroconv* const* graphs,
         for (int r = 0; r < q; ++r)
             DRC_REQUIRE(graphs[q] != graphs[r], "hgnn_create: graphs %d and %d share one context (its scratch is per step)", r, q);
     const HeteroDims d0 = heteroconv_dims(graphs[0]);
-    DRC_REQUIRE(d0.k_cell == d0.k_net, "hgnn_create: the model uses one k for both node types");
-    for (int q = 1; q < n_graphs; ++q) {
+    for (int q = 1; q < n_graphs; ++q) {   // the parameters are shared, so the width is; each sub-graph keeps its own K
         const HeteroDims d = heteroconv_dims(graphs[q]);
-        DRC_REQUIRE(d.D == d0.D && d.k_cell == d0.k_cell && d.k_net == d0.k_net,
-                    "hgnn_create: graph %d has D/k = %d/%d/%d, graph 0 has %d/%d/%d", q, d.D, d.k_cell, d.k_net, d0.D,
-                    d0.k_cell, d0.k_net);
+        DRC_REQUIRE(d.D == d0.D, "hgnn_create: graph %d has D = %d, graph 0 has %d", q, d.D, d0.D);
     }
     dr_hgnn* m = new (std::nothrow) dr_hgnn();
     if (!m) return fail(DR_ERR_HIP, "hgnn_create: out of host memory");
-    m->n_graphs = n_graphs; m->L = n_layers; m->D = d0.D; m->k = d0.k_cell;
+    m->n_graphs = n_graphs; m->L = n_layers; m->D = d0.D;
     m->PL = (int64_t)n_layers * 5 * d0.D * d0.D;
     m->n_cells_total = 0;
     m->gall = m->loss_part = m->dwh_part = nullptr;
@@ -251,7 +248,7 @@ int hgnn_create(dr_hgnn** model, int32_t n_graphs, dr_heteroconv* const* graphs,
         DRC_TRY(alloc_t(m, &m->gall, (size_t)n_graphs * m->PL));
         DRC_TRY(alloc_t(m, &m->loss_part, (size_t)n_graphs * kHeadBlocks));
         DRC_TRY(alloc_t(m, &m->dwh_part, (size_t)n_graphs * kHeadBlocks * m->D));
-        const int L = n_layers, D = m->D, k = m->k;
+        const int L = n_layers, D = m->D;
         for (int q = 0; q < n_graphs; ++q) {
             GraphState& gs = m->g[q];
             const HeteroDims d = heteroconv_dims(graphs[q]);
@@ -271,10 +268,18 @@ int hgnn_create(dr_hgnn** model, int32_t n_graphs, dr_heteroconv* const* graphs,
                 DRC_TRY(alloc_t(m, &gs.act_c[l], nc * D));
                 DRC_TRY(alloc_t(m, &gs.act_n[l], nn * D));
                 dr_heteroconv_saved& S = gs.saved[l];
-                DRC_TRY(alloc_t(m, &S.vals_cell, nc * k));
-                DRC_TRY(alloc_t(m, &S.idx_cell, nc * k));
-                DRC_TRY(alloc_t(m, &S.vals_net, nn * k));
-                DRC_TRY(alloc_t(m, &S.idx_net, nn * k));
+                DRC_TRY(alloc_t(m, &S.vals_cell, nc * d.k_near));
+                DRC_TRY(alloc_t(m, &S.idx_cell, nc * d.k_near));
+                DRC_TRY(alloc_t(m, &S.vals_net, nn * d.k_pinned));
+                DRC_TRY(alloc_t(m, &S.idx_net, nn * d.k_pinned));
+                if (d.k_pins != d.k_near) {
+                    DRC_TRY(alloc_t(m, &S.vals_cell_pins, nc * d.k_pins));
+                    DRC_TRY(alloc_t(m, &S.idx_cell_pins, nc * d.k_pins));
+                }
+                if (d.k_self != d.k_pinned) {
+                    DRC_TRY(alloc_t(m, &S.vals_net_self, nn * d.k_self));
+                    DRC_TRY(alloc_t(m, &S.idx_net_self, nn * d.k_self));
+                }
                 DRC_TRY(alloc_t(m, &S.H_near, nc * D));
                 DRC_TRY(alloc_t(m, &S.H_pins, nn * D));
                 DRC_TRY(alloc_t(m, &S.H_pinned, nc * D));

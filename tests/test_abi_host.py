@@ -27,7 +27,7 @@ def test_header_functions_are_exported_and_bound():
     for n in names:
         assert hasattr(lib, n), f"{n} declared in the header but not exported"
     assert sorted(P.EXPORTS) == names
-    assert P.dr_abi_version() == 1
+    assert P.dr_abi_version() == 2
 
 
 def _null_csr(n_rows=4, n_cols=4, nnz=0, rowptr=8, colidx=8, vals=8):
