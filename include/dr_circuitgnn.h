@@ -160,8 +160,8 @@ typedef struct dr_heteroconv_saved {          /* caller-owned device buffers wri
 /*
  * Build the per-graph context: validates the three relations (near Nc x Nc, pins Nn x Nc,
  * pinned Nc x Nn, all with vals), transposes them on the device, creates three streams and the events
- * that join them, and allocates the scratch the backward pass needs.  This is the only call of the
- * library that allocates device memory; heteroconv_destroy releases it.  The CSR arrays passed in stay
+ * that join them, and allocates the scratch the backward pass needs.  Device memory is allocated only by the
+ * *_create calls (released by the matching *_destroy) and, temporarily, by heteroconv_profile_k.  The CSR arrays passed in stay
  * owned by the caller and must outlive the context.  The call synchronises the device before returning.
  * Requires D in {32, 64, 96, 128}, 1 <= k_cell, k_net <= D.
  */
@@ -182,6 +182,23 @@ int heteroconv_create(dr_heteroconv** ctx, const dr_csr* near, const dr_csr* pin
 int heteroconv_create_per_relation(dr_heteroconv** ctx, const dr_csr* near, const dr_csr* pins, const dr_csr* pinned,
                                    int32_t D, int32_t k_near, int32_t k_pins, int32_t k_pinned);
 int heteroconv_get_k(const dr_heteroconv* ctx, int32_t* k_near, int32_t* k_pins, int32_t* k_self, int32_t* k_pinned);
+
+/*
+ * Preprocessing: optimal-K profiling of one sub-graph (paper Sections 4.1 and 4.3: the DR-SpMM kernels are timed on
+ * each sub-graph for K in {2, 4, ..., 64} and the fastest K of each edge type is used for training).  For every
+ * relation (0 near, 1 pins, 2 pinned) and every candidate K the source embeddings go through D-ReLU at that K,
+ * then dr_spmm_fwd and dr_spmm_bwd of the relation run `warmup` untimed and `reps` timed times (HIP events on
+ * one stream).  X_cell[Nc,D], X_net[Nn,D]: representative embeddings on the device; they also stand in for the
+ * upstream gradients of the backward (kernel time does not depend on the values).
+ * ms_fwd, ms_bwd: HOST arrays [3 * n_candidates], relation-major, mean milliseconds per launch.
+ * best_k: HOST array [3], for each relation the candidate with the least ms_fwd + ms_bwd (ties: the smaller K) --
+ * the argument triple of heteroconv_create_per_relation.  The context only lends its transposed adjacencies and
+ * D; the K it was created with plays no part.  Allocates and frees its own device scratch; synchronises the device.
+ * Requires 1 <= candidates[i] <= D, 1 <= n_candidates <= 64, warmup >= 0, 1 <= reps <= 1000.
+ */
+int heteroconv_profile_k(dr_heteroconv* ctx, const float* X_cell, const float* X_net,
+                         const int32_t* candidates, int32_t n_candidates, int32_t warmup, int32_t reps,
+                         float* ms_fwd, float* ms_bwd, int32_t* best_k);
 
 /*
  * Forward of one layer.  Inputs X_cell[Nc,D], X_net[Nn,D]; outputs Y_cell[Nc,D], Y_net[Nn,D] and every

@@ -23,6 +23,20 @@ from typing import Dict, List, Optional, Sequence
 import numpy as np
 
 from . import WEIGHT_NAMES, heteroconv_bwd, heteroconv_fwd
+from . import per_relation as _pr
+
+
+def _layer_fwd(rel, xc, xn, W, k):
+    """k: one int for both node types, or per_relation.Ks (one K per edge type, paper Section 4.3)."""
+    if isinstance(k, _pr.Ks):
+        return _pr.heteroconv_fwd(*rel, xc, xn, W, k)
+    return heteroconv_fwd(*rel, xc, xn, W, k, k)
+
+
+def _layer_bwd(rel, W, saved, dYc, dYn):
+    if "idx_cell_near" in saved:
+        return _pr.heteroconv_bwd(*rel, W, saved, dYc, dYn)
+    return heteroconv_bwd(*rel, W, saved, dYc, dYn)
 
 
 def n_params(L: int, D: int) -> int:
@@ -47,16 +61,15 @@ def pack(Ws: Sequence[Dict[str, np.ndarray]], w_head) -> np.ndarray:
 
 
 def forward_graph(rel, X_cell, X_net, Ws, w_head, k: int, layer_inputs: Optional[List] = None):
-    """One sub-graph.  rel = (near, pins, pinned) oracle relations.  layer_inputs[l] = (X_cell, X_net) overrides
+    """One sub-graph.  rel = (near, pins, pinned) oracle relations; k an int or per_relation.Ks.  layer_inputs[l] = (X_cell, X_net) overrides
     the input of layer l (l >= 1).  Returns dict(layers=[layer oracle outputs + inputs], pred)."""
-    near, pins, pinned = rel
     L = len(Ws)
     xc, xn = np.asarray(X_cell, dtype=np.float64), np.asarray(X_net, dtype=np.float64)
     layers = []
     for l in range(L):
         if layer_inputs is not None and l >= 1 and layer_inputs[l] is not None:
             xc, xn = (np.asarray(a, dtype=np.float64) for a in layer_inputs[l])
-        o = heteroconv_fwd(near, pins, pinned, xc, xn, Ws[l], k, k)
+        o = _layer_fwd(rel, xc, xn, Ws[l], k)
         o["X_cell"], o["X_net"] = xc, xn
         layers.append(o)
         if l < L - 1:
@@ -78,7 +91,6 @@ def backward_graph(rel, fwd, Ws, w_head, target, n_total: int, saved_override: O
     state (vals/idx/H/mask) of layer l; grad_override[l] = (dY_cell, dY_net) replaces the gradient arriving at the
     OUTPUT of layer l.  Returns dict(dW=[per layer {name: [D,D]}], dw_head, dpred, dY=[(dYc, dYn) per layer],
     dX=[(dXc, dXn) per layer])."""
-    near, pins, pinned = rel
     L = len(Ws)
     w_head = np.asarray(w_head, dtype=np.float64)
     dpred = 2.0 * (fwd["pred"] - np.asarray(target, dtype=np.float64)) / n_total
@@ -92,7 +104,7 @@ def backward_graph(rel, fwd, Ws, w_head, target, n_total: int, saved_override: O
             dYc, dYn = (np.asarray(a, dtype=np.float64) for a in grad_override[l])
         lay = fwd["layers"][l]
         saved = lay if saved_override is None or saved_override[l] is None else saved_override[l]
-        ob = heteroconv_bwd(near, pins, pinned, Ws[l], saved, dYc, dYn)
+        ob = _layer_bwd(rel, Ws[l], saved, dYc, dYn)
         dW[l] = ob["dW"]
         dYs[l] = (dYc, dYn)
         dXs[l] = (ob["dX_cell"], ob["dX_net"])
@@ -116,9 +128,11 @@ def adam_step(theta, grad, m, v, lr: float, beta1: float, beta2: float, eps: flo
 
 def train_step(rels, X_cells, X_nets, targets, theta, m, v, L: int, D: int, k: int, lr=2e-4, beta1=0.9, beta2=0.999,
                eps=1e-8, weight_decay=1e-5, t=1):
-    """Whole step on a batch of sub-graphs.  Returns dict(loss, grad, theta, m, v, fwd=[...], bwd=[...])."""
+    """Whole step on a batch of sub-graphs; k is one K for all or a list with one entry (int or per_relation.Ks) per
+    sub-graph.  Returns dict(loss, grad, theta, m, v, fwd=[...], bwd=[...])."""
     Ws, w_head = unpack(theta, L, D)
-    fwds = [forward_graph(r, xc, xn, Ws, w_head, k) for r, xc, xn in zip(rels, X_cells, X_nets)]
+    ks = list(k) if isinstance(k, (list, tuple)) and not isinstance(k, _pr.Ks) else [k] * len(rels)
+    fwds = [forward_graph(r, xc, xn, Ws, w_head, kq) for r, xc, xn, kq in zip(rels, X_cells, X_nets, ks)]
     n_total = sum(len(f["pred"]) for f in fwds)
     loss = loss_of([f["pred"] for f in fwds], targets)
     bwds = [backward_graph(r, f, Ws, w_head, tg, n_total) for r, f, tg in zip(rels, fwds, targets)]

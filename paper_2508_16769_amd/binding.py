@@ -32,7 +32,7 @@ EXPORTS = (
     "dr_last_error", "dr_abi_version", "dr_topk", "dr_spmm_fwd", "dr_spmm_bwd",
     "dr_csr_transpose_workspace_bytes", "dr_csr_transpose",
     "dr_csr_normalize_workspace_bytes", "dr_csr_normalize",
-    "heteroconv_create", "heteroconv_create_per_relation", "heteroconv_get_k", "heteroconv_fwd", "heteroconv_bwd", "heteroconv_get_transpose", "heteroconv_destroy",
+    "heteroconv_create", "heteroconv_create_per_relation", "heteroconv_get_k", "heteroconv_profile_k", "heteroconv_fwd", "heteroconv_bwd", "heteroconv_get_transpose", "heteroconv_destroy",
     "heteroconv_profile", "heteroconv_num_kernels", "heteroconv_kernel_name", "heteroconv_kernel_times",
     "heteroconv_set_overlap",
     "hgnn_num_params", "hgnn_create", "hgnn_train_step", "hgnn_get_layer_buffers", "hgnn_destroy",
@@ -210,6 +210,17 @@ class HeteroConv:
         ks = [ctypes.c_int32(0) for _ in range(4)]
         _check(load().heteroconv_get_k(self._ctx, *[ctypes.byref(v) for v in ks]))
         return tuple(int(v.value) for v in ks)
+
+    def heteroconv_profile_k(self, X_cell, X_net, candidates: Sequence[int], warmup: int = 2, reps: int = 5):
+        """Returns (ms_fwd[3][n], ms_bwd[3][n], best_k) as nested lists / a tuple (synchronises the device)."""
+        n = len(candidates)
+        cand = (ctypes.c_int32 * n)(*[int(k) for k in candidates])
+        f, b = (ctypes.c_float * (3 * n))(), (ctypes.c_float * (3 * n))()
+        best = (ctypes.c_int32 * 3)()
+        _check(load().heteroconv_profile_k(self._ctx, _ptr(X_cell), _ptr(X_net), cand, ctypes.c_int32(n),
+                                           ctypes.c_int32(warmup), ctypes.c_int32(reps), f, b, best))
+        tab = lambda a: [[float(a[r * n + i]) for i in range(n)] for r in range(3)]
+        return tab(f), tab(b), tuple(int(v) for v in best)
 
     def alloc_saved(self, device="cuda") -> Dict[str, torch.Tensor]:
         Nc, Nn, D = self.Nc, self.Nn, self.D

@@ -31,6 +31,12 @@ int hip_fail(hipError_t e, const char* what);
         if (!(cond)) return ::drc::fail(DR_ERR_INVALID_ARG, __VA_ARGS__); \
     } while (0)
 
+#define DRC_TRY(expr)                  \
+    do {                               \
+        int drc_rc__ = (expr);         \
+        if (drc_rc__) return drc_rc__; \
+    } while (0)
+
 int check_csr(const dr_csr* A, const char* name, bool need_vals);
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 inline hipStream_t as_stream(void* s) { return static_cast<hipStream_t>(s); }

@@ -253,6 +253,74 @@ int heteroconv_profile(dr_heteroconv* ctx, int enable) {
     return DR_OK;
 }
 
+int heteroconv_profile_k(dr_heteroconv* c, const float* X_cell, const float* X_net, const int32_t* candidates,
+                         int32_t n_candidates, int32_t warmup, int32_t reps, float* ms_fwd, float* ms_bwd,
+                         int32_t* best_k) {
+    DRC_REQUIRE(c != nullptr, "heteroconv_profile_k: null context");
+    DRC_REQUIRE(X_cell && X_net && candidates && ms_fwd && ms_bwd && best_k, "heteroconv_profile_k: null argument");
+    DRC_REQUIRE(aligned(X_cell, 16) && aligned(X_net, 16), "heteroconv_profile_k: embeddings must be 16-byte aligned");
+    DRC_REQUIRE(n_candidates >= 1 && n_candidates <= 64, "heteroconv_profile_k: n_candidates = %d out of range [1, 64]", n_candidates);
+    DRC_REQUIRE(warmup >= 0 && reps >= 1 && reps <= 1000, "heteroconv_profile_k: warmup = %d, reps = %d", warmup, reps);
+    int kmax = 0;
+    for (int i = 0; i < n_candidates; ++i) {
+        DRC_REQUIRE(candidates[i] >= 1 && candidates[i] <= c->D, "heteroconv_profile_k: candidate %d is %d, D = %d", i,
+                    candidates[i], c->D);
+        if (candidates[i] > kmax) kmax = candidates[i];
+    }
+    const int D = c->D;
+    const size_t rows = (size_t)(c->Nc > c->Nn ? c->Nc : c->Nn);
+    float *vals = nullptr, *H = nullptr, *G = nullptr;
+    uint16_t* idx = nullptr;
+    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+    hipStream_t s = c->st[0];
+    auto body = [&]() -> int {
+        DRC_HIP(hipDeviceSynchronize());
+        DRC_HIP(hipMalloc((void**)&vals, 4 * rows * kmax + 256));
+        DRC_HIP(hipMalloc((void**)&idx, 2 * rows * kmax + 256));
+        DRC_HIP(hipMalloc((void**)&G, 4 * rows * kmax + 256));
+        DRC_HIP(hipMalloc((void**)&H, 4 * rows * D + 256));
+        for (hipEvent_t& e : ev) DRC_HIP(hipEventCreate(&e));
+        for (int r = 0; r < 3; ++r) {
+            // sources of near and pins are cells, of pinned nets; the upstream gradient of the backward is any
+            // dense [M, D] array (the kernels' time does not depend on values): the destination type's embeddings
+            const float* Xsrc = (r == 2) ? X_net : X_cell;
+            const float* dH = (r == 1) ? X_net : X_cell;
+            const int64_t n_src = c->A[r].n_cols;
+            int best = -1;
+            float best_ms = 0.f;
+            for (int i = 0; i < n_candidates; ++i) {
+                const int k = candidates[i];
+                DRC_TRY(launch_topk(Xsrc, n_src, D, k, vals, idx, s));
+                for (int w = 0; w < warmup; ++w) {
+                    DRC_TRY(launch_spmm_fwd(&c->A[r], vals, idx, D, k, H, s));
+                    DRC_TRY(launch_spmm_bwd(&c->At[r], dH, idx, D, k, G, 0, s));
+                }
+                DRC_HIP(hipEventRecord(ev[0], s));
+                for (int q = 0; q < reps; ++q) DRC_TRY(launch_spmm_fwd(&c->A[r], vals, idx, D, k, H, s));
+                DRC_HIP(hipEventRecord(ev[1], s));
+                for (int q = 0; q < reps; ++q) DRC_TRY(launch_spmm_bwd(&c->At[r], dH, idx, D, k, G, 0, s));
+                DRC_HIP(hipEventRecord(ev[2], s));
+                DRC_HIP(hipEventSynchronize(ev[2]));
+                float f = 0.f, b = 0.f;
+                DRC_HIP(hipEventElapsedTime(&f, ev[0], ev[1]));
+                DRC_HIP(hipEventElapsedTime(&b, ev[1], ev[2]));
+                ms_fwd[r * n_candidates + i] = f / reps;
+                ms_bwd[r * n_candidates + i] = b / reps;
+                const float tot = (f + b) / reps;
+                if (best < 0 || tot < best_ms || (tot == best_ms && k < candidates[best])) { best = i; best_ms = tot; }
+            }
+            best_k[r] = candidates[best];
+        }
+        return DR_OK;
+    };
+    const int rc = body();
+    (void)hipDeviceSynchronize();
+    for (hipEvent_t e : ev)
+        if (e) (void)hipEventDestroy(e);
+    (void)hipFree(vals); (void)hipFree(idx); (void)hipFree(G); (void)hipFree(H);
+    return rc;
+}
+
 int heteroconv_num_kernels(void) { return kNumKernels; }
 
 const char* heteroconv_kernel_name(int id) { return (id >= 0 && id < kNumKernels) ? kKernelNames[id] : ""; }
@@ -317,12 +385,6 @@ static CbsrSets cbsr_sets(const dr_heteroconv* c, const dr_heteroconv_saved* S) 
     q.i_self = q.net_split ? S->idx_net_self : S->idx_net;
     return q;
 }
-
-#define DRC_TRY(expr)            \
-    do {                         \
-        int drc_rc__ = (expr);   \
-        if (drc_rc__) return drc_rc__; \
-    } while (0)
 
 int heteroconv_fwd(dr_heteroconv* c, const float* X_cell, const float* X_net, const dr_heteroconv_weights* W,
                    float* Y_cell, float* Y_net, const dr_heteroconv_saved* S, void* stream) {

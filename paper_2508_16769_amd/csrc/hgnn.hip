@@ -182,12 +182,6 @@ void model_release(dr_hgnn* m) {
     delete m;
 }
 
-#define DRC_TRY(expr)            \
-    do {                         \
-        int drc_rc__ = (expr);   \
-        if (drc_rc__) return drc_rc__; \
-    } while (0)
-
 template <typename T>
 int alloc_t(dr_hgnn* m, T** p, size_t count) { return model_alloc(m, reinterpret_cast<void**>(p), count * sizeof(T)); }
 

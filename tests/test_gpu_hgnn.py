@@ -162,6 +162,100 @@ def test_train_step_parity(case):
         c.heteroconv_destroy()
 
 
+def _check_layer_ks(model, rels, Ws, q, l, L, D, ks, X0=None):
+    """Teacher-forced comparison of one layer of a sub-graph that has one K per edge type (dense dX)."""
+    from oracle import per_relation as opr
+    b = {kk: (vv.cpu().numpy() if torch.is_tensor(vv) else {n: t.cpu().numpy() for n, t in vv.items()})
+         for kk, vv in model.hgnn_get_layer_buffers(q, l).items()}
+    if l == 0 and X0 is not None:
+        assert np.array_equal(b["X_cell"], X0[0]) and np.array_equal(b["X_net"], X0[1])
+    of = opr.heteroconv_fwd(*rels[q], b["X_cell"], b["X_net"], Ws[l], ks)
+    mine = {"cell_near": "cell", "net_pinned": "net",
+            "cell_pins": "cell_pins" if ks.pins != ks.near else "cell", "net_self": "net_self" if ks.self_ != ks.pinned else "net"}
+    saved = {n: b[n] for n in ("H_near", "H_pins", "H_pinned", "mask")}
+    for theirs, m in mine.items():
+        idx = host_idx(torch.from_numpy(b["idx_" + m]))
+        assert np.array_equal(idx, of["idx_" + theirs]), (q, l, theirs)
+        assert np.array_equal(b["vals_" + m].astype(np.float64), of["vals_" + theirs]), (q, l, theirs)
+        saved["idx_" + theirs], saved["vals_" + theirs] = idx, b["vals_" + m]
+    want_c, want_n = of["Y_cell"], of["Y_net"]
+    if l < L - 1:
+        want_c, want_n = np.maximum(want_c, 0), np.maximum(want_n, 0)
+    assert_row_bound(b["Y_cell"], want_c, of["l1_cell"].sum(axis=1), f"g{q} l{l} Y_cell")
+    assert_row_bound(b["Y_net"], want_n, of["l1_net"].sum(axis=1), f"g{q} l{l} Y_net")
+    decided = np.abs(of["Z_near"] - of["Z_pinned"]) > 2e-5 * of["l1_cell"]
+    assert np.array_equal(b["mask"][decided], of["mask"][decided])
+    ob = opr.heteroconv_bwd(*rels[q], Ws[l], saved, b["dY_cell"], b["dY_net"])
+    want_gc, want_gn = ob["dX_cell"].copy(), ob["dX_net"].copy()
+    if l >= 1:
+        want_gc *= b["X_cell"] > 0
+        want_gn *= b["X_net"] > 0
+    assert_row_bound(b["dX_cell"], want_gc, ob["l1_dX_cell"].sum(axis=1), f"g{q} l{l} dX_cell")
+    assert_row_bound(b["dX_net"], want_gn, ob["l1_dX_net"].sum(axis=1), f"g{q} l{l} dX_net")
+    assert np.all(b["dX_cell"][ob["l1_dX_cell"] == 0] == 0) and np.all(b["dX_net"][ob["l1_dX_net"] == 0] == 0)
+    Xs_c = oracle.densify(saved["vals_cell_near"], saved["idx_cell_near"], D)
+    Xs_n = oracle.densify(saved["vals_net_self"], saved["idx_net_self"], D)
+    bounds = _wgrad_bounds({n: np.asarray(saved[n], np.float64) for n in ("H_near", "H_pins", "H_pinned")}, Xs_c, Xs_n,
+                           b["dY_cell"].astype(np.float64), b["dY_net"].astype(np.float64), saved["mask"])
+    for n in P.WEIGHT_NAMES:
+        err = np.abs(b["dW"][n].astype(np.float64) - ob["dW"][n])
+        assert np.all(err <= 1e-5 * bounds[n] + 1e-30), (q, l, n, err.max())
+    return b
+
+
+def test_train_step_with_own_k_per_subgraph():
+    """Three sub-graphs that share the parameters and keep their own K: one K per edge type (all different), one K
+    per edge type with the cells sharing a selection, and one K per node type.  Every layer is checked teacher-forced;
+    the loss and the batch gradient are checked against the sums of what the layers produced and the free oracle."""
+    from oracle.per_relation import Ks
+    D, L = 128, 2
+    graphs, rels, ctxs, keep, Xc, Xn, tg, theta0 = _setup(3, 2000, 1400, (64, 42), D, 8, L, seed0=60)
+    for c in ctxs:
+        c.heteroconv_destroy()
+    kset = [Ks.per_relation(8, 32, 16), Ks.per_relation(16, 16, 4), 24]
+    ctxs = [P.HeteroConv(*keep[0], D, per_relation=(8, 32, 16)), P.HeteroConv(*keep[1], D, per_relation=(16, 16, 4)),
+            P.HeteroConv(*keep[2], D, 24, 24)]
+    say("hgnn: three sub-graphs with their own K")
+    model = P.Hgnn(ctxs, L)
+    n_par = P.hgnn_num_params(L, D)
+    theta = dev(theta0)
+    m = torch.zeros(n_par, dtype=torch.float32, device="cuda")
+    v = torch.zeros(n_par, dtype=torch.float32, device="cuda")
+    grad = torch.full((n_par,), float("nan"), dtype=torch.float32, device="cuda")
+    loss = torch.full((1,), float("nan"), dtype=torch.float32, device="cuda")
+    dXc, dXn, dtg = [dev(a) for a in Xc], [dev(a) for a in Xn], [dev(a) for a in tg]   # kept alive: layer 0 reads them back
+    model.hgnn_train_step(dXc, dXn, dtg, theta, m, v, LR, B1, B2, EPS, WD, 1, grad, loss)
+    torch.cuda.synchronize()
+    Ws, w_head = ohgnn.unpack(theta0.astype(np.float64), L, D)
+    n_total = sum(g.Nc for g in graphs)
+    sq_sum, g_layers, g_head = 0.0, np.zeros(n_par - D), np.zeros(D)
+    for q in range(3):
+        for l in range(L):
+            if isinstance(kset[q], Ks):
+                b = _check_layer_ks(model, rels, Ws, q, l, L, D, kset[q], X0=(Xc[q], Xn[q]))
+            else:
+                b = _check_layer(model, rels, Ws, q, l, L, D, kset[q], X0=(Xc[q], Xn[q]))
+            for i, n in enumerate(P.WEIGHT_NAMES):
+                lo = (l * 5 + i) * D * D
+                g_layers[lo:lo + D * D] += b["dW"][n].astype(np.float64).ravel()
+        r = b["pred"].astype(np.float64) - tg[q]
+        sq_sum += float(np.sum(r * r))
+        g_head += b["Y_cell"].astype(np.float64).T @ b["dpred"].astype(np.float64)
+    loss_gpu = float(loss.cpu()[0])
+    assert abs(loss_gpu - sq_sum / n_total) <= 1e-5 * (sq_sum / n_total)
+    gg = grad.cpu().numpy().astype(np.float64)
+    assert np.allclose(gg[:n_par - D], g_layers, rtol=1e-5, atol=1e-9)
+    assert np.allclose(gg[n_par - D:], g_head, rtol=1e-4, atol=1e-7)
+    free = ohgnn.train_step(rels, Xc, Xn, tg, theta0.astype(np.float64), np.zeros(n_par), np.zeros(n_par), L, D, kset,
+                            LR, B1, B2, EPS, WD, 1)
+    assert abs(loss_gpu - free["loss"]) <= 1e-3 * free["loss"], (loss_gpu, free["loss"])
+    cos = float(gg @ free["grad"] / (np.linalg.norm(gg) * np.linalg.norm(free["grad"])))
+    assert cos > 0.999, cos
+    model.hgnn_destroy()
+    for c in ctxs:
+        c.heteroconv_destroy()
+
+
 def test_full_size_step_of_eight_subgraphs():
     """The batch of the training-step configuration: 8 independent sub-graphs of 20 000 cells / 14 000 nets,
     3 layers, D = 128, k = 32.  Two (sub-graph, layer) pairs are recomputed by the oracle; the loss, the gradient

@@ -175,3 +175,45 @@ def test_per_relation_argument_errors():
         layer.heteroconv_fwd(X, Xn, Wd, torch.empty_like(X), torch.empty_like(Xn), saved)
     assert e.value.code == P.DR_ERR_INVALID_ARG and "vals_cell_pins" in str(e.value)
     layer.heteroconv_destroy()
+
+
+def test_profile_k_times_every_candidate_and_picks_the_fastest():
+    """Optimal-K profiling of a training-size sub-graph: a positive time for every (relation, K), best_k is the
+    arg-min of the returned table, and a context built from it runs."""
+    g = make_graph("subgraph", seed=3)
+    D = 128
+    T = make_tensors(g.Nc, g.Nn, D, seed=3)
+    rels = [P.device_relation(g.near, P.DR_NORM_MEAN), P.device_relation(g.pins, P.DR_NORM_MEAN),
+            P.device_relation(g.pinned, P.DR_NORM_SYM)]
+    say(f"profile_k: sub-graph of {g.Nc} cells / {g.Nn} nets")
+    ctx = P.HeteroConv(*rels, D, 1, 1)
+    cand = (2, 4, 8, 16, 32, 64)
+    Xc, Xn = dev(T.X_cell), dev(T.X_net)
+    ms_f, ms_b, best = ctx.heteroconv_profile_k(Xc, Xn, cand, warmup=2, reps=5)
+    for r, name in enumerate(("near", "pins", "pinned")):
+        say(f"  {name:7s} fwd ms " + " ".join(f"{v:.4f}" for v in ms_f[r]) + " | bwd ms " + " ".join(f"{v:.4f}" for v in ms_b[r]))
+        tot = np.array(ms_f[r]) + np.array(ms_b[r])
+        assert np.all(np.array(ms_f[r]) > 0) and np.all(np.array(ms_b[r]) > 0)
+        assert best[r] == cand[int(np.argmin(tot))]
+        # more kept values never make the kernels markedly faster
+        assert tot[-1] > 0.8 * tot[0]
+    say(f"  best k_near/k_pins/k_pinned = {best}")
+    # the embeddings were only read
+    assert np.array_equal(Xc.cpu().numpy(), T.X_cell) and np.array_equal(Xn.cpu().numpy(), T.X_net)
+    tuned = P.HeteroConv(*rels, D, per_relation=best)
+    saved = tuned.alloc_saved()
+    Wd = {n: dev(T.W[n]) for n in P.WEIGHT_NAMES}
+    Yc = torch.empty((g.Nc, D), dtype=torch.float32, device="cuda")
+    Yn = torch.empty((g.Nn, D), dtype=torch.float32, device="cuda")
+    tuned.heteroconv_fwd(Xc, Xn, Wd, Yc, Yn, saved)
+    torch.cuda.synchronize()
+    assert torch.isfinite(Yc).all() and torch.isfinite(Yn).all()
+    # argument errors come back before anything is launched
+    for bad in ((), (0, 4), (4, 129)):
+        with pytest.raises(P.DrError) as e:
+            ctx.heteroconv_profile_k(Xc, Xn, bad)
+        assert e.value.code == P.DR_ERR_INVALID_ARG
+    with pytest.raises(P.DrError):
+        ctx.heteroconv_profile_k(Xc, Xn, cand, reps=0)
+    tuned.heteroconv_destroy()
+    ctx.heteroconv_destroy()

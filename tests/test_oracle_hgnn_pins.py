@@ -115,3 +115,28 @@ def test_adam_matches_torch():
         opt.step()
         th, m, v = hgnn.adam_step(th, g, m, v, lr, b1, b2, eps, wd, t)
         assert np.allclose(th, p.detach().numpy(), rtol=1e-12, atol=1e-15), t
+
+
+def test_gradient_with_one_k_per_edge_type_and_per_subgraph():
+    """Sub-graphs that keep their own (k_near, k_pins, k_pinned): the batch gradient against central differences."""
+    from oracle.per_relation import Ks
+    D, L = 8, 2
+    ks = [Ks.per_relation(2, 5, 3), 4]
+    rels, Xc, Xn, tg = _batch(D)
+    rng = np.random.default_rng(21)
+    theta = rng.uniform(-0.6, 0.6, hgnn.n_params(L, D))
+
+    def loss(th):
+        Ws, wh = hgnn.unpack(th, L, D)
+        preds = [hgnn.forward_graph(r, a, b, Ws, wh, k)["pred"] for r, a, b, k in zip(rels, Xc, Xn, ks)]
+        return hgnn.loss_of(preds, tg)
+
+    out = hgnn.train_step(rels, Xc, Xn, tg, theta, np.zeros_like(theta), np.zeros_like(theta), L, D, ks)
+    assert abs(out["loss"] - loss(theta)) < 1e-14
+    h = 1e-6
+    for trial in range(5):
+        d = rng.standard_normal(theta.shape)
+        d /= np.linalg.norm(d)
+        fd = (loss(theta + h * d) - loss(theta - h * d)) / (2 * h)
+        an = float(out["grad"] @ d)
+        assert abs(fd - an) <= 2e-6 * max(1.0, abs(an)), (trial, fd, an)
