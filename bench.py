@@ -29,8 +29,11 @@ MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix, published
 # algorithmic (compulsory) bytes and flops per kernel: every array the kernel must read or write, once
 # ----------------------------------------------------------------------------------------------------
 
-def kernel_models(Nc, Nn, E, D, kc, kn):
-    """{kernel name: (bytes, flops)} for one step.  E = dict(near=, pins=, pinned=)."""
+def kernel_models(Nc, Nn, E, D, ks):
+    """{kernel name: (bytes, flops)} for one step.  E = dict(near=, pins=, pinned=); ks = (k_near, k_pins, k_self,
+    k_pinned): D-ReLU widths of the cells for near / for pins and of the nets for the pins self term / for pinned
+    (k_cell, k_cell, k_net, k_net with one K per node type)."""
+    k_near, k_pins, k_self, k_pinned = ks
     W = 4 * D * D
 
     def topk(n, k):
@@ -43,39 +46,47 @@ def kernel_models(Nc, Nn, E, D, kc, kn):
         return 4 * (Nsrc + 1) + 8 * e + 2 * Nsrc * k + min(4 * e * k, 4 * M * D) + 4 * Nsrc * k, 2 * e * k
 
     m = {}
-    m["dr_topk.cell"] = topk(Nc, kc)
-    m["dr_topk.net"] = topk(Nn, kn)
-    m["dr_spmm_fwd.near"] = fwd(Nc, Nc, E["near"], kc)
-    m["dr_spmm_fwd.pins"] = fwd(Nn, Nc, E["pins"], kc)
-    m["dr_spmm_fwd.pinned"] = fwd(Nc, Nn, E["pinned"], kn)
-    m["proj.near"] = (6 * Nc * kc + 4 * Nc * D + 2 * W + 4 * Nc * D, 2 * Nc * D * (D + D))
-    m["proj.pins"] = (6 * Nn * kn + 4 * Nn * D + 2 * W + 4 * Nn * D, 2 * Nn * D * (D + D))
+    m["dr_topk.cell"] = topk(Nc, k_near)
+    m["dr_topk.net"] = topk(Nn, k_pinned)
+    if k_pins != k_near:
+        m["dr_topk.cell.pins"] = topk(Nc, k_pins)
+    if k_self != k_pinned:
+        m["dr_topk.net.self"] = topk(Nn, k_self)
+    m["dr_spmm_fwd.near"] = fwd(Nc, Nc, E["near"], k_near)
+    m["dr_spmm_fwd.pins"] = fwd(Nn, Nc, E["pins"], k_pins)
+    m["dr_spmm_fwd.pinned"] = fwd(Nc, Nn, E["pinned"], k_pinned)
+    m["proj.near"] = (6 * Nc * k_near + 4 * Nc * D + 2 * W + 4 * Nc * D, 2 * Nc * D * (D + D))
+    m["proj.pins"] = (6 * Nn * k_self + 4 * Nn * D + 2 * W + 4 * Nn * D, 2 * Nn * D * (D + D))
     m["proj.pinned+merge"] = (4 * Nc * D + W + 8 * Nc * D + Nc * D, 2 * Nc * D * D)
     m["dproj.near"] = (5 * Nc * D + W + 4 * Nc * D, 2 * Nc * D * D)
     m["dproj.pins"] = (4 * Nn * D + W + 4 * Nn * D, 2 * Nn * D * D)
     m["dproj.pinned"] = (5 * Nc * D + W + 4 * Nc * D, 2 * Nc * D * D)
-    m["dr_spmm_bwd.near"] = bwd(Nc, Nc, E["near"], kc)
-    m["dr_spmm_bwd.pins"] = bwd(Nc, Nn, E["pins"], kc)
-    m["dr_spmm_bwd.pinned"] = bwd(Nn, Nc, E["pinned"], kn)
-    # self-term gradient sampled at the saved indices, added to the compact SpMM gradient, written as dense dX
-    m["dself.near+dX"] = (5 * Nc * D + W + 6 * Nc * kc + 4 * Nc * D, 2 * Nc * D * D)
-    m["dself.pins+dX"] = (4 * Nn * D + W + 6 * Nn * kn + 4 * Nn * D, 2 * Nn * D * D)
+    m["dr_spmm_bwd.near"] = bwd(Nc, Nc, E["near"], k_near)
+    m["dr_spmm_bwd.pins"] = bwd(Nc, Nn, E["pins"], k_pins)
+    m["dr_spmm_bwd.pinned"] = bwd(Nn, Nc, E["pinned"], k_pinned)
+    # self-term gradient sampled at the saved indices, added to the compact SpMM gradient(s), written as dense dX
+    cell_sets = 6 * Nc * k_near + (6 * Nc * k_pins if k_pins != k_near else 0)
+    net_sets = 6 * Nn * k_pinned + (2 * Nn * k_self if k_self != k_pinned else 0)
+    m["dself.near+dX"] = (5 * Nc * D + W + cell_sets + 4 * Nc * D, 2 * Nc * D * D)
+    m["dself.pins+dX"] = (4 * Nn * D + W + net_sets + 4 * Nn * D, 2 * Nn * D * D)
     m["wgrad.neigh_near"] = (4 * Nc * D + 5 * Nc * D + W, 2 * Nc * D * D)
-    m["wgrad.self_near"] = (6 * Nc * kc + 5 * Nc * D + W, 2 * Nc * D * D)
+    m["wgrad.self_near"] = (6 * Nc * k_near + 5 * Nc * D + W, 2 * Nc * D * D)
     m["wgrad.neigh_pins"] = (8 * Nn * D + W, 2 * Nn * D * D)
-    m["wgrad.self_pins"] = (6 * Nn * kn + 4 * Nn * D + W, 2 * Nn * D * D)
+    m["wgrad.self_pins"] = (6 * Nn * k_self + 4 * Nn * D + W, 2 * Nn * D * D)
     m["wgrad.pinned"] = (4 * Nc * D + 5 * Nc * D + W, 2 * Nc * D * D)
     return m
 
 
-DR_KERNELS = ("dr_topk.cell", "dr_topk.net", "dr_spmm_fwd.near", "dr_spmm_fwd.pins", "dr_spmm_fwd.pinned",
+DR_KERNELS = ("dr_topk.cell", "dr_topk.net", "dr_topk.cell.pins", "dr_topk.net.self",
+              "dr_spmm_fwd.near", "dr_spmm_fwd.pins", "dr_spmm_fwd.pinned",
               "dr_spmm_bwd.near", "dr_spmm_bwd.pins", "dr_spmm_bwd.pinned")
 
 
-def cpu_baseline(name: str, D: int, k: int, scale: int):
+def cpu_baseline(name: str, D: int, ks, scale: int):
     """The oracle's layer forward + backward on a 1/scale-size graph drawn from the same laws."""
     import numpy as np  # noqa: F401
     import oracle
+    from oracle import per_relation as opr
     from circuit_synth import make_graph, make_tensors, workload
     w = workload(name)
     gw, gh = w["grid"]
@@ -88,15 +99,21 @@ def cpu_baseline(name: str, D: int, k: int, scale: int):
     T = make_tensors(Nc, Nn, D, seed=0)
     rels = (oracle.relation(g.near, oracle.NORM_MEAN), oracle.relation(g.pins, oracle.NORM_MEAN),
             oracle.relation(g.pinned, oracle.NORM_SYM))
+    one_k = ks[0] == ks[1] and ks[2] == ks[3]
     t0 = time.perf_counter()
-    of = oracle.heteroconv_fwd(*rels, T.X_cell, T.X_net, T.W, k, k)
-    oracle.heteroconv_bwd(*rels, T.W, of, T.dY_cell, T.dY_net)
+    if one_k:
+        of = oracle.heteroconv_fwd(*rels, T.X_cell, T.X_net, T.W, ks[0], ks[3])
+        oracle.heteroconv_bwd(*rels, T.W, of, T.dY_cell, T.dY_net)
+    else:
+        of = opr.heteroconv_fwd(*rels, T.X_cell, T.X_net, T.W, opr.Ks(*ks))
+        opr.heteroconv_bwd(*rels, T.W, of, T.dY_cell, T.dY_net)
     dt = time.perf_counter() - t0
-    models = kernel_models(Nc, Nn, dict(near=g.near.nnz, pins=g.pins.nnz, pinned=g.pinned.nnz), D, k, k)
+    models = kernel_models(Nc, Nn, dict(near=g.near.nnz, pins=g.pins.nnz, pinned=g.pinned.nnz), D, ks)
     step_bytes = sum(b for b, _ in models.values())
     return dict(value=round(step_bytes / dt / 1e9, 4), unit="GB/s", cores=1, kind="oracle",
                 sample=f"oracle HeteroConv fwd+bwd (fp64, 1 thread) on a 1/{scale}-scale '{name}' graph: "
-                       f"{Nc} cells, {Nn} nets, E_near={g.near.nnz}, E_pins={g.pins.nnz}, D={D}, k={k}; "
+                       f"{Nc} cells, {Nn} nets, E_near={g.near.nnz}, E_pins={g.pins.nnz}, D={D}, "
+                       f"k={ks[0] if one_k and ks[0] == ks[3] else '/'.join(map(str, ks))}; "
                        f"{dt:.2f} s for {step_bytes / 1e6:.1f} MB of algorithmic traffic",
                 seconds=round(dt, 3), host_cores_available=len(os.sched_getaffinity(0)))
 
@@ -108,6 +125,11 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="large", help="tiny | small | medium | large | subgraph")
     ap.add_argument("--k", type=int, default=None, help="D-ReLU k (default: the workload's; large sweeps 8..64)")
+    ap.add_argument("--k-per-relation", default=None,
+                    help="one K per edge type: 'k_near,k_pins,k_pinned', or 'best' = what --profile-k picks")
+    ap.add_argument("--profile-k", action="store_true",
+                    help="optimal-K profiling of the workload's graph over K = 2..64 before the timed steps "
+                         "(reported as k_profile)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-scale", type=int, default=None, help="oracle sample = 1/scale of the workload")
     ap.add_argument("--no-profile-events", action="store_true", help="do not bracket kernels with HIP events")
@@ -167,10 +189,27 @@ def main() -> int:
     t_graph = time.perf_counter()
     layer = P.HeteroConv(near, pins, pinned, D, k, k)     # device transposes + scratch
     t_ctx = time.perf_counter() - t_graph
+    X_cell, X_net = dev(T.X_cell), dev(T.X_net)
+    k_profile = None
+    if args.profile_k or args.k_per_relation == "best":
+        cand = [c for c in (2, 4, 8, 16, 32, 64) if c <= D]
+        tp = time.perf_counter()
+        ms_f, ms_b, best = layer.heteroconv_profile_k(X_cell, X_net, cand, warmup=2, reps=5)
+        k_profile = dict(candidates=cand, relations=["near", "pins", "pinned"],
+                         ms_fwd=[[round(v, 4) for v in r] for r in ms_f], ms_bwd=[[round(v, 4) for v in r] for r in ms_b],
+                         best=list(best), seconds=round(time.perf_counter() - tp, 3))
+    if args.k_per_relation:
+        kk = k_profile["best"] if args.k_per_relation == "best" else [int(v) for v in args.k_per_relation.split(",")]
+        if len(kk) != 3:
+            print("bench.py: --k-per-relation takes k_near,k_pins,k_pinned", file=sys.stderr)
+            return 2
+        layer.heteroconv_destroy()
+        layer = P.HeteroConv(near, pins, pinned, D, per_relation=kk)
+    ks = layer.heteroconv_get_k()
+    klabel = str(k) if not args.k_per_relation else "k_near/k_pins/k_pinned=" + "/".join(str(v) for v in (ks[0], ks[1], ks[3]))
     layer.heteroconv_set_overlap({"auto": P.DR_OVERLAP_AUTO, "on": P.DR_OVERLAP_ON, "off": P.DR_OVERLAP_OFF}[args.overlap])
     saved = layer.alloc_saved()
     Wd = {n: dev(T.W[n]) for n in P.WEIGHT_NAMES}
-    X_cell, X_net = dev(T.X_cell), dev(T.X_net)
     dY_cell, dY_net = dev(T.dY_cell), dev(T.dY_net)
     Y_cell = torch.empty((g.Nc, D), dtype=torch.float32, device="cuda")
     Y_net = torch.empty((g.Nn, D), dtype=torch.float32, device="cuda")
@@ -199,9 +238,9 @@ def main() -> int:
     times = {} if args.no_profile_events else layer.heteroconv_kernel_times()
     layer.heteroconv_profile(False)
 
-    models = kernel_models(g.Nc, g.Nn, E, D, k, k)
+    models = kernel_models(g.Nc, g.Nn, E, D, ks)
     step_bytes = sum(b for b, _ in models.values())
-    dr_bytes = sum(models[n][0] for n in DR_KERNELS)
+    dr_bytes = sum(models[n][0] for n in DR_KERNELS if n in models)
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
 
     kernels = {}
@@ -222,7 +261,8 @@ def main() -> int:
         tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
         if os.path.exists(tpath):
             try:
-                traffic = json.load(open(tpath)).get(f"{args.workload}.k{k}", {}).get(dom)
+                tkey = f"{args.workload}.k{k}" if not args.k_per_relation else None
+                traffic = json.load(open(tpath)).get(tkey, {}).get(dom)
             except Exception:
                 traffic = None
         intensity = f / b
@@ -241,7 +281,8 @@ def main() -> int:
             roofline["measured_hbm_frac"] = round(traffic / avg_s / 1e9 / HBM_PEAK_GBS, 4)
         dr_ms = sum(kernels[n]["ms"] for n in DR_KERNELS if n in kernels)
         dr_flops = sum(models[n][1] for n in DR_KERNELS if n.startswith("dr_spmm"))
-        dr_region = dict(kernels="D-ReLU x2 + DR-SpMM fwd x3 + bwd x3", sum_ms=round(dr_ms, 4),
+        n_topk = sum(1 for n in DR_KERNELS if n.startswith("dr_topk") and n in kernels)
+        dr_region = dict(kernels=f"D-ReLU x{n_topk} + DR-SpMM fwd x3 + bwd x3", sum_ms=round(dr_ms, 4),
                          MB=round(dr_bytes / 1e6, 1), GBs=round(dr_bytes / (dr_ms * 1e-3) / 1e9, 1),
                          frac_of_hbm_peak=round(dr_bytes / (dr_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                          GFLOPs=round(dr_flops / (dr_ms * 1e-3) / 1e9, 1))
@@ -260,7 +301,7 @@ def main() -> int:
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": f"{args.workload}: {g.Nc} cells, {g.Nn} nets, E_near={E['near']}, "
-                               f"E_pins={E['pins']}, D={D}, k={k}, one HeteroConv layer fwd+bwd"
+                               f"E_pins={E['pins']}, D={D}, k={klabel}, one HeteroConv layer fwd+bwd"
                                + (" (cell ids randomly permuted)" if args.permute_cells else ""),
                    "step_algorithmic_MB": round(step_bytes / 1e6, 1),
                    "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
@@ -270,9 +311,11 @@ def main() -> int:
         "dr_spmm_kernels": dr_region,
         "kernels": kernels,
     }
+    if k_profile:
+        out["k_profile"] = k_profile
     if not args.no_cpu_baseline:
         scale = args.cpu_scale or max(1, g.Nc // 200000)     # about 10-15 s of single-thread oracle work
-        out["cpu_baseline"] = cpu_baseline(args.workload, D, k, scale)
+        out["cpu_baseline"] = cpu_baseline(args.workload, D, ks, scale)
     layer.heteroconv_destroy()
     print(json.dumps(out), flush=True)
     return 0

@@ -210,18 +210,36 @@ struct Stream {
 // forward
 // ---------------------------------------------------------------------------------------------------
 
-template <int KPL> struct Pairs {        // KPL consecutive (value, column) pairs of one CBSR row
-    float v[KPL];
-    uint16_t c[KPL];
-    __device__ __forceinline__ void load(const float* __restrict__ vals, const uint16_t* __restrict__ idx, uint32_t off) {
-        if constexpr (KPL == 1) {
-            v[0] = vals[off];
-            c[0] = idx[off];
+// The pairs of one gathered CBSR row that one lane of a group handles.
+//   KPL > 0: KPL consecutive pairs [t*KPL, (t+1)*KPL), vector loads (k = 8*KPL).
+//   KPL < 0: the -KPL pairs t, t+8, t+16, ... with scalar loads, for every other k <= -8*KPL (the small K of the
+//            optimal-K candidates among them).  Pairs past k are loaded from a clamped address and accumulated
+//            into the padding words behind the row buffer, so no load or LDS access is conditional.
+template <int KPL> struct Pairs {
+    static constexpr int N = KPL > 0 ? KPL : -KPL;
+    float v[N];
+    uint16_t c[N];
+    __device__ __forceinline__ void load(const float* __restrict__ vals, const uint16_t* __restrict__ idx, uint32_t rowbase,
+                                         int t, int k, int D) {
+        if constexpr (KPL < 0) {
+#pragma unroll
+            for (int u = 0; u < N; ++u) {
+                const int q = t + kLPE * u;
+                const uint32_t off = rowbase + (uint32_t)min(q, k - 1);
+                v[u] = vals[off];
+                const uint16_t col = idx[off];
+                c[u] = q < k ? col : (uint16_t)(D + (t & (kBufPad - 1)));
+            }
+        } else if constexpr (KPL == 1) {
+            v[0] = vals[rowbase + t];
+            c[0] = idx[rowbase + t];
         } else if constexpr (KPL == 2) {
+            const uint32_t off = rowbase + 2 * t;
             float2 a = *reinterpret_cast<const float2*>(vals + off);
             ushort2 b = *reinterpret_cast<const ushort2*>(idx + off);
             v[0] = a.x; v[1] = a.y; c[0] = b.x; c[1] = b.y;
         } else {
+            const uint32_t off = rowbase + KPL * t;
 #pragma unroll
             for (int q = 0; q < KPL / 4; ++q) {
                 float4 a = *reinterpret_cast<const float4*>(vals + off + 4 * q);
@@ -232,13 +250,13 @@ template <int KPL> struct Pairs {        // KPL consecutive (value, column) pair
         }
     }
     // buf[c] += a * v for all pairs; the columns of one CBSR row are distinct, so the reads can all be
-    // issued before the writes
+    // issued before the writes (lanes past k share padding words: what lands there is never read)
     __device__ __forceinline__ void accumulate(float* buf, float a) const {
-        float old[KPL];
+        float old[N];
 #pragma unroll
-        for (int u = 0; u < KPL; ++u) old[u] = buf[c[u]];
+        for (int u = 0; u < N; ++u) old[u] = buf[c[u]];
 #pragma unroll
-        for (int u = 0; u < KPL; ++u) buf[c[u]] = fmaf(a, v[u], old[u]);
+        for (int u = 0; u < N; ++u) buf[c[u]] = fmaf(a, v[u], old[u]);
     }
 };
 
@@ -269,14 +287,14 @@ template <int KPL, int EPI> struct FwdBatch {   // EPI consecutive stream record
 template <int KPL, int EPI, bool STRIDED>
 __device__ __forceinline__ void fwd_issue(FwdBatch<KPL, EPI>& b, Stream& st, const WavePlan& plan,
                                           const float* __restrict__ xs_vals, const uint16_t* __restrict__ xs_idx,
-                                          int k, int t, int g, int sa, int npass, int base) {
+                                          int D, int k, int t, int g, int sa, int npass, int base) {
 #pragma unroll
     for (int q = 0; q < EPI; ++q) {
         const bool valid = !st.done;
         const int2 rec = plan.sRec[valid ? st.cur : 0];
         const uint32_t col = valid ? (uint32_t)rec.x : 0u;   // exhausted lanes gather source row 0
         b.a[q] = __int_as_float(rec.y);
-        b.p[q].load(xs_vals, xs_idx, col * (uint32_t)k + (uint32_t)(t * KPL));
+        b.p[q].load(xs_vals, xs_idx, col * (uint32_t)k, t, k, D);
         b.meta[q] = valid ? st.template advance<STRIDED>(plan, sa, npass, base) : 0u;
     }
 }
@@ -297,19 +315,19 @@ template <int KPL, int EPI, bool STRIDED>
 __device__ __forceinline__ void fwd_run(Stream& st, const WavePlan& plan, const float* __restrict__ xs_vals,
                                         const uint16_t* __restrict__ xs_idx, float* buf, float* __restrict__ Hblk,
                                         int D, int k, int t, int g, int sa, int npass, int base, int vec_store) {
-    if constexpr (KPL > 0) {
+    if constexpr (KPL != 0) {
         FwdBatch<KPL, EPI> A, B;
-        fwd_issue<KPL, EPI, STRIDED>(A, st, plan, xs_vals, xs_idx, k, t, g, sa, npass, base);
+        fwd_issue<KPL, EPI, STRIDED>(A, st, plan, xs_vals, xs_idx, D, k, t, g, sa, npass, base);
         for (;;) {
-            fwd_issue<KPL, EPI, STRIDED>(B, st, plan, xs_vals, xs_idx, k, t, g, sa, npass, base);
+            fwd_issue<KPL, EPI, STRIDED>(B, st, plan, xs_vals, xs_idx, D, k, t, g, sa, npass, base);
             fwd_consume(A, buf, Hblk, D, t, vec_store);
             if (!__any(B.meta[0] & kValid)) break;
-            fwd_issue<KPL, EPI, STRIDED>(A, st, plan, xs_vals, xs_idx, k, t, g, sa, npass, base);
+            fwd_issue<KPL, EPI, STRIDED>(A, st, plan, xs_vals, xs_idx, D, k, t, g, sa, npass, base);
             fwd_consume(B, buf, Hblk, D, t, vec_store);
             if (!__any(A.meta[0] & kValid)) break;
         }
     } else {
-        // generic k: one record at a time, lane t takes pairs t, t+8, ... with scalar loads
+        // k > 32 that is not 64 or 128: one record at a time, lane t takes pairs t, t+8, ... with scalar loads
         while (__any(!st.done)) {
             if (!st.done) {
                 const int2 rec = plan.sRec[st.cur];
@@ -407,6 +425,7 @@ int launch_spmm_fwd(const dr_csr* A, const float* xs_vals, const uint16_t* xs_id
         else if (q == 2 && aligned(xs_vals, 8) && aligned(xs_idx, 4)) kpl = 2;
         else if ((q == 4 || q == 8 || q == 16) && aligned(xs_vals, 16) && aligned(xs_idx, 8)) kpl = q;
     }
+    if (kpl == 0 && k <= 4 * kLPE) kpl = -((k + kLPE - 1) / kLPE);   // strided scalar pairs, masked past k
     const size_t lds = sizeof(float) * (size_t)kNG * (D + kBufPad) + sizeof(int) * (size_t)plan_ints();
     dim3 grid((unsigned)(per_xcd * kNumXcd)), block(kWave);
 #define DRC_LAUNCH_FWD(V, E)                                                                                       \
@@ -418,6 +437,10 @@ int launch_spmm_fwd(const dr_csr* A, const float* xs_vals, const uint16_t* xs_id
         case 4: DRC_LAUNCH_FWD(4, 2); break;
         case 8: DRC_LAUNCH_FWD(8, 1); break;
         case 16: DRC_LAUNCH_FWD(16, 1); break;
+        case -1: DRC_LAUNCH_FWD(-1, 4); break;
+        case -2: DRC_LAUNCH_FWD(-2, 3); break;
+        case -3: DRC_LAUNCH_FWD(-3, 2); break;
+        case -4: DRC_LAUNCH_FWD(-4, 2); break;
         default: DRC_LAUNCH_FWD(0, 1); break;
     }
 #undef DRC_LAUNCH_FWD

@@ -126,6 +126,11 @@ SPMM_CASES = [
     (300, 200, 7, 96, 6, False, False),        # k % 4 == 2: pair loads
     (200, 150, 5, 1024, 300, False, False),    # wide rows, k above one lane group
     (100, 80, 5, 5, 1, True, False),
+    (777, 1301, 9, 128, 2, False, True),       # fewer pairs than lanes in a row group (masked lanes), long rows
+    (1000, 900, 12, 128, 4, True, True),
+    (600, 500, 10, 64, 12, True, True),        # two strided pairs per lane, the second masked for half the lanes
+    (600, 500, 10, 96, 20, False, True),       # three
+    (600, 500, 10, 128, 28, True, False),      # four
 ]
 
 
