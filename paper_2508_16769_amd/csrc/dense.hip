@@ -386,11 +386,19 @@ __global__ __launch_bounds__(kPT, (EPI == kEpiStore ? (AK == kACbsrDense ? 2 : 4
                         __builtin_amdgcn_wave_barrier();
                         const int k2 = p.second.k;
                         const size_t base2 = (size_t)min(tile * BM + prow, p.rows - 1) * k2;
-                        for (int u = 0; u * TPR < k2; ++u) {           // fetched here: no registers held across the multiply
-                            const int t = ppart + TPR * u;
-                            const float v = p.second.compact[base2 + min(t, k2 - 1)];
-                            const int c = p.second.idx[base2 + min(t, k2 - 1)];
-                            orow[t < k2 ? c : D] += v;
+                        // fetched here, four pairs per thread at a time: no registers held across the multiply
+                        for (int u0 = 0; u0 * TPR < k2; u0 += 4) {
+                            float v[4];
+                            int cc[4];
+#pragma unroll
+                            for (int u = 0; u < 4; ++u) {
+                                const int t = ppart + TPR * (u0 + u);
+                                v[u] = p.second.compact[base2 + min(t, k2 - 1)];
+                                const int c = p.second.idx[base2 + min(t, k2 - 1)];
+                                cc[u] = t < k2 ? c : D;
+                            }
+#pragma unroll
+                            for (int u = 0; u < 4; ++u) orow[cc[u]] += v[u];
                         }
                     }
                 }

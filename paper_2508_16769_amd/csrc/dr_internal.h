@@ -50,6 +50,9 @@ __device__ __forceinline__ int xcd_contiguous_tile(int wg, int per_xcd) {
 
 // launchers (host side, argument checks already done by the ABI layer) ------------------------------
 int launch_topk(const float* X, int64_t n, int D, int k, float* vals, uint16_t* idx, hipStream_t s);
+// the same rows selected at two widths in one pass over X (vals2 == nullptr: only the first)
+int launch_topk2(const float* X, int64_t n, int D, int k, float* vals, uint16_t* idx, int k2, float* vals2, uint16_t* idx2,
+                 hipStream_t s);
 int launch_spmm_fwd(const dr_csr* A, const float* xs_vals, const uint16_t* xs_idx, int D, int k, float* H,
                     hipStream_t s);
 int launch_spmm_bwd(const dr_csr* At, const float* dH, const uint16_t* xs_idx, int D, int k, float* dXs,

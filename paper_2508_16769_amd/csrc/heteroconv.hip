@@ -10,12 +10,12 @@
 namespace {
 // kernel ids for the optional per-kernel timing (heteroconv_profile / heteroconv_kernel_times)
 enum KernelId {
-    kTopkCell, kTopkNet, kTopkCellPins, kTopkNetSelf, kFwdNear, kFwdPins, kFwdPinned, kProjNear, kProjPins, kProjPinnedMerge,
+    kTopkCell, kTopkNet, kFwdNear, kFwdPins, kFwdPinned, kProjNear, kProjPins, kProjPinnedMerge,
     kDhNear, kBwdNear, kWgNeighNear, kWgSelfNear, kDhPins, kBwdPins, kSelfNearSample,
     kWgNeighPins, kWgSelfPins, kDhPinned, kBwdPinned, kSelfPinsSample, kWgPinned, kNumKernels
 };
 const char* const kKernelNames[kNumKernels] = {
-    "dr_topk.cell", "dr_topk.net", "dr_topk.cell.pins", "dr_topk.net.self", "dr_spmm_fwd.near", "dr_spmm_fwd.pins", "dr_spmm_fwd.pinned",
+    "dr_topk.cell", "dr_topk.net", "dr_spmm_fwd.near", "dr_spmm_fwd.pins", "dr_spmm_fwd.pinned",
     "proj.near", "proj.pins", "proj.pinned+merge",
     "dproj.near", "dr_spmm_bwd.near", "wgrad.neigh_near", "wgrad.self_near", "dproj.pins", "dr_spmm_bwd.pins",
     "dself.near+dX", "wgrad.neigh_pins", "wgrad.self_pins", "dproj.pinned",
@@ -408,22 +408,25 @@ int heteroconv_fwd(dr_heteroconv* c, const float* X_cell, const float* X_net, co
     // relations (pinned, pins) come before the grid-local one, and the streaming projections last.
     const CbsrSets q = cbsr_sets(c, S);
 
-    // D-ReLU(net) at k_pinned, then pinned: net -> cell
-    { ScopedTiming tm(c, kTopkNet, s_pinned); DRC_TRY(launch_topk(X_net, c->Nn, D, c->k_pinned, S->vals_net, S->idx_net, s_pinned)); }
+    // D-ReLU(net), then pinned: net -> cell.  A node type that is read at two widths is selected at both in one
+    // pass over its embeddings.
+    {
+        ScopedTiming tm(c, kTopkNet, s_pinned);
+        DRC_TRY(launch_topk2(X_net, c->Nn, D, c->k_pinned, S->vals_net, S->idx_net, c->k_self,
+                             q.net_split ? S->vals_net_self : nullptr, q.net_split ? S->idx_net_self : nullptr, s_pinned));
+    }
     DRC_HIP(hipEventRecord(c->ev_topk_net, s_pinned));
     { ScopedTiming tm(c, kFwdPinned, s_pinned); DRC_TRY(launch_spmm_fwd(&c->A[2], q.v_pinned, q.i_pinned, D, c->k_pinned, S->H_pinned, s_pinned)); }
 
     // D-ReLU(cell), then pins: cell -> net and near: cell -> cell
-    if (q.cell_split) {
-        { ScopedTiming tm(c, kTopkCellPins, s_pins); DRC_TRY(launch_topk(X_cell, c->Nc, D, c->k_pins, S->vals_cell_pins, S->idx_cell_pins, s_pins)); }
-        { ScopedTiming tm(c, kFwdPins, s_pins); DRC_TRY(launch_spmm_fwd(&c->A[1], q.v_pins, q.i_pins, D, c->k_pins, S->H_pins, s_pins)); }
-        { ScopedTiming tm(c, kTopkCell, s_near); DRC_TRY(launch_topk(X_cell, c->Nc, D, c->k_near, S->vals_cell, S->idx_cell, s_near)); }
-    } else {
-        { ScopedTiming tm(c, kTopkCell, s_near); DRC_TRY(launch_topk(X_cell, c->Nc, D, c->k_near, S->vals_cell, S->idx_cell, s_near)); }
-        DRC_HIP(hipEventRecord(c->ev_topk_cell, s_near));
-        DRC_HIP(hipStreamWaitEvent(s_pins, c->ev_topk_cell, 0));
-        { ScopedTiming tm(c, kFwdPins, s_pins); DRC_TRY(launch_spmm_fwd(&c->A[1], q.v_pins, q.i_pins, D, c->k_pins, S->H_pins, s_pins)); }
+    {
+        ScopedTiming tm(c, kTopkCell, s_near);
+        DRC_TRY(launch_topk2(X_cell, c->Nc, D, c->k_near, S->vals_cell, S->idx_cell, c->k_pins,
+                             q.cell_split ? S->vals_cell_pins : nullptr, q.cell_split ? S->idx_cell_pins : nullptr, s_near));
     }
+    DRC_HIP(hipEventRecord(c->ev_topk_cell, s_near));
+    DRC_HIP(hipStreamWaitEvent(s_pins, c->ev_topk_cell, 0));
+    { ScopedTiming tm(c, kFwdPins, s_pins); DRC_TRY(launch_spmm_fwd(&c->A[1], q.v_pins, q.i_pins, D, c->k_pins, S->H_pins, s_pins)); }
     { ScopedTiming tm(c, kFwdNear, s_near); DRC_TRY(launch_spmm_fwd(&c->A[0], q.v_near, q.i_near, D, c->k_near, S->H_near, s_near)); }
 
     // projections: near (self + neighbour), pins (self + neighbour), pinned merged into Y_cell by max
@@ -434,12 +437,7 @@ int heteroconv_fwd(dr_heteroconv* c, const float* X_cell, const float* X_net, co
         { ScopedTiming tm(c, kProjNear, s_near); DRC_TRY(launch_gemm(seg, 2, c->Nc, D, kEpiStore, Y_cell, nullptr, SampleSet{}, SampleSet{}, s_near)); }
     }
     DRC_HIP(hipEventRecord(c->ev_near, s_near));
-    if (q.net_split) {   // the self term of the pins module has its own width: selected on the pins stream itself
-        ScopedTiming tm(c, kTopkNetSelf, s_pins);
-        DRC_TRY(launch_topk(X_net, c->Nn, D, c->k_self, S->vals_net_self, S->idx_net_self, s_pins));
-    } else {
-        DRC_HIP(hipStreamWaitEvent(s_pins, c->ev_topk_net, 0));
-    }
+    DRC_HIP(hipStreamWaitEvent(s_pins, c->ev_topk_net, 0));
     {
         GemmOperand seg[2] = {};
         seg[0].cbsr_vals = q.v_self; seg[0].cbsr_idx = q.i_self; seg[0].k = c->k_self; seg[0].W = W->self_pins;

@@ -7,7 +7,7 @@
 // popcount of the ballot, started below the previous row's sign and exponent bits when two probes confirm
 // them, and with an early exit once a probe isolates exactly k elements; compaction
 // positions come from mbcnt prefix counts of the keep-ballots, which yields ascending column order for
-// free.
+// free.  A row that is needed at two widths (one K per edge type) is loaded once and selected twice.
 #include "dr_internal.h"
 
 namespace drc {
@@ -24,9 +24,10 @@ __device__ __forceinline__ int lanes_below(unsigned long long m) {
 
 constexpr int kRowsInFlight = 4;   // rows whose loads are outstanding per wavefront
 
-template <int EPL>
+template <int EPL, bool DUAL>
 __global__ __launch_bounds__(256) void topk_rows_kernel(const float* __restrict__ X, int n, int D, int k,
-                                                        float* __restrict__ vals, uint16_t* __restrict__ idx) {
+                                                        float* __restrict__ vals, uint16_t* __restrict__ idx, int k2,
+                                                        float* __restrict__ vals2, uint16_t* __restrict__ idx2) {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
     const int stride = gridDim.x * (blockDim.x >> 6);        // rows between consecutive rows of one wavefront
@@ -40,8 +41,9 @@ __global__ __launch_bounds__(256) void topk_rows_kernel(const float* __restrict_
 #pragma unroll
         for (int s = 0; s < EPL; ++s) dst[s] = __builtin_nontemporal_load(x + min(s * kWave + lane, D - 1));   // read once
     };
-    uint32_t t_hint = 0;                                      // threshold of the previous row of this wavefront
-    auto select_row = [&](const float (&val)[EPL], int row) {
+    uint32_t hint = 0, hint2 = 0;                             // thresholds of the previous row of this wavefront
+    auto select_row = [&](const float (&val)[EPL], int row, int k, float* __restrict__ vals, uint16_t* __restrict__ idx,
+                          uint32_t& t_hint) {
         uint32_t key[EPL];
 #pragma unroll
         for (int s = 0; s < EPL; ++s) key[s] = (s * kWave + lane < D) ? order_key(val[s]) : 0u;   // padding key 0 < real keys
@@ -103,28 +105,43 @@ __global__ __launch_bounds__(256) void topk_rows_kernel(const float* __restrict_
 #pragma unroll
         for (int i = 0; i < kRowsInFlight; ++i) {
             const int row = base + i * stride;
-            if (row < n) select_row(v[i], row);
+            if (row < n) {
+                select_row(v[i], row, k, vals, idx, hint);
+                if constexpr (DUAL) select_row(v[i], row, k2, vals2, idx2, hint2);
+            }
             load_row(v[i], row + kRowsInFlight * stride);
         }
     }
 }
 
 template <int EPL>
-static void launch_epl(const float* X, int n, int D, int k, float* vals, uint16_t* idx, hipStream_t s) {
+static void launch_epl(const float* X, int n, int D, int k, float* vals, uint16_t* idx, int k2, float* vals2,
+                       uint16_t* idx2, hipStream_t s) {
     int waves_per_block = 4;
     long blocks = ((long)n + waves_per_block - 1) / waves_per_block;
     if (blocks > 4096) blocks = 4096;            // two full rounds of 8 waves/SIMD; each wavefront strides over rows
-    hipLaunchKernelGGL(topk_rows_kernel<EPL>, dim3((unsigned)blocks), dim3(256), 0, s, X, n, D, k, vals, idx);
+    if (vals2)
+        hipLaunchKernelGGL((topk_rows_kernel<EPL, true>), dim3((unsigned)blocks), dim3(256), 0, s, X, n, D, k, vals, idx, k2,
+                           vals2, idx2);
+    else
+        hipLaunchKernelGGL((topk_rows_kernel<EPL, false>), dim3((unsigned)blocks), dim3(256), 0, s, X, n, D, k, vals, idx, 0,
+                           nullptr, nullptr);
+}
+
+int launch_topk2(const float* X, int64_t n, int D, int k, float* vals, uint16_t* idx, int k2, float* vals2, uint16_t* idx2,
+                 hipStream_t s) {
+    if (n == 0) return DR_OK;
+    if (D <= 64) launch_epl<1>(X, (int)n, D, k, vals, idx, k2, vals2, idx2, s);
+    else if (D <= 128) launch_epl<2>(X, (int)n, D, k, vals, idx, k2, vals2, idx2, s);
+    else if (D <= 256) launch_epl<4>(X, (int)n, D, k, vals, idx, k2, vals2, idx2, s);
+    else if (D <= 512) launch_epl<8>(X, (int)n, D, k, vals, idx, k2, vals2, idx2, s);
+    else launch_epl<16>(X, (int)n, D, k, vals, idx, k2, vals2, idx2, s);
+    DRC_HIP(hipGetLastError());
+    return DR_OK;
 }
 
 int launch_topk(const float* X, int64_t n, int D, int k, float* vals, uint16_t* idx, hipStream_t s) {
-    if (D <= 64) launch_epl<1>(X, (int)n, D, k, vals, idx, s);
-    else if (D <= 128) launch_epl<2>(X, (int)n, D, k, vals, idx, s);
-    else if (D <= 256) launch_epl<4>(X, (int)n, D, k, vals, idx, s);
-    else if (D <= 512) launch_epl<8>(X, (int)n, D, k, vals, idx, s);
-    else launch_epl<16>(X, (int)n, D, k, vals, idx, s);
-    DRC_HIP(hipGetLastError());
-    return DR_OK;
+    return launch_topk2(X, n, D, k, vals, idx, 0, nullptr, nullptr, s);
 }
 
 }  // namespace drc
