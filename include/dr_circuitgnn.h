@@ -287,6 +287,19 @@ int64_t hgnn_num_params(int32_t n_layers, int32_t D);
 int hgnn_create(dr_hgnn** model, int32_t n_graphs, dr_heteroconv* const* graphs, int32_t n_layers);
 
 /*
+ * The same model with the batch stacked into ONE block-diagonal graph on the device (sub-graph q's rows and
+ * columns shifted by the node counts of the sub-graphs before it): a step then issues one launch per kernel for the
+ * whole batch instead of one per sub-graph, which is the faster mapping for small sub-graphs (a 20 000-cell launch
+ * fills a fraction of the GPU).  The result is the same step: same selections, loss and gradient up to the order of
+ * the fp32 sums over rows.  All contexts must have the same D and the same K; they only lend their relations and may
+ * be destroyed once the call returns (the CSR arrays are copied).  hgnn_train_step takes the same per-sub-graph
+ * pointer tables; inputs that already lie behind one another in memory (X_cell[q+1] == X_cell[q] + Nc_q * D, ...) are
+ * read in place, others are first copied into a staging buffer.  hgnn_get_layer_buffers returns sub-graph q's rows
+ * of the stacked buffers; dW is then the gradient of the whole batch for every q.
+ */
+int hgnn_create_batched(dr_hgnn** model, int32_t n_graphs, dr_heteroconv* const* graphs, int32_t n_layers);
+
+/*
  * One training step.  X_cell[g] / X_net[g] / target[g]: host arrays of n_graphs device pointers
  * ([Nc_g,D], [Nn_g,D], [Nc_g]).  theta, adam_m, adam_v: device vectors of hgnn_num_params floats, updated in
  * place (step = 1 for the first update; moments start at zero); the hyper-parameters are doubles so that

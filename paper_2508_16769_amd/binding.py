@@ -35,7 +35,7 @@ EXPORTS = (
     "heteroconv_create", "heteroconv_create_per_relation", "heteroconv_get_k", "heteroconv_profile_k", "heteroconv_fwd", "heteroconv_bwd", "heteroconv_get_transpose", "heteroconv_destroy",
     "heteroconv_profile", "heteroconv_num_kernels", "heteroconv_kernel_name", "heteroconv_kernel_times",
     "heteroconv_set_overlap",
-    "hgnn_num_params", "hgnn_create", "hgnn_train_step", "hgnn_get_layer_buffers", "hgnn_destroy",
+    "hgnn_num_params", "hgnn_create", "hgnn_create_batched", "hgnn_train_step", "hgnn_get_layer_buffers", "hgnn_destroy",
 )
 
 
@@ -319,12 +319,14 @@ def _view(ptr: int, shape, dtype) -> torch.Tensor:
 class Hgnn:
     """Owner of a ``dr_hgnn*`` model state (hgnn_create / hgnn_destroy) over a batch of sub-graph contexts."""
 
-    def __init__(self, graphs: Sequence["HeteroConv"], n_layers: int):
+    def __init__(self, graphs: Sequence["HeteroConv"], n_layers: int, batched: bool = False):
+        """batched=False -> hgnn_create (one stream per sub-graph); True -> hgnn_create_batched (one stacked graph)."""
         self._graphs = list(graphs)
-        self.n_layers, self.D = n_layers, graphs[0].D
+        self.n_layers, self.D, self.batched = n_layers, graphs[0].D, batched
         self._model = ctypes.c_void_p(0)
         arr = (ctypes.c_void_p * len(graphs))(*[g._ctx.value for g in graphs])
-        _check(load().hgnn_create(ctypes.byref(self._model), ctypes.c_int32(len(graphs)), arr, ctypes.c_int32(n_layers)))
+        create = load().hgnn_create_batched if batched else load().hgnn_create
+        _check(create(ctypes.byref(self._model), ctypes.c_int32(len(graphs)), arr, ctypes.c_int32(n_layers)))
 
     def hgnn_train_step(self, X_cell, X_net, target, theta, adam_m, adam_v, lr, beta1, beta2, eps, weight_decay, step,
                         grad_out, loss_out, stream=None) -> None:

@@ -70,6 +70,9 @@ struct HeteroDims {
     int k_near, k_pins, k_self, k_pinned;   // D-ReLU widths: cells for near / for pins, nets for the pins self term / for pinned
 };
 HeteroDims heteroconv_dims(const dr_heteroconv* c);
+const dr_csr* heteroconv_relations(const dr_heteroconv* c);   // [3] near, pins, pinned as given to the create call
+int heteroconv_create_widths(dr_heteroconv** ctx, const dr_csr* near, const dr_csr* pins, const dr_csr* pinned, int32_t D,
+                             int32_t k_near, int32_t k_pins, int32_t k_self, int32_t k_pinned);
 
 // dense part of the layer ------------------------------------------------------------------------------
 struct GemmOperand {              // one K-segment of C = sum_seg A_seg * B_seg

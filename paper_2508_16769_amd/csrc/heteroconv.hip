@@ -123,8 +123,10 @@ struct ScopedTiming {
 
 }  // namespace
 
-static int create_impl(dr_heteroconv** ctx, const dr_csr* near, const dr_csr* pins, const dr_csr* pinned, int32_t D,
-                       int32_t k_near, int32_t k_pins, int32_t k_self, int32_t k_pinned) {
+const dr_csr* drc::heteroconv_relations(const dr_heteroconv* c) { return c->A; }
+
+int drc::heteroconv_create_widths(dr_heteroconv** ctx, const dr_csr* near, const dr_csr* pins, const dr_csr* pinned, int32_t D,
+                                  int32_t k_near, int32_t k_pins, int32_t k_self, int32_t k_pinned) {
     DRC_REQUIRE(ctx != nullptr, "heteroconv_create: null ctx");
     *ctx = nullptr;
     if (int rc = check_csr(near, "heteroconv_create: near", true)) return rc;
@@ -199,12 +201,12 @@ extern "C" {
 
 int heteroconv_create(dr_heteroconv** ctx, const dr_csr* near, const dr_csr* pins, const dr_csr* pinned,
                       int32_t D, int32_t k_cell, int32_t k_net) {
-    return create_impl(ctx, near, pins, pinned, D, k_cell, k_cell, k_net, k_net);
+    return heteroconv_create_widths(ctx, near, pins, pinned, D, k_cell, k_cell, k_net, k_net);
 }
 
 int heteroconv_create_per_relation(dr_heteroconv** ctx, const dr_csr* near, const dr_csr* pins, const dr_csr* pinned,
                                    int32_t D, int32_t k_near, int32_t k_pins, int32_t k_pinned) {
-    return create_impl(ctx, near, pins, pinned, D, k_near, k_pins, k_pins, k_pinned);
+    return heteroconv_create_widths(ctx, near, pins, pinned, D, k_near, k_pins, k_pins, k_pinned);
 }
 
 int heteroconv_get_k(const dr_heteroconv* ctx, int32_t* k_near, int32_t* k_pins, int32_t* k_self, int32_t* k_pinned) {

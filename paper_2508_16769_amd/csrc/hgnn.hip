@@ -10,6 +10,12 @@
 //   head_bwd_kernel                    dY = dpred (x) w_head, per-workgroup partials of dw_head = Y^T dpred
 //   loss_reduce_kernel, adam_kernel    fixed-order sums over sub-graphs and partials, then the update
 // Every sum has a fixed order, so a step is reproducible bit for bit.
+//
+// Batched mode (hgnn_create_batched): the sub-graphs are stacked into ONE block-diagonal graph on the device
+// (rows and columns of sub-graph q shifted by the node counts of the sub-graphs before it) and the step runs
+// as a single-graph step: one launch per kernel for the whole batch instead of one per sub-graph.  A
+// 20 000-cell launch fills a fraction of the chip and a streamed step of 8 x 3 layers issues some 800 of
+// them, so for small sub-graphs stacking is the faster mapping of "independent sub-graphs" (Section 3.4).
 #include "dr_internal.h"
 
 #include <cmath>
@@ -132,6 +138,37 @@ __global__ __launch_bounds__(256) void adam_kernel(float* __restrict__ theta, fl
     theta[e] = th - lr * (m2 * inv_bc1) / (sqrtf(v2 * inv_bc2) + eps);
 }
 
+// block-diagonal stacking of CSR parts: part q's rows go to [row_off, row_off + n_rows), its columns are
+// shifted by col_off and its edges go to [nnz_off, nnz_off + nnz)
+__global__ __launch_bounds__(256) void concat_csr_kernel(const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colidx,
+                                                         const float* __restrict__ vals, int n_rows, int nnz, int row_off,
+                                                         int col_off, int nnz_off, int write_end, int32_t* __restrict__ o_rowptr,
+                                                         int32_t* __restrict__ o_colidx, float* __restrict__ o_vals) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n_rows) o_rowptr[row_off + i] = rowptr[i] + nnz_off;
+    if (i == 0 && write_end) o_rowptr[row_off + n_rows] = nnz_off + nnz;
+    for (int e = i; e < nnz; e += gridDim.x * 256) {
+        o_colidx[nnz_off + e] = colidx[e] + col_off;
+        o_vals[nnz_off + e] = vals[e];
+    }
+}
+
+// up to kGatherParts row blocks, each contiguous on its own, copied behind one another (dwords)
+constexpr int kGatherParts = 32;
+struct GatherArgs {
+    const uint32_t* src[kGatherParts];
+    unsigned long long start[kGatherParts + 1];   // dword offset of part i in dst; start[n] = total
+    int n;
+};
+__global__ __launch_bounds__(256) void gather_parts_kernel(GatherArgs a, uint32_t* __restrict__ dst) {
+    const unsigned long long total = a.start[a.n];
+    for (unsigned long long i = (unsigned long long)blockIdx.x * 256 + threadIdx.x; i < total; i += (unsigned long long)gridDim.x * 256) {
+        int q = 0;
+        while (q + 1 < a.n && a.start[q + 1] <= i) ++q;
+        dst[i] = a.src[q][i - a.start[q]];
+    }
+}
+
 struct GraphState {
     dr_heteroconv* ctx;
     int64_t Nc, Nn;
@@ -149,7 +186,14 @@ struct GraphState {
 }  // namespace drc
 
 struct dr_hgnn {
-    int n_graphs, L, D;
+    int n_graphs, L, D;                        // n_graphs: states that are stepped (1 for a batched model)
+    int n_user;                                // sub-graphs the caller sees
+    bool batched;
+    std::vector<int64_t> off_c, off_n;         // [n_user + 1] first cell / net row of sub-graph q in the stacked graph
+    std::vector<const float*> ux_c, ux_n;      // [n_user] caller's inputs of the last step (for inspection)
+    dr_heteroconv* big;                        // batched: context of the stacked graph (owned)
+    dr_csr big_rel[3];                         // batched: its relations (arrays in `owned`)
+    float *Xc_all, *Xn_all, *tg_all;           // batched: staging for inputs the caller does not hold contiguously
     int64_t PL;                                // layer parameters: L*5*D*D
     int64_t n_cells_total;
     std::vector<drc::GraphState> g;
@@ -179,6 +223,7 @@ void model_release(dr_hgnn* m) {
         if (gs.done) (void)hipEventDestroy(gs.done);
     }
     if (m->fork) (void)hipEventDestroy(m->fork);
+    if (m->big) (void)heteroconv_destroy(m->big);
     delete m;
 }
 
@@ -211,7 +256,7 @@ int64_t hgnn_num_params(int32_t n_layers, int32_t D) {
     return (int64_t)n_layers * 5 * D * D + D;
 }
 
-int hgnn_create(dr_hgnn** model, int32_t n_graphs, dr_heteroconv* const* graphs, int32_t n_layers) {
+static int create_model(dr_hgnn** model, int32_t n_graphs, dr_heteroconv* const* graphs, int32_t n_layers, bool batched) {
     DRC_REQUIRE(model != nullptr, "hgnn_create: null model");
     *model = nullptr;
     DRC_REQUIRE(n_graphs >= 1 && n_graphs <= 1024, "hgnn_create: n_graphs = %d out of range [1, 1024]", n_graphs);
@@ -220,33 +265,83 @@ int hgnn_create(dr_hgnn** model, int32_t n_graphs, dr_heteroconv* const* graphs,
     for (int q = 0; q < n_graphs; ++q) DRC_REQUIRE(graphs[q] != nullptr, "hgnn_create: graph %d is null", q);
     for (int q = 0; q < n_graphs; ++q)
         for (int r = 0; r < q; ++r)
-            DRC_REQUIRE(graphs[q] != graphs[r], "hgnn_create: graphs %d and %d share one context (its scratch is per step)", r, q);
+            DRC_REQUIRE(batched || graphs[q] != graphs[r], "hgnn_create: graphs %d and %d share one context (its scratch is per step)", r, q);
     const HeteroDims d0 = heteroconv_dims(graphs[0]);
     for (int q = 1; q < n_graphs; ++q) {   // the parameters are shared, so the width is; each sub-graph keeps its own K
         const HeteroDims d = heteroconv_dims(graphs[q]);
         DRC_REQUIRE(d.D == d0.D, "hgnn_create: graph %d has D = %d, graph 0 has %d", q, d.D, d0.D);
+        DRC_REQUIRE(!batched || (d.k_near == d0.k_near && d.k_pins == d0.k_pins && d.k_self == d0.k_self && d.k_pinned == d0.k_pinned),
+                    "hgnn_create_batched: graph %d has other K than graph 0 (one launch serves the whole batch)", q);
     }
     dr_hgnn* m = new (std::nothrow) dr_hgnn();
     if (!m) return fail(DR_ERR_HIP, "hgnn_create: out of host memory");
-    m->n_graphs = n_graphs; m->L = n_layers; m->D = d0.D;
+    m->n_user = n_graphs; m->batched = batched;
+    m->n_graphs = batched ? 1 : n_graphs; m->L = n_layers; m->D = d0.D;
     m->PL = (int64_t)n_layers * 5 * d0.D * d0.D;
     m->n_cells_total = 0;
     m->gall = m->loss_part = m->dwh_part = nullptr;
+    m->Xc_all = m->Xn_all = m->tg_all = nullptr;
+    m->big = nullptr;
     m->fork = nullptr;
-    m->g.resize(n_graphs);
+    m->g.resize(m->n_graphs);
+    m->off_c.assign(n_graphs + 1, 0); m->off_n.assign(n_graphs + 1, 0);
+    m->ux_c.assign(n_graphs, nullptr); m->ux_n.assign(n_graphs, nullptr);
     for (auto& gs : m->g) { gs.stream = nullptr; gs.done = nullptr; gs.X_cell = gs.X_net = nullptr; }
+    for (int q = 0; q < n_graphs; ++q) {
+        const HeteroDims d = heteroconv_dims(graphs[q]);
+        m->off_c[q + 1] = m->off_c[q] + d.Nc;
+        m->off_n[q + 1] = m->off_n[q] + d.Nn;
+    }
     int rc = DR_OK;
     auto body = [&]() -> int {
         DRC_HIP(hipGetDevice(&m->device));
         DRC_HIP(hipEventCreateWithFlags(&m->fork, hipEventDisableTiming));
-        DRC_TRY(alloc_t(m, &m->gall, (size_t)n_graphs * m->PL));
-        DRC_TRY(alloc_t(m, &m->loss_part, (size_t)n_graphs * kHeadBlocks));
-        DRC_TRY(alloc_t(m, &m->dwh_part, (size_t)n_graphs * kHeadBlocks * m->D));
         const int L = n_layers, D = m->D;
-        for (int q = 0; q < n_graphs; ++q) {
+        std::vector<dr_heteroconv*> ctxs(graphs, graphs + n_graphs);
+        if (batched) {
+            // ---- stack the sub-graphs' relations into one block-diagonal graph and build its context ----
+            const int64_t Nc = m->off_c[n_graphs], Nn = m->off_n[n_graphs];
+            for (int r = 0; r < 3; ++r) {
+                int64_t nnz = 0;
+                for (int q = 0; q < n_graphs; ++q) nnz += heteroconv_relations(graphs[q])[r].nnz;
+                DRC_REQUIRE(nnz < (int64_t(1) << 31), "hgnn_create_batched: the stacked graph has 2^31 or more edges in a relation");
+                const int64_t rows = (r == 1) ? Nn : Nc, cols = (r == 2) ? Nn : Nc;
+                int32_t *rp = nullptr, *ci = nullptr;
+                float* v = nullptr;
+                DRC_TRY(alloc_t(m, &rp, (size_t)rows + 1));
+                DRC_TRY(alloc_t(m, &ci, (size_t)nnz));
+                DRC_TRY(alloc_t(m, &v, (size_t)nnz));
+                int64_t e0 = 0;
+                for (int q = 0; q < n_graphs; ++q) {
+                    const dr_csr& A = heteroconv_relations(graphs[q])[r];
+                    const int64_t row_off = (r == 1) ? m->off_n[q] : m->off_c[q], col_off = (r == 2) ? m->off_n[q] : m->off_c[q];
+                    const int64_t work = A.n_rows > A.nnz ? A.n_rows : A.nnz;
+                    unsigned blocks = (unsigned)((work + 255) / 256);
+                    blocks = blocks < 1 ? 1 : (blocks > 4096 ? 4096 : blocks);
+                    if ((int64_t)blocks * 256 < A.n_rows) blocks = (unsigned)((A.n_rows + 255) / 256);   // one thread per row pointer
+                    hipLaunchKernelGGL(concat_csr_kernel, dim3(blocks), dim3(256), 0, nullptr, A.rowptr, A.colidx, A.vals, (int)A.n_rows,
+                                       (int)A.nnz, (int)row_off, (int)col_off, (int)e0, q == n_graphs - 1 ? 1 : 0, rp, ci, v);
+                    e0 += A.nnz;
+                }
+                DRC_HIP(hipGetLastError());
+                m->big_rel[r] = dr_csr{rows, cols, nnz, rp, ci, v};
+            }
+            DRC_HIP(hipDeviceSynchronize());
+            DRC_TRY(heteroconv_create_widths(&m->big, &m->big_rel[0], &m->big_rel[1], &m->big_rel[2], D, d0.k_near, d0.k_pins,
+                                             d0.k_self, d0.k_pinned));
+            ctxs.assign(1, m->big);
+            DRC_TRY(alloc_t(m, &m->Xc_all, (size_t)Nc * D));
+            DRC_TRY(alloc_t(m, &m->Xn_all, (size_t)Nn * D));
+            DRC_TRY(alloc_t(m, &m->tg_all, (size_t)Nc));
+        }
+        const int ns = m->n_graphs;
+        DRC_TRY(alloc_t(m, &m->gall, (size_t)ns * m->PL));
+        DRC_TRY(alloc_t(m, &m->loss_part, (size_t)ns * kHeadBlocks));
+        DRC_TRY(alloc_t(m, &m->dwh_part, (size_t)ns * kHeadBlocks * m->D));
+        for (int q = 0; q < ns; ++q) {
             GraphState& gs = m->g[q];
-            const HeteroDims d = heteroconv_dims(graphs[q]);
-            gs.ctx = graphs[q]; gs.Nc = d.Nc; gs.Nn = d.Nn;
+            const HeteroDims d = heteroconv_dims(ctxs[q]);
+            gs.ctx = ctxs[q]; gs.Nc = d.Nc; gs.Nn = d.Nn;
             DRC_REQUIRE(d.Nc >= 1 && d.Nc < (1ll << 31) / D, "hgnn_create: graph %d has %lld cells", q, (long long)d.Nc);
             m->n_cells_total += d.Nc;
             DRC_HIP(hipStreamCreateWithFlags(&gs.stream, hipStreamNonBlocking));
@@ -298,6 +393,40 @@ int hgnn_create(dr_hgnn** model, int32_t n_graphs, dr_heteroconv* const* graphs,
     return DR_OK;
 }
 
+// Copies the caller's per-sub-graph blocks behind one another into `dst` unless they already lie that way in
+// memory; returns the pointer the step should read.
+static int stacked_input(const float* const* parts, int n, const std::vector<int64_t>& off, int width, float* dst,
+                         hipStream_t s, const float** out) {
+    bool contiguous = true;
+    for (int q = 1; q < n && contiguous; ++q) contiguous = parts[q] == parts[0] + (size_t)off[q] * width;
+    if (contiguous) { *out = parts[0]; return DR_OK; }
+    for (int q0 = 0; q0 < n; q0 += kGatherParts) {
+        GatherArgs a;
+        a.n = n - q0 < kGatherParts ? n - q0 : kGatherParts;
+        for (int i = 0; i < a.n; ++i) {
+            a.src[i] = reinterpret_cast<const uint32_t*>(parts[q0 + i]);
+            a.start[i] = (unsigned long long)(off[q0 + i] - off[q0]) * width;
+        }
+        a.start[a.n] = (unsigned long long)(off[q0 + a.n] - off[q0]) * width;
+        for (int i = a.n; i < kGatherParts; ++i) { a.src[i] = nullptr; a.start[i + 1] = a.start[a.n]; }
+        unsigned long long blocks = (a.start[a.n] + 255) / 256;
+        blocks = blocks < 1 ? 1 : (blocks > 8192 ? 8192 : blocks);
+        hipLaunchKernelGGL(gather_parts_kernel, dim3((unsigned)blocks), dim3(256), 0, s, a,
+                           reinterpret_cast<uint32_t*>(dst + (size_t)off[q0] * width));
+    }
+    DRC_HIP(hipGetLastError());
+    *out = dst;
+    return DR_OK;
+}
+
+int hgnn_create(dr_hgnn** model, int32_t n_graphs, dr_heteroconv* const* graphs, int32_t n_layers) {
+    return create_model(model, n_graphs, graphs, n_layers, false);
+}
+
+int hgnn_create_batched(dr_hgnn** model, int32_t n_graphs, dr_heteroconv* const* graphs, int32_t n_layers) {
+    return create_model(model, n_graphs, graphs, n_layers, true);
+}
+
 int hgnn_train_step(dr_hgnn* m, const float* const* X_cell, const float* const* X_net, const float* const* target,
                     float* theta, float* adam_m, float* adam_v, double lr, double beta1, double beta2, double eps,
                     double weight_decay, int32_t step, float* grad_out, float* loss_out, void* stream) {
@@ -308,9 +437,17 @@ int hgnn_train_step(dr_hgnn* m, const float* const* X_cell, const float* const* 
     DRC_REQUIRE(step >= 1, "hgnn_train_step: step = %d (the first update is step 1)", step);
     DRC_REQUIRE(beta1 >= 0.0 && beta1 < 1.0 && beta2 >= 0.0 && beta2 < 1.0 && eps > 0.0,
                 "hgnn_train_step: Adam constants out of range");
-    for (int q = 0; q < m->n_graphs; ++q)
+    for (int q = 0; q < m->n_user; ++q)
         DRC_REQUIRE(X_cell[q] && X_net[q] && target[q], "hgnn_train_step: null tensor for graph %d", q);
     hipStream_t user = as_stream(stream);
+    for (int q = 0; q < m->n_user; ++q) { m->ux_c[q] = X_cell[q]; m->ux_n[q] = X_net[q]; }
+    const float *one_c = nullptr, *one_n = nullptr, *one_t = nullptr;      // batched: the stacked inputs
+    if (m->batched) {
+        DRC_TRY(stacked_input(X_cell, m->n_user, m->off_c, m->D, m->Xc_all, user, &one_c));
+        DRC_TRY(stacked_input(X_net, m->n_user, m->off_n, m->D, m->Xn_all, user, &one_n));
+        DRC_TRY(stacked_input(target, m->n_user, m->off_c, 1, m->tg_all, user, &one_t));
+        X_cell = &one_c; X_net = &one_n; target = &one_t;
+    }
     const int L = m->L, D = m->D;
     const float scale = (float)(2.0 / (double)m->n_cells_total);
 
@@ -395,21 +532,33 @@ int hgnn_train_step(dr_hgnn* m, const float* const* X_cell, const float* const* 
 int hgnn_get_layer_buffers(const dr_hgnn* m, int32_t graph, int32_t layer, dr_hgnn_layer_buffers* out,
                            const float** pred, const float** dpred) {
     DRC_REQUIRE(m != nullptr && out != nullptr, "hgnn_get_layer_buffers: null argument");
-    DRC_REQUIRE(graph >= 0 && graph < m->n_graphs, "hgnn_get_layer_buffers: graph %d out of range", graph);
+    DRC_REQUIRE(graph >= 0 && graph < m->n_user, "hgnn_get_layer_buffers: graph %d out of range", graph);
     DRC_REQUIRE(layer >= 0 && layer < m->L, "hgnn_get_layer_buffers: layer %d out of range", layer);
-    const GraphState& gs = m->g[graph];
-    out->X_cell = layer == 0 ? gs.X_cell : gs.act_c[layer - 1];
-    out->X_net = layer == 0 ? gs.X_net : gs.act_n[layer - 1];
-    out->Y_cell = gs.act_c[layer];
-    out->Y_net = gs.act_n[layer];
-    out->saved = gs.saved[layer];
-    out->dY_cell = gs.G_c[layer + 1];
-    out->dY_net = gs.G_n[layer + 1];
-    out->dX_cell = gs.G_c[layer];
-    out->dX_net = gs.G_n[layer];
-    out->dW = layer_wgrads(gs.gvec, layer, m->D);
-    if (pred) *pred = gs.pred;
-    if (dpred) *dpred = gs.dpred;
+    // a batched model holds one stacked state: sub-graph q's rows start at off_c[q] / off_n[q] in every buffer
+    const GraphState& gs = m->g[m->batched ? 0 : graph];
+    const size_t oc = m->batched ? (size_t)m->off_c[graph] : 0, on = m->batched ? (size_t)m->off_n[graph] : 0;
+    const size_t D = (size_t)m->D;
+    const HeteroDims d = heteroconv_dims(gs.ctx);
+    out->X_cell = layer == 0 ? m->ux_c[graph] : gs.act_c[layer - 1] + oc * D;
+    out->X_net = layer == 0 ? m->ux_n[graph] : gs.act_n[layer - 1] + on * D;
+    out->Y_cell = gs.act_c[layer] + oc * D;
+    out->Y_net = gs.act_n[layer] + on * D;
+    const dr_heteroconv_saved& S = gs.saved[layer];
+    dr_heteroconv_saved& o = out->saved;
+    o = dr_heteroconv_saved{};
+    o.vals_cell = S.vals_cell + oc * d.k_near;   o.idx_cell = S.idx_cell + oc * d.k_near;
+    o.vals_net = S.vals_net + on * d.k_pinned;   o.idx_net = S.idx_net + on * d.k_pinned;
+    o.H_near = S.H_near + oc * D; o.H_pins = S.H_pins + on * D; o.H_pinned = S.H_pinned + oc * D;
+    o.mask = S.mask + oc * D;
+    if (S.vals_cell_pins) { o.vals_cell_pins = S.vals_cell_pins + oc * d.k_pins; o.idx_cell_pins = S.idx_cell_pins + oc * d.k_pins; }
+    if (S.vals_net_self) { o.vals_net_self = S.vals_net_self + on * d.k_self; o.idx_net_self = S.idx_net_self + on * d.k_self; }
+    out->dY_cell = gs.G_c[layer + 1] + oc * D;
+    out->dY_net = gs.G_n[layer + 1] + on * D;
+    out->dX_cell = gs.G_c[layer] + oc * D;
+    out->dX_net = gs.G_n[layer] + on * D;
+    out->dW = layer_wgrads(gs.gvec, layer, m->D);       // batched: of the whole batch, whichever sub-graph is asked for
+    if (pred) *pred = gs.pred + oc;
+    if (dpred) *dpred = gs.dpred + oc;
     return DR_OK;
 }
 

@@ -49,7 +49,7 @@ def _wgrad_bounds(saved, Xs_c, Xs_n, dYc, dYn, mask):
                 pinned=np.abs(saved["H_pinned"]).T @ dZq)
 
 
-def _check_layer(model, rels, Ws, q, l, L, D, k, X0=None):
+def _check_layer(model, rels, Ws, q, l, L, D, k, X0=None, check_dw=True):
     """Teacher-forced comparison of sub-graph q, layer l; returns the buffers (numpy) of that layer."""
     b = {kk: (vv.cpu().numpy() if torch.is_tensor(vv) else {n: t.cpu().numpy() for n, t in vv.items()})
          for kk, vv in model.hgnn_get_layer_buffers(q, l).items()}
@@ -90,7 +90,7 @@ def _check_layer(model, rels, Ws, q, l, L, D, k, X0=None):
                            b["dY_cell"].astype(np.float64), b["dY_net"].astype(np.float64), saved["mask"])
     for i, n in enumerate(P.WEIGHT_NAMES):
         err = np.abs(b["dW"][n].astype(np.float64) - ob["dW"][n])
-        assert np.all(err <= 1e-5 * bounds[n] + 1e-30), (q, l, n, err.max())
+        assert not check_dw or np.all(err <= 1e-5 * bounds[n] + 1e-30), (q, l, n, err.max())
     return b
 
 
@@ -326,6 +326,24 @@ def test_full_size_step_of_eight_subgraphs():
     torch.cuda.synchronize()
     say(f"hgnn full size: {(time.perf_counter() - t0) * 100:.3f} ms per training step, loss {float(loss.cpu()[0]):.5f}")
     model.hgnn_destroy()
+    # the same batch stacked into one graph by the library: same first step, one launch per kernel
+    batched = P.Hgnn(ctxs, L, batched=True)
+    th_b = dev(theta0)
+    m_b, v_b = torch.zeros_like(m), torch.zeros_like(v)
+    grad_b, loss_b = torch.empty_like(grad), torch.empty_like(loss)
+    batched.hgnn_train_step(dXc, dXn, dtg, th_b, m_b, v_b, LR, B1, B2, EPS, WD, 1, grad_b, loss_b)
+    torch.cuda.synchronize()
+    assert abs(float(loss_b.cpu()[0]) - sq / n_total) <= 1e-5 * sq / n_total
+    assert np.allclose(grad_b.cpu().numpy(), gg, rtol=1e-4, atol=1e-6 * np.abs(gg).max())
+    for _ in range(2):
+        batched.hgnn_train_step(dXc, dXn, dtg, th_b, m_b, v_b, LR, B1, B2, EPS, WD, 2, grad_b, loss_b)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(10):
+        batched.hgnn_train_step(dXc, dXn, dtg, th_b, m_b, v_b, LR, B1, B2, EPS, WD, 3 + i, grad_b, loss_b)
+    torch.cuda.synchronize()
+    say(f"hgnn full size, batched: {(time.perf_counter() - t0) * 100:.3f} ms per training step (inputs gathered each step)")
+    batched.hgnn_destroy()
     for c in ctxs:
         c.heteroconv_destroy()
 
@@ -373,6 +391,80 @@ def test_block_diagonal_batch_equals_separate_subgraphs():
     assert np.array_equal(idx_a, idx_b)                      # last layer's selections: bit-identical inputs reached it
     assert abs(loss_a - loss_b) <= 1e-6 * abs(loss_a)
     assert np.allclose(grad_a, grad_b, rtol=1e-4, atol=1e-6 * np.abs(grad_a).max())
+
+
+@pytest.mark.parametrize("contiguous", [False, True], ids=["scattered_inputs", "contiguous_inputs"])
+def test_batched_model_stacks_the_subgraphs_on_the_device(contiguous):
+    """hgnn_create_batched: the library stacks the batch into one block-diagonal graph itself.  Its step is checked
+    (a) bit for bit against a one-graph model built from the host-side block-diagonal graph, (b) layer by layer
+    against the oracle through the per-sub-graph views of the stacked buffers, (c) against the streamed model."""
+    from circuit_synth import block_diagonal
+    D, k, L, n_graphs = 128, 32, 2, 3
+    rng = np.random.default_rng(6)
+    gs = [make_graph("small", seed=50 + q, Nc=1700 + 130 * q, Nn=1000 + 70 * q, grid=(50, 40)) for q in range(n_graphs)]
+    say(f"hgnn batched: {n_graphs} sub-graphs, contiguous inputs: {contiguous}")
+    Xc = [rng.standard_normal((g.Nc, D)).astype(np.float32) for g in gs]
+    Xn = [rng.standard_normal((g.Nn, D)).astype(np.float32) for g in gs]
+    tg = [rng.standard_normal(g.Nc).astype(np.float32) for g in gs]
+    n_par = P.hgnn_num_params(L, D)
+    bound = np.sqrt(6.0 / (2 * D))
+    theta0 = rng.uniform(-bound, bound, n_par).astype(np.float32)
+
+    def contexts(graph_list):
+        keep = [(P.device_relation(g.near, P.DR_NORM_MEAN), P.device_relation(g.pins, P.DR_NORM_MEAN),
+                 P.device_relation(g.pinned, P.DR_NORM_SYM)) for g in graph_list]
+        return keep, [P.HeteroConv(d[0], d[1], d[2], D, k, k) for d in keep]
+
+    def tensors():
+        if not contiguous:
+            return [dev(a) for a in Xc], [dev(a) for a in Xn], [dev(a) for a in tg], None
+        allc, alln, allt = dev(np.concatenate(Xc)), dev(np.concatenate(Xn)), dev(np.concatenate(tg))
+        oc = np.cumsum([0] + [g.Nc for g in gs])
+        on = np.cumsum([0] + [g.Nn for g in gs])
+        return ([allc[oc[q]:oc[q + 1]] for q in range(n_graphs)], [alln[on[q]:on[q + 1]] for q in range(n_graphs)],
+                [allt[oc[q]:oc[q + 1]] for q in range(n_graphs)], (allc, alln, allt))
+
+    def run(model, xs):
+        th = dev(theta0)
+        m = torch.zeros(n_par, dtype=torch.float32, device="cuda")
+        v = torch.zeros(n_par, dtype=torch.float32, device="cuda")
+        gr = torch.full((n_par,), float("nan"), dtype=torch.float32, device="cuda")
+        ls = torch.full((1,), float("nan"), dtype=torch.float32, device="cuda")
+        model.hgnn_train_step(xs[0], xs[1], xs[2], th, m, v, LR, B1, B2, EPS, WD, 1, gr, ls)
+        torch.cuda.synchronize()
+        return float(ls.cpu()[0]), gr.cpu().numpy(), th.cpu().numpy()
+
+    keep, ctxs = contexts(gs)
+    xs = tensors()
+    batched = P.Hgnn(ctxs, L, batched=True)
+    loss_b, grad_b, theta_b = run(batched, xs)
+    # (a) the host-side block-diagonal graph as one sub-graph: identical launches, identical bits
+    keep1, ctx1 = contexts([block_diagonal(gs)])
+    one = P.Hgnn(ctx1, L)
+    x1 = ([dev(np.concatenate(Xc))], [dev(np.concatenate(Xn))], [dev(np.concatenate(tg))])
+    loss_1, grad_1, theta_1 = run(one, x1)
+    assert loss_b == loss_1 and np.array_equal(grad_b, grad_1) and np.array_equal(theta_b, theta_1)
+    # (b) per-sub-graph views of the stacked buffers against the oracle, teacher-forced
+    rels = [(oracle.relation(g.near, oracle.NORM_MEAN), oracle.relation(g.pins, oracle.NORM_MEAN),
+             oracle.relation(g.pinned, oracle.NORM_SYM)) for g in gs]
+    Ws, w_head = ohgnn.unpack(theta0.astype(np.float64), L, D)
+    for q, l in ((0, 0), (1, 1), (2, 0), (2, 1)):
+        b = _check_layer(batched, rels, Ws, q, l, L, D, k, X0=(Xc[q], Xn[q]), check_dw=False)
+    r = b["pred"].astype(np.float64) - tg[2]
+    assert np.allclose(b["dpred"], 2.0 * r / sum(g.Nc for g in gs), rtol=2e-6, atol=0)
+    # (c) the streamed model of the same contexts: same step up to the order of the sums over rows
+    streamed = P.Hgnn(ctxs, L)
+    loss_s, grad_s, theta_s = run(streamed, xs)
+    assert abs(loss_b - loss_s) <= 1e-6 * abs(loss_s)
+    assert np.allclose(grad_b, grad_s, rtol=1e-4, atol=1e-6 * np.abs(grad_s).max())
+    # contexts with different K cannot share one launch
+    other = P.HeteroConv(*keep[0], D, 16, 16)
+    with pytest.raises(P.DrError):
+        P.Hgnn([ctxs[0], other], L, batched=True)
+    for mdl in (batched, one, streamed):
+        mdl.hgnn_destroy()
+    for c in ctxs + ctx1 + [other]:
+        c.heteroconv_destroy()
 
 
 def test_rejects_bad_arguments():
