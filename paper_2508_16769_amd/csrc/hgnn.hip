@@ -26,7 +26,11 @@
 
 namespace drc {
 
-constexpr int kHeadBlocks = 64;   // workgroups (partials) per sub-graph in the read-out kernels
+// workgroups (= partial sums) of the read-out kernels for a state of n cells: about 256 rows each, at least 64
+inline int head_blocks(int64_t n) {
+    int64_t b = (n + 255) / 256;
+    return (int)(b < 64 ? 64 : (b > 2048 ? 2048 : b));
+}
 constexpr int kMaxWorkers = 8;    // host threads that enqueue sub-graphs side by side
 
 __global__ __launch_bounds__(256) void relu_inplace(float4* __restrict__ y, size_t n4) {
@@ -116,7 +120,7 @@ __global__ __launch_bounds__(64) void loss_reduce_kernel(const float* __restrict
 // g = sum over sub-graphs (fixed order) of the gradient pieces; Adam with L2 weight decay, bias-corrected
 __global__ __launch_bounds__(256) void adam_kernel(float* __restrict__ theta, float* __restrict__ m, float* __restrict__ v,
                                                    float* __restrict__ grad_out, const float* __restrict__ gall,
-                                                   const float* __restrict__ dwh_part, int n_graphs, int64_t PL, int D,
+                                                   const float* __restrict__ dwh_part, int n_graphs, int n_head_parts, int64_t PL, int D,
                                                    float lr, float beta1, float beta2, float omb1, float omb2,
                                                    float eps, float wd, float inv_bc1, float inv_bc2) {
     const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -126,7 +130,7 @@ __global__ __launch_bounds__(256) void adam_kernel(float* __restrict__ theta, fl
         for (int q = 0; q < n_graphs; ++q) g += gall[(size_t)q * PL + e];
     } else {
         const int c = (int)(e - PL);
-        for (int q = 0; q < n_graphs * kHeadBlocks; ++q) g += dwh_part[(size_t)q * D + c];
+        for (int q = 0; q < n_head_parts; ++q) g += dwh_part[(size_t)q * D + c];
     }
     grad_out[e] = g;
     const float th = theta[e];
@@ -178,6 +182,7 @@ struct GraphState {
     float* gvec;                               // this sub-graph's layer-weight gradients, theta layout (slice of gall)
     float *pred, *dpred;
     float *loss_part, *dwh_part;               // slices of the model's partial arrays
+    int hb;                                    // workgroups of the read-out kernels = partials in those slices
     hipStream_t stream;
     hipEvent_t done;
     const float *X_cell, *X_net;               // caller's inputs of the last step (for inspection)
@@ -199,6 +204,7 @@ struct dr_hgnn {
     std::vector<drc::GraphState> g;
     std::vector<void*> owned;
     float *gall, *loss_part, *dwh_part;
+    int n_head_parts;                          // read-out partials of all states together
     hipEvent_t fork;
     int device;
 };
@@ -336,8 +342,11 @@ static int create_model(dr_hgnn** model, int32_t n_graphs, dr_heteroconv* const*
         }
         const int ns = m->n_graphs;
         DRC_TRY(alloc_t(m, &m->gall, (size_t)ns * m->PL));
-        DRC_TRY(alloc_t(m, &m->loss_part, (size_t)ns * kHeadBlocks));
-        DRC_TRY(alloc_t(m, &m->dwh_part, (size_t)ns * kHeadBlocks * m->D));
+        m->n_head_parts = 0;
+        for (int q = 0; q < ns; ++q) m->n_head_parts += head_blocks(heteroconv_dims(ctxs[q]).Nc);
+        DRC_TRY(alloc_t(m, &m->loss_part, (size_t)m->n_head_parts));
+        DRC_TRY(alloc_t(m, &m->dwh_part, (size_t)m->n_head_parts * m->D));
+        int part0 = 0;
         for (int q = 0; q < ns; ++q) {
             GraphState& gs = m->g[q];
             const HeteroDims d = heteroconv_dims(ctxs[q]);
@@ -347,8 +356,10 @@ static int create_model(dr_hgnn** model, int32_t n_graphs, dr_heteroconv* const*
             DRC_HIP(hipStreamCreateWithFlags(&gs.stream, hipStreamNonBlocking));
             DRC_HIP(hipEventCreateWithFlags(&gs.done, hipEventDisableTiming));
             gs.gvec = m->gall + (size_t)q * m->PL;
-            gs.loss_part = m->loss_part + (size_t)q * kHeadBlocks;
-            gs.dwh_part = m->dwh_part + (size_t)q * kHeadBlocks * D;
+            gs.hb = head_blocks(d.Nc);
+            gs.loss_part = m->loss_part + (size_t)part0;
+            gs.dwh_part = m->dwh_part + (size_t)part0 * D;
+            part0 += gs.hb;
             gs.act_c.assign(L, nullptr); gs.act_n.assign(L, nullptr);
             gs.G_c.assign(L + 1, nullptr); gs.G_n.assign(L + 1, nullptr);
             gs.saved.assign(L, dr_heteroconv_saved{});
@@ -474,9 +485,9 @@ int hgnn_train_step(dr_hgnn* m, const float* const* X_cell, const float* const* 
         }
         // ---- read-out, loss, gradient of the last layer's output ----
         const float* w_head = theta + m->PL;
-        hipLaunchKernelGGL(head_fwd_kernel, dim3(kHeadBlocks), dim3(256), 0, s, gs.act_c[L - 1], w_head, target[q], n, D,
+        hipLaunchKernelGGL(head_fwd_kernel, dim3(gs.hb), dim3(256), 0, s, gs.act_c[L - 1], w_head, target[q], n, D,
                            scale, gs.pred, gs.dpred, gs.loss_part);
-        hipLaunchKernelGGL(head_bwd_kernel, dim3(kHeadBlocks), dim3(256), 256 * sizeof(float), s, gs.act_c[L - 1], w_head,
+        hipLaunchKernelGGL(head_bwd_kernel, dim3(gs.hb), dim3(256), 256 * sizeof(float), s, gs.act_c[L - 1], w_head,
                            gs.dpred, n, D, gs.G_c[L], gs.dwh_part);
         DRC_TRY(launch_fill_u32(reinterpret_cast<uint32_t*>(gs.G_n[L]), (size_t)gs.Nn * D, 0u, s));   // nets feed no loss
         DRC_HIP(hipGetLastError());
@@ -517,13 +528,13 @@ int hgnn_train_step(dr_hgnn* m, const float* const* X_cell, const float* const* 
     for (int q = 0; q < m->n_graphs; ++q) DRC_HIP(hipStreamWaitEvent(user, m->g[q].done, 0));
 
     // ---- loss and parameter update, after every sub-graph has delivered its gradient ----
-    hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(kWave), 0, user, m->loss_part, m->n_graphs * kHeadBlocks,
+    hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(kWave), 0, user, m->loss_part, m->n_head_parts,
                        (float)(1.0 / (double)m->n_cells_total), loss_out);
     const int64_t P = m->PL + D;
     const float inv_bc1 = (float)(1.0 / (1.0 - std::pow(beta1, (double)step)));
     const float inv_bc2 = (float)(1.0 / (1.0 - std::pow(beta2, (double)step)));
     hipLaunchKernelGGL(adam_kernel, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, user, theta, adam_m, adam_v, grad_out,
-                       m->gall, m->dwh_part, m->n_graphs, m->PL, D, (float)lr, (float)beta1, (float)beta2, (float)(1.0 - beta1),
+                       m->gall, m->dwh_part, m->n_graphs, m->n_head_parts, m->PL, D, (float)lr, (float)beta1, (float)beta2, (float)(1.0 - beta1),
                        (float)(1.0 - beta2), (float)eps, (float)weight_decay, inv_bc1, inv_bc2);
     DRC_HIP(hipGetLastError());
     return DR_OK;
