@@ -107,8 +107,8 @@ def test_rank_order_prefixes_are_the_smaller_selections():
         assert np.array_equal(ik, i8[:, :k]) and np.array_equal(vk, v8[:, :k])
         assert np.array_equal(np.sort(ik, axis=1), oracle.topk(X, k)[1])
     assert np.all(np.diff(v8, axis=1) <= 0)                       # descending values
-    tie = np.where(v8[5] == 0.5)[0]                               # planted tie: columns ascending among equals
-    assert len(tie) == 4 and np.all(np.diff(i8[5, tie]) > 0)
+    tie = np.where(v8[5] == 0.5)[0]        # planted tie of columns 0..3: those that fit are the lowest, in column order
+    assert len(tie) >= 2 and list(i8[5, tie]) == list(range(len(tie)))
     # signed zeros compare equal: the lower column comes first
     z = np.where(np.isin(i8[7], (2, 9)))[0]
     if len(z) == 2:
