@@ -92,6 +92,37 @@ int dr_spmm_bwd(const dr_csr* At, const float* dH, const uint16_t* xs_idx,
                 int32_t D, int32_t k, float* dXs, int accumulate, void* stream);
 
 /*
+ * Degree-adaptive K (paper Section 3.2, Alg. 1 stage 2 "dynamic warp partitioning" and the text after Alg. 1):
+ * neighbour groups are classified by their size, and the larger a destination's neighbour group the fewer entries
+ * of each neighbour's embedding it receives (K1 > K2 > K3).  The paper prints no formula, boundaries or K values;
+ * this build takes them as arguments and defines, for a relation with CSR A (rows = destinations):
+ *     K(i) = k1 if deg(i) <= t1,  k2 if t1 < deg(i) <= t2,  k3 otherwise          (deg = stored entries of row i of A)
+ *     H[i,:] = sum over edges (i <- j):  A.vals[e] * f_{K(i)}(X_j)                 (f_K: the K largest entries of the row)
+ * and the backward as the derivative of that with the selections held fixed.  The row-sparse operand is stored in
+ * RANK order -- pair t of a row is its t-th largest value (ties: lower column first) -- so every f_K with K <= k1
+ * is a prefix of the k1 stored pairs.
+ */
+typedef struct dr_degree_classes {
+    int32_t t1, t2;        /* 0 <= t1 <= t2 */
+    int32_t k1, k2, k3;    /* min(D, 64) >= k1 >= k2 >= k3 >= 1 */
+} dr_degree_classes;
+
+/* D-ReLU in rank order: vals[n,k], idx[n,k] hold the k largest signed values of every row of X[n,D], largest first
+ * (same selection and tie rule as dr_topk; only the order of the pairs differs).  Requires 1 <= k <= D <= DR_MAX_D. */
+int dr_topk_ranked(const float* X, int64_t n, int32_t D, int32_t k, float* vals, uint16_t* idx, void* stream);
+
+/* Forward: H[M,D] fully overwritten.  (xr_vals, xr_idx): rank-ordered CBSR [N, cls->k1] of the source node type. */
+int dr_spmm_fwd_adaptive(const dr_csr* A, const float* xr_vals, const uint16_t* xr_idx, int32_t D,
+                         const dr_degree_classes* cls, float* H, void* stream);
+
+/* Backward: dXr[j,t] (=|+=) sum over edges e of row j of At with t < K(destination of e):
+ *     At.vals[e] * dH[At.colidx[e], xr_idx[j,t]],        dXr[N, cls->k1] in the rank order of xr_idx.
+ * At = CSR of A^T; A_rowptr = row pointers [M+1] of A itself (device), from which the degree class of every
+ * destination is read.  Requires M < 2^30. */
+int dr_spmm_bwd_adaptive(const dr_csr* At, const int32_t* A_rowptr, const float* dH, const uint16_t* xr_idx, int32_t D,
+                         const dr_degree_classes* cls, float* dXr, int accumulate, void* stream);
+
+/*
  * Setup: stable CSR transpose (Alg. 2 stage 1, "transpose A to CSC").  Row j of the result lists the
  * entries of column j of A in increasing original row and, for equal rows, original storage order.
  * Outputs t_rowptr[n_cols+1], t_colidx[nnz], t_vals[nnz] (t_vals and A->vals may both be NULL for a

@@ -30,6 +30,7 @@ DR_OVERLAP_OFF = 2
 WEIGHT_NAMES = ("self_near", "neigh_near", "self_pins", "neigh_pins", "pinned")
 EXPORTS = (
     "dr_last_error", "dr_abi_version", "dr_topk", "dr_spmm_fwd", "dr_spmm_bwd",
+    "dr_topk_ranked", "dr_spmm_fwd_adaptive", "dr_spmm_bwd_adaptive",
     "dr_csr_transpose_workspace_bytes", "dr_csr_transpose",
     "dr_csr_normalize_workspace_bytes", "dr_csr_normalize",
     "heteroconv_create", "heteroconv_create_per_relation", "heteroconv_get_k", "heteroconv_profile_k", "heteroconv_fwd", "heteroconv_bwd", "heteroconv_get_transpose", "heteroconv_destroy",
@@ -155,6 +156,31 @@ def dr_spmm_bwd(At: Csr, dH: torch.Tensor, xs_idx: torch.Tensor, D: int, k: int,
     a = At.c()
     _check(load().dr_spmm_bwd(ctypes.byref(a), _ptr(dH), _ptr(xs_idx), ctypes.c_int32(D), ctypes.c_int32(k),
                               _ptr(dXs), ctypes.c_int(1 if accumulate else 0), _stream(stream)))
+
+
+class dr_degree_classes(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("t1", "t2", "k1", "k2", "k3")]
+
+
+def dr_topk_ranked(X: torch.Tensor, k: int, vals: torch.Tensor, idx: torch.Tensor, stream=None) -> None:
+    n, D = X.shape
+    _check(load().dr_topk_ranked(_ptr(X), ctypes.c_int64(n), ctypes.c_int32(D), ctypes.c_int32(k), _ptr(vals), _ptr(idx),
+                                 _stream(stream)))
+
+
+def dr_spmm_fwd_adaptive(A: Csr, xr_vals: torch.Tensor, xr_idx: torch.Tensor, D: int, classes: Sequence[int],
+                         H: torch.Tensor, stream=None) -> None:
+    """classes = (t1, t2, k1, k2, k3)."""
+    a, c = A.c(), dr_degree_classes(*[int(v) for v in classes])
+    _check(load().dr_spmm_fwd_adaptive(ctypes.byref(a), _ptr(xr_vals), _ptr(xr_idx), ctypes.c_int32(D), ctypes.byref(c),
+                                       _ptr(H), _stream(stream)))
+
+
+def dr_spmm_bwd_adaptive(At: Csr, A_rowptr: torch.Tensor, dH: torch.Tensor, xr_idx: torch.Tensor, D: int,
+                         classes: Sequence[int], dXr: torch.Tensor, accumulate: bool = False, stream=None) -> None:
+    a, c = At.c(), dr_degree_classes(*[int(v) for v in classes])
+    _check(load().dr_spmm_bwd_adaptive(ctypes.byref(a), _ptr(A_rowptr), _ptr(dH), _ptr(xr_idx), ctypes.c_int32(D),
+                                       ctypes.byref(c), _ptr(dXr), ctypes.c_int(1 if accumulate else 0), _stream(stream)))
 
 
 def dr_csr_transpose_workspace_bytes(n_rows: int, n_cols: int, nnz: int) -> int:

@@ -92,6 +92,52 @@ int dr_spmm_bwd(const dr_csr* At, const float* dH, const uint16_t* xs_idx, int32
     return launch_spmm_bwd(At, dH, xs_idx, D, k, dXs, accumulate, as_stream(stream));
 }
 
+static int check_classes(const dr_degree_classes* c, int32_t D, const char* fn) {
+    DRC_REQUIRE(c != nullptr, "%s: null degree classes", fn);
+    DRC_REQUIRE(c->t1 >= 0 && c->t1 <= c->t2, "%s: class boundaries must satisfy 0 <= t1 <= t2 (got %d, %d)", fn, c->t1, c->t2);
+    DRC_REQUIRE(c->k3 >= 1 && c->k2 >= c->k3 && c->k1 >= c->k2, "%s: widths must satisfy k1 >= k2 >= k3 >= 1 (got %d, %d, %d)", fn,
+                c->k1, c->k2, c->k3);
+    if (int rc = check_dk(D, c->k1, fn)) return rc;
+    if (c->k1 > 64) return fail(DR_ERR_UNSUPPORTED, "%s: k1 = %d exceeds 64", fn, c->k1);
+    return DR_OK;
+}
+
+int dr_topk_ranked(const float* X, int64_t n, int32_t D, int32_t k, float* vals, uint16_t* idx, void* stream) {
+    if (int rc = check_dk(D, k, "dr_topk_ranked")) return rc;
+    DRC_REQUIRE(n >= 0 && n < (int64_t(1) << 31), "dr_topk_ranked: n out of range");
+    if (n == 0) return DR_OK;
+    DRC_REQUIRE(X && vals && idx, "dr_topk_ranked: null pointer");
+    DRC_REQUIRE(aligned(X, 4) && aligned(vals, 4) && aligned(idx, 2), "dr_topk_ranked: misaligned pointer");
+    DRC_REQUIRE(n * (int64_t)D < (int64_t(1) << 33) && n * (int64_t)k < (int64_t(1) << 31), "dr_topk_ranked: n*D or n*k too large");
+    return launch_topk_ranked(X, n, D, k, vals, idx, as_stream(stream));
+}
+
+int dr_spmm_fwd_adaptive(const dr_csr* A, const float* xr_vals, const uint16_t* xr_idx, int32_t D,
+                         const dr_degree_classes* cls, float* H, void* stream) {
+    if (int rc = check_csr(A, "dr_spmm_fwd_adaptive: A", true)) return rc;
+    if (int rc = check_classes(cls, D, "dr_spmm_fwd_adaptive")) return rc;
+    if (A->n_rows == 0) return DR_OK;
+    DRC_REQUIRE(H != nullptr, "dr_spmm_fwd_adaptive: null H");
+    DRC_REQUIRE(A->nnz == 0 || (xr_vals && xr_idx), "dr_spmm_fwd_adaptive: null CBSR operand");
+    DRC_REQUIRE(aligned(H, 4) && aligned(xr_vals, 4) && aligned(xr_idx, 2), "dr_spmm_fwd_adaptive: misaligned pointer");
+    DRC_REQUIRE(A->n_cols * (int64_t)cls->k1 < (int64_t(1) << 31), "dr_spmm_fwd_adaptive: N*k1 >= 2^31");
+    return launch_spmm_fwd_adaptive(A, xr_vals, xr_idx, D, cls, H, as_stream(stream));
+}
+
+int dr_spmm_bwd_adaptive(const dr_csr* At, const int32_t* A_rowptr, const float* dH, const uint16_t* xr_idx, int32_t D,
+                         const dr_degree_classes* cls, float* dXr, int accumulate, void* stream) {
+    if (int rc = check_csr(At, "dr_spmm_bwd_adaptive: At", true)) return rc;
+    if (int rc = check_classes(cls, D, "dr_spmm_bwd_adaptive")) return rc;
+    if (At->n_rows == 0) return DR_OK;
+    DRC_REQUIRE(dXr != nullptr && xr_idx != nullptr, "dr_spmm_bwd_adaptive: null dXr or xr_idx");
+    DRC_REQUIRE(At->nnz == 0 || (dH != nullptr && A_rowptr != nullptr), "dr_spmm_bwd_adaptive: null dH or A_rowptr");
+    DRC_REQUIRE(aligned(dH, 4) && aligned(dXr, 4) && aligned(xr_idx, 2) && aligned(A_rowptr, 4),
+                "dr_spmm_bwd_adaptive: misaligned pointer");
+    DRC_REQUIRE(At->n_cols < (int64_t(1) << 30), "dr_spmm_bwd_adaptive: 2^30 or more destinations");
+    DRC_REQUIRE(At->n_cols * (int64_t)D < (int64_t(1) << 32), "dr_spmm_bwd_adaptive: M*D >= 2^32");
+    return launch_spmm_bwd_adaptive(At, A_rowptr, dH, xr_idx, D, cls, dXr, accumulate, as_stream(stream));
+}
+
 static size_t align256(size_t b) { return (b + 255) & ~size_t(255); }
 
 size_t dr_csr_transpose_workspace_bytes(int64_t n_rows, int64_t n_cols, int64_t nnz) {

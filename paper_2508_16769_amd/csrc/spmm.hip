@@ -123,8 +123,18 @@ __device__ __forceinline__ int pass_end(const WavePlan& p, int sa) {
 
 // Stages the records of solo slots [sa, sb) into sRec, laid out in slot order.  Every lane issues its
 // loads (at most kStageIters, all independent) before the first one is consumed.
+// With `deg_rowptr` (adaptive-K backward) the degree class of the edge's other end point, looked up in that row
+// pointer array, travels in the two top bits of the staged column (columns stay below 2^30 there).
+constexpr unsigned kColMask = 0x3fffffffu;
+__device__ __forceinline__ int tag_class(int col, const int32_t* __restrict__ deg_rowptr, int t1, int t2) {
+    if (!deg_rowptr) return col;
+    const int deg = deg_rowptr[col + 1] - deg_rowptr[col];
+    return col | ((deg <= t1 ? 0 : (deg <= t2 ? 1 : 2)) << 30);
+}
+
 __device__ __forceinline__ void stage_solo(const WavePlan& p, const int32_t* __restrict__ colidx,
-                                           const float* __restrict__ avals, int sa, int sb) {
+                                           const float* __restrict__ avals, int sa, int sb,
+                                           const int32_t* __restrict__ deg_rowptr = nullptr, int t1 = 0, int t2 = 0) {
     const int lane = threadIdx.x;
     const int base = p.sStart[sa];
     const int total = p.sStart[sb] - base;
@@ -139,7 +149,8 @@ __device__ __forceinline__ void stage_solo(const WavePlan& p, const int32_t* __r
             if (p.sStart[mid] - base <= dd) lo = mid; else hi = mid;
         }
         const int e = p.sRp[p.sOrder[lo]] + dd - (p.sStart[lo] - base);
-        r[j] = make_int2(__builtin_nontemporal_load(colidx + e), __float_as_int(__builtin_nontemporal_load(avals + e)));
+        r[j] = make_int2(tag_class(__builtin_nontemporal_load(colidx + e), deg_rowptr, t1, t2),
+                         __float_as_int(__builtin_nontemporal_load(avals + e)));
     }
 #pragma unroll
     for (int j = 0; j < kStageIters; ++j) {
@@ -150,14 +161,16 @@ __device__ __forceinline__ void stage_solo(const WavePlan& p, const int32_t* __r
 
 // Stages records [c0, c0 + n) of one long row (n <= kCap, n >= 1).
 __device__ __forceinline__ void stage_chunk(const WavePlan& p, const int32_t* __restrict__ colidx,
-                                            const float* __restrict__ avals, int c0, int n) {
+                                            const float* __restrict__ avals, int c0, int n,
+                                            const int32_t* __restrict__ deg_rowptr = nullptr, int t1 = 0, int t2 = 0) {
     const int lane = threadIdx.x;
     int2 r[kStageIters];
 #pragma unroll
     for (int j = 0; j < kStageIters; ++j) {
         const int d = lane + kWave * j;
         const int e = c0 + ((d < n) ? d : 0);
-        r[j] = make_int2(__builtin_nontemporal_load(colidx + e), __float_as_int(__builtin_nontemporal_load(avals + e)));
+        r[j] = make_int2(tag_class(__builtin_nontemporal_load(colidx + e), deg_rowptr, t1, t2),
+                         __float_as_int(__builtin_nontemporal_load(avals + e)));
     }
 #pragma unroll
     for (int j = 0; j < kStageIters; ++j) {
@@ -284,17 +297,28 @@ template <int KPL, int EPI> struct FwdBatch {   // EPI consecutive stream record
     unsigned meta[EPI];
 };
 
-template <int KPL, int EPI, bool STRIDED>
+// Degree classes of the adaptive-K variant (paper Section 3.2, Alg. 1 stage 2): a destination row with at most t1
+// edges receives the k1 largest entries of each neighbour, one with at most t2 edges the k2 largest, the others k3.
+struct DegreeK {
+    int t1, t2, k2, k3;
+    __device__ __forceinline__ int width(int deg, int k1) const { return deg <= t1 ? k1 : (deg <= t2 ? k2 : k3); }
+    __device__ __forceinline__ int cls(int deg) const { return deg <= t1 ? 0 : (deg <= t2 ? 1 : 2); }
+    __device__ __forceinline__ int width_of_class(int c, int k1) const { return c == 0 ? k1 : (c == 1 ? k2 : k3); }
+};
+
+template <int KPL, int EPI, bool STRIDED, bool ADAPT>
 __device__ __forceinline__ void fwd_issue(FwdBatch<KPL, EPI>& b, Stream& st, const WavePlan& plan,
                                           const float* __restrict__ xs_vals, const uint16_t* __restrict__ xs_idx,
-                                          int D, int k, int t, int g, int sa, int npass, int base) {
+                                          int D, int k, int t, int g, int sa, int npass, int base, const DegreeK& dk) {
 #pragma unroll
     for (int q = 0; q < EPI; ++q) {
         const bool valid = !st.done;
         const int2 rec = plan.sRec[valid ? st.cur : 0];
         const uint32_t col = valid ? (uint32_t)rec.x : 0u;   // exhausted lanes gather source row 0
         b.a[q] = __int_as_float(rec.y);
-        b.p[q].load(xs_vals, xs_idx, col * (uint32_t)k, t, k, D);
+        int kk = k;                                          // pairs of the gathered row this destination takes
+        if constexpr (ADAPT) kk = dk.width(plan.sRp[st.row + 1] - plan.sRp[st.row], k);   // a prefix of the rank order
+        b.p[q].load(xs_vals, xs_idx, col * (uint32_t)k, t, kk, D);
         b.meta[q] = valid ? st.template advance<STRIDED>(plan, sa, npass, base) : 0u;
     }
 }
@@ -311,18 +335,19 @@ __device__ __forceinline__ void fwd_consume(const FwdBatch<KPL, EPI>& b, float* 
     }
 }
 
-template <int KPL, int EPI, bool STRIDED>
+template <int KPL, int EPI, bool STRIDED, bool ADAPT>
 __device__ __forceinline__ void fwd_run(Stream& st, const WavePlan& plan, const float* __restrict__ xs_vals,
                                         const uint16_t* __restrict__ xs_idx, float* buf, float* __restrict__ Hblk,
-                                        int D, int k, int t, int g, int sa, int npass, int base, int vec_store) {
+                                        int D, int k, int t, int g, int sa, int npass, int base, int vec_store,
+                                        const DegreeK& dk) {
     if constexpr (KPL != 0) {
         FwdBatch<KPL, EPI> A, B;
-        fwd_issue<KPL, EPI, STRIDED>(A, st, plan, xs_vals, xs_idx, D, k, t, g, sa, npass, base);
+        fwd_issue<KPL, EPI, STRIDED, ADAPT>(A, st, plan, xs_vals, xs_idx, D, k, t, g, sa, npass, base, dk);
         for (;;) {
-            fwd_issue<KPL, EPI, STRIDED>(B, st, plan, xs_vals, xs_idx, D, k, t, g, sa, npass, base);
+            fwd_issue<KPL, EPI, STRIDED, ADAPT>(B, st, plan, xs_vals, xs_idx, D, k, t, g, sa, npass, base, dk);
             fwd_consume(A, buf, Hblk, D, t, vec_store);
             if (!__any(B.meta[0] & kValid)) break;
-            fwd_issue<KPL, EPI, STRIDED>(A, st, plan, xs_vals, xs_idx, D, k, t, g, sa, npass, base);
+            fwd_issue<KPL, EPI, STRIDED, ADAPT>(A, st, plan, xs_vals, xs_idx, D, k, t, g, sa, npass, base, dk);
             fwd_consume(B, buf, Hblk, D, t, vec_store);
             if (!__any(A.meta[0] & kValid)) break;
         }
@@ -344,11 +369,12 @@ __device__ __forceinline__ void fwd_run(Stream& st, const WavePlan& plan, const 
     }
 }
 
-template <int KPL, int EPI>
+template <int KPL, int EPI, bool ADAPT>
 __global__ __launch_bounds__(kWave) void spmm_fwd_kernel(
     const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colidx, const float* __restrict__ avals,
     const float* __restrict__ xs_vals, const uint16_t* __restrict__ xs_idx, float* __restrict__ H,
-    int M, int D, int k, int n_tiles, int per_xcd, int vec_store) {
+    int M, int D, int k, int n_tiles, int per_xcd, int vec_store, DegreeK dk) {
+    static_assert(!ADAPT || KPL < 0, "the adaptive-K forward uses the masked strided-pair path");
     extern __shared__ float4 smem4[];
     float* rowbuf = reinterpret_cast<float*>(smem4);                 // [kNG][D], 16-byte aligned
     const int tile_id = xcd_contiguous_tile(blockIdx.x, per_xcd);
@@ -380,7 +406,7 @@ __global__ __launch_bounds__(kWave) void spmm_fwd_kernel(
             stage_chunk(plan, colidx, avals, c0, n);
             lds_fence();
             Stream st{g, n, row, g >= n ? 1 : 0};
-            fwd_run<KPL, EPI, true>(st, plan, xs_vals, xs_idx, buf, Hblk, D, k, t, g, 0, 0, 0, vec_store);
+            fwd_run<KPL, EPI, true, ADAPT>(st, plan, xs_vals, xs_idx, buf, Hblk, D, k, t, g, 0, 0, 0, vec_store, dk);
         }
         lds_fence();
         float* out = Hblk + (size_t)row * D;
@@ -405,8 +431,8 @@ __global__ __launch_bounds__(kWave) void spmm_fwd_kernel(
         lds_fence();
         Stream st{0, 0, 0, 0};
         st.take_slot(plan, g, sa, sb - sa, plan.sStart[sa]);     // first 8 rows of the pass: one per group
-        fwd_run<KPL, EPI, false>(st, plan, xs_vals, xs_idx, buf, Hblk, D, k, t, g, sa, sb - sa, plan.sStart[sa],
-                                 vec_store);
+        fwd_run<KPL, EPI, false, ADAPT>(st, plan, xs_vals, xs_idx, buf, Hblk, D, k, t, g, sa, sb - sa, plan.sStart[sa],
+                                        vec_store, dk);
         sa = sb;
     }
 }
@@ -428,9 +454,9 @@ int launch_spmm_fwd(const dr_csr* A, const float* xs_vals, const uint16_t* xs_id
     if (kpl == 0 && k <= 4 * kLPE) kpl = -((k + kLPE - 1) / kLPE);   // strided scalar pairs, masked past k
     const size_t lds = sizeof(float) * (size_t)kNG * (D + kBufPad) + sizeof(int) * (size_t)plan_ints();
     dim3 grid((unsigned)(per_xcd * kNumXcd)), block(kWave);
-#define DRC_LAUNCH_FWD(V, E)                                                                                       \
-    hipLaunchKernelGGL((spmm_fwd_kernel<V, E>), grid, block, lds, s, A->rowptr, A->colidx, A->vals, xs_vals, xs_idx, \
-                       H, M, D, k, n_tiles, per_xcd, vec_store)
+#define DRC_LAUNCH_FWD(V, E)                                                                                              \
+    hipLaunchKernelGGL((spmm_fwd_kernel<V, E, false>), grid, block, lds, s, A->rowptr, A->colidx, A->vals, xs_vals, xs_idx, \
+                       H, M, D, k, n_tiles, per_xcd, vec_store, DegreeK{})
     switch (kpl) {
         case 1: DRC_LAUNCH_FWD(1, 4); break;
         case 2: DRC_LAUNCH_FWD(2, 3); break;
@@ -444,6 +470,31 @@ int launch_spmm_fwd(const dr_csr* A, const float* xs_vals, const uint16_t* xs_id
         default: DRC_LAUNCH_FWD(0, 1); break;
     }
 #undef DRC_LAUNCH_FWD
+    DRC_HIP(hipGetLastError());
+    return DR_OK;
+}
+
+int launch_spmm_fwd_adaptive(const dr_csr* A, const float* xr_vals, const uint16_t* xr_idx, int D, const dr_degree_classes* c,
+                             float* H, hipStream_t s) {
+    const int M = (int)A->n_rows, k = c->k1;
+    if (A->nnz == 0) return launch_fill_u32(reinterpret_cast<uint32_t*>(H), (size_t)M * D, 0u, s);
+    const int n_tiles = (M + kRW - 1) / kRW;
+    const int per_xcd = (n_tiles + kNumXcd - 1) / kNumXcd;
+    const int vec_store = (D % 4 == 0 && aligned(H, 16)) ? 1 : 0;
+    const size_t lds = sizeof(float) * (size_t)kNG * (D + kBufPad) + sizeof(int) * (size_t)plan_ints();
+    const DegreeK dk{c->t1, c->t2, c->k2, c->k3};
+    dim3 grid((unsigned)(per_xcd * kNumXcd)), block(kWave);
+#define DRC_LAUNCH_FWD_A(V, E)                                                                                            \
+    hipLaunchKernelGGL((spmm_fwd_kernel<V, E, true>), grid, block, lds, s, A->rowptr, A->colidx, A->vals, xr_vals, xr_idx, \
+                       H, M, D, k, n_tiles, per_xcd, vec_store, dk)
+    switch ((k + kLPE - 1) / kLPE) {           // strided pairs per lane at the largest width
+        case 1: DRC_LAUNCH_FWD_A(-1, 4); break;
+        case 2: DRC_LAUNCH_FWD_A(-2, 3); break;
+        case 3: DRC_LAUNCH_FWD_A(-3, 2); break;
+        case 4: DRC_LAUNCH_FWD_A(-4, 2); break;
+        default: DRC_LAUNCH_FWD_A(-8, 1); break;   // k1 <= 64 (checked by the caller)
+    }
+#undef DRC_LAUNCH_FWD_A
     DRC_HIP(hipGetLastError());
     return DR_OK;
 }
@@ -466,36 +517,55 @@ __device__ __forceinline__ void load_ci(int (&ci)[KPL], const uint16_t* sIdx, in
     for (int u = 0; u < KPL; ++u) ci[u] = sIdx[row * (kLPE * KPL) + t + kLPE * u];
 }
 
-template <int KPL, int EPI, bool STRIDED>
+constexpr unsigned kClassShift = 16;   // adaptive-K backward: degree class of the record's destination in meta bits 16-17
+
+template <int KPL, int EPI, bool STRIDED, bool ADAPT>
 __device__ __forceinline__ void bwd_issue(BwdBatch<KPL, EPI>& b, Stream& st, int (&ci)[KPL], const WavePlan& plan,
-                                          const uint16_t* sIdx, const float* __restrict__ dH, int D, int t, int g,
-                                          int sa, int npass, int base) {
+                                          const uint16_t* sIdx, const float* __restrict__ dH, int D, int k, int t, int g,
+                                          int sa, int npass, int base, const DegreeK& dk) {
 #pragma unroll
     for (int q = 0; q < EPI; ++q) {
         const bool valid = !st.done;
         const int2 rec = plan.sRec[valid ? st.cur : 0];
-        const uint32_t col = valid ? (uint32_t)rec.x : 0u;
+        uint32_t col = valid ? (uint32_t)rec.x : 0u;
+        unsigned cls = 0;
+        if constexpr (ADAPT) { cls = col >> 30; col &= kColMask; }
         b.a[q] = __int_as_float(rec.y);
         const float* rowp = dH + (size_t)col * (uint32_t)D;
+        if constexpr (ADAPT) {
+            // slots at or past the destination's width read the column of slot 0 instead (a word the group's first
+            // lane reads anyway): no load is conditional, and no further sector of the dH row is touched
+            const int kq = dk.width_of_class((int)cls, k);
+            const int c0 = sIdx[st.row * (kLPE * KPL)];
 #pragma unroll
-        for (int u = 0; u < KPL; ++u) b.v[q][u] = rowp[ci[u]];
+            for (int u = 0; u < KPL; ++u) b.v[q][u] = rowp[(t + kLPE * u < kq) ? ci[u] : c0];
+        } else {
+#pragma unroll
+            for (int u = 0; u < KPL; ++u) b.v[q][u] = rowp[ci[u]];
+        }
         unsigned m = 0;
         if (valid) {
-            m = st.template advance<STRIDED>(plan, sa, npass, base);
+            m = st.template advance<STRIDED>(plan, sa, npass, base) | (cls << kClassShift);
             if (!STRIDED && (m & kLast) && !st.done) load_ci<KPL>(ci, sIdx, st.row, t);
         }
         b.meta[q] = m;
     }
 }
 
-template <int KPL, int EPI>
+template <int KPL, int EPI, bool ADAPT>
 __device__ __forceinline__ void bwd_consume(const BwdBatch<KPL, EPI>& b, float (&acc)[KPL], float* __restrict__ Gblk,
-                                            int k, int s0, int t, int accumulate) {
+                                            int k, int s0, int t, int accumulate, const DegreeK& dk) {
 #pragma unroll
     for (int q = 0; q < EPI; ++q) {
         if (b.meta[q] & kValid) {
+            if constexpr (ADAPT) {
+                const int kq = dk.width_of_class((int)((b.meta[q] >> kClassShift) & 3u), k);
 #pragma unroll
-            for (int u = 0; u < KPL; ++u) acc[u] = fmaf(b.a[q], b.v[q][u], acc[u]);
+                for (int u = 0; u < KPL; ++u) acc[u] = fmaf(b.a[q], (t + kLPE * u < kq) ? b.v[q][u] : 0.f, acc[u]);
+            } else {
+#pragma unroll
+                for (int u = 0; u < KPL; ++u) acc[u] = fmaf(b.a[q], b.v[q][u], acc[u]);
+            }
             if (b.meta[q] & kLast) {
                 float* o = Gblk + (size_t)(b.meta[q] & kRowMask) * k;
 #pragma unroll
@@ -509,28 +579,28 @@ __device__ __forceinline__ void bwd_consume(const BwdBatch<KPL, EPI>& b, float (
     }
 }
 
-template <int KPL, int EPI, bool STRIDED>
+template <int KPL, int EPI, bool STRIDED, bool ADAPT>
 __device__ __forceinline__ void bwd_run(Stream& st, int (&ci)[KPL], float (&acc)[KPL], const WavePlan& plan,
                                         const uint16_t* sIdx, const float* __restrict__ dH, float* __restrict__ Gblk,
                                         int D, int k, int s0, int t, int g, int sa, int npass, int base,
-                                        int accumulate) {
+                                        int accumulate, const DegreeK& dk) {
     BwdBatch<KPL, EPI> A, B;
-    bwd_issue<KPL, EPI, STRIDED>(A, st, ci, plan, sIdx, dH, D, t, g, sa, npass, base);
+    bwd_issue<KPL, EPI, STRIDED, ADAPT>(A, st, ci, plan, sIdx, dH, D, k, t, g, sa, npass, base, dk);
     for (;;) {
-        bwd_issue<KPL, EPI, STRIDED>(B, st, ci, plan, sIdx, dH, D, t, g, sa, npass, base);
-        bwd_consume(A, acc, Gblk, k, s0, t, accumulate);
+        bwd_issue<KPL, EPI, STRIDED, ADAPT>(B, st, ci, plan, sIdx, dH, D, k, t, g, sa, npass, base, dk);
+        bwd_consume<KPL, EPI, ADAPT>(A, acc, Gblk, k, s0, t, accumulate, dk);
         if (!__any(B.meta[0] & kValid)) break;
-        bwd_issue<KPL, EPI, STRIDED>(A, st, ci, plan, sIdx, dH, D, t, g, sa, npass, base);
-        bwd_consume(B, acc, Gblk, k, s0, t, accumulate);
+        bwd_issue<KPL, EPI, STRIDED, ADAPT>(A, st, ci, plan, sIdx, dH, D, k, t, g, sa, npass, base, dk);
+        bwd_consume<KPL, EPI, ADAPT>(B, acc, Gblk, k, s0, t, accumulate, dk);
         if (!__any(A.meta[0] & kValid)) break;
     }
 }
 
-template <int KPL, int EPI>
+template <int KPL, int EPI, bool ADAPT>
 __global__ __launch_bounds__(kWave) void spmm_bwd_kernel(
     const int32_t* __restrict__ t_rowptr, const int32_t* __restrict__ t_colidx, const float* __restrict__ t_vals,
     const float* __restrict__ dH, const uint16_t* __restrict__ xs_idx, float* __restrict__ dXs,
-    int N, int D, int k, int n_tiles, int per_xcd, int accumulate) {
+    int N, int D, int k, int n_tiles, int per_xcd, int accumulate, const int32_t* __restrict__ deg_rowptr, DegreeK dk) {
     extern __shared__ float4 smem4[];
     constexpr int kWin = kLPE * KPL;                                       // compact slots per pass over the block
     float* part = reinterpret_cast<float*>(smem4);                         // [kNG][kWin] long-row partials
@@ -575,10 +645,10 @@ __global__ __launch_bounds__(kWave) void spmm_bwd_kernel(
             for (int c0 = e0; c0 < e1; c0 += kCap) {
                 const int n = min(kCap, e1 - c0);
                 lds_fence();
-                stage_chunk(plan, t_colidx, t_vals, c0, n);
+                stage_chunk(plan, t_colidx, t_vals, c0, n, ADAPT ? deg_rowptr : nullptr, dk.t1, dk.t2);
                 lds_fence();
                 Stream st{g, n, row, g >= n ? 1 : 0};
-                bwd_run<KPL, EPI, true>(st, ci, acc, plan, sIdx, dH, Gblk, D, k, s0, t, g, 0, 0, 0, accumulate);
+                bwd_run<KPL, EPI, true, ADAPT>(st, ci, acc, plan, sIdx, dH, Gblk, D, k, s0, t, g, 0, 0, 0, accumulate, dk);
             }
 #pragma unroll
             for (int u = 0; u < KPL; ++u) part[g * kWin + t + kLPE * u] = acc[u];
@@ -600,7 +670,7 @@ __global__ __launch_bounds__(kWave) void spmm_bwd_kernel(
             const int sb = pass_end(plan, sa);
             lds_fence();
             if (lane == 0) *plan.sNext = kNG;
-            stage_solo(plan, t_colidx, t_vals, sa, sb);
+            stage_solo(plan, t_colidx, t_vals, sa, sb, ADAPT ? deg_rowptr : nullptr, dk.t1, dk.t2);
             lds_fence();
             Stream st{0, 0, 0, 0};
             st.take_slot(plan, g, sa, sb - sa, plan.sStart[sa]);
@@ -609,15 +679,15 @@ __global__ __launch_bounds__(kWave) void spmm_bwd_kernel(
 #pragma unroll
             for (int u = 0; u < KPL; ++u) { ci[u] = 0; acc[u] = 0.f; }
             if (!st.done) load_ci<KPL>(ci, sIdx, st.row, t);
-            bwd_run<KPL, EPI, false>(st, ci, acc, plan, sIdx, dH, Gblk, D, k, s0, t, g, sa, sb - sa, plan.sStart[sa],
-                                     accumulate);
+            bwd_run<KPL, EPI, false, ADAPT>(st, ci, acc, plan, sIdx, dH, Gblk, D, k, s0, t, g, sa, sb - sa, plan.sStart[sa],
+                                            accumulate, dk);
             sa = sb;
         }
     }
 }
 
-int launch_spmm_bwd(const dr_csr* At, const float* dH, const uint16_t* xs_idx, int D, int k, float* dXs,
-                    int accumulate, hipStream_t s) {
+static int launch_bwd_any(const dr_csr* At, const float* dH, const uint16_t* xs_idx, int D, int k, float* dXs, int accumulate,
+                          const int32_t* deg_rowptr, DegreeK dk, hipStream_t s) {
     const int N = (int)At->n_rows;
     if (At->nnz == 0) {
         if (accumulate) return DR_OK;
@@ -632,18 +702,37 @@ int launch_spmm_bwd(const dr_csr* At, const float* dH, const uint16_t* xs_idx, i
     dim3 grid((unsigned)(per_xcd * kNumXcd)), block(kWave);
     const size_t lds = sizeof(float) * (size_t)kNG * (kLPE * kpl) + sizeof(uint16_t) * (size_t)kRW * (kLPE * kpl) +
                        sizeof(int) * (size_t)plan_ints();
-#define DRC_LAUNCH_BWD(V, E)                                                                                         \
-    hipLaunchKernelGGL((spmm_bwd_kernel<V, E>), grid, block, lds, s, At->rowptr, At->colidx, At->vals, dH, xs_idx, dXs, \
-                       N, D, k, n_tiles, per_xcd, accumulate ? 1 : 0)
-    switch (kpl) {
-        case 1: DRC_LAUNCH_BWD(1, 4); break;
-        case 2: DRC_LAUNCH_BWD(2, 4); break;
-        case 4: DRC_LAUNCH_BWD(4, 2); break;
-        default: DRC_LAUNCH_BWD(8, 1); break;
+#define DRC_LAUNCH_BWD(V, E, A)                                                                                            \
+    hipLaunchKernelGGL((spmm_bwd_kernel<V, E, A>), grid, block, lds, s, At->rowptr, At->colidx, At->vals, dH, xs_idx, dXs, \
+                       N, D, k, n_tiles, per_xcd, accumulate ? 1 : 0, deg_rowptr, dk)
+    if (deg_rowptr) {
+        switch (kpl) {
+            case 1: DRC_LAUNCH_BWD(1, 4, true); break;
+            case 2: DRC_LAUNCH_BWD(2, 4, true); break;
+            case 4: DRC_LAUNCH_BWD(4, 2, true); break;
+            default: DRC_LAUNCH_BWD(8, 1, true); break;   // k <= 64: one window of slots (checked by the caller)
+        }
+    } else {
+        switch (kpl) {
+            case 1: DRC_LAUNCH_BWD(1, 4, false); break;
+            case 2: DRC_LAUNCH_BWD(2, 4, false); break;
+            case 4: DRC_LAUNCH_BWD(4, 2, false); break;
+            default: DRC_LAUNCH_BWD(8, 1, false); break;
+        }
     }
 #undef DRC_LAUNCH_BWD
     DRC_HIP(hipGetLastError());
     return DR_OK;
+}
+
+int launch_spmm_bwd(const dr_csr* At, const float* dH, const uint16_t* xs_idx, int D, int k, float* dXs,
+                    int accumulate, hipStream_t s) {
+    return launch_bwd_any(At, dH, xs_idx, D, k, dXs, accumulate, nullptr, DegreeK{}, s);
+}
+
+int launch_spmm_bwd_adaptive(const dr_csr* At, const int32_t* a_rowptr, const float* dH, const uint16_t* xr_idx, int D,
+                             const dr_degree_classes* c, float* dXr, int accumulate, hipStream_t s) {
+    return launch_bwd_any(At, dH, xr_idx, D, c->k1, dXr, accumulate, a_rowptr, DegreeK{c->t1, c->t2, c->k2, c->k3}, s);
 }
 
 }  // namespace drc

@@ -8,6 +8,9 @@
 // them, and with an early exit once a probe isolates exactly k elements; compaction
 // positions come from mbcnt prefix counts of the keep-ballots, which yields ascending column order for
 // free.  A row that is needed at two widths (one K per edge type) is loaded once and selected twice.
+// The rank-ordered variant (largest value first; every smaller selection is a prefix, which degree-adaptive
+// K relies on) stages the kept keys of a row in LDS in column order and lets every kept element count the
+// keys that precede it: greater, or equal with a lower column.
 #include "dr_internal.h"
 
 namespace drc {
@@ -24,12 +27,14 @@ __device__ __forceinline__ int lanes_below(unsigned long long m) {
 
 constexpr int kRowsInFlight = 4;   // rows whose loads are outstanding per wavefront
 
-template <int EPL, bool DUAL>
+template <int EPL, bool DUAL, bool RANKED>
 __global__ __launch_bounds__(256) void topk_rows_kernel(const float* __restrict__ X, int n, int D, int k,
                                                         float* __restrict__ vals, uint16_t* __restrict__ idx, int k2,
                                                         float* __restrict__ vals2, uint16_t* __restrict__ idx2) {
+    extern __shared__ uint32_t kept_keys[];                   // RANKED: [4 wavefronts][k] keys of the current row
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
+    uint32_t* const my_keys = kept_keys + wave * k;
     const int stride = gridDim.x * (blockDim.x >> 6);        // rows between consecutive rows of one wavefront
     const int row0 = blockIdx.x * (blockDim.x >> 6) + wave;
 
@@ -82,6 +87,8 @@ __global__ __launch_bounds__(256) void topk_rows_kernel(const float* __restrict_
         const int need_eq = k - n_gt;                   // >= 1 ties to take, lowest columns first
         int kept_before = 0, eq_before = 0;
         const size_t base = (size_t)row * k;
+        bool keep_s[EPL];
+        int pos_s[EPL];
 #pragma unroll
         for (int s = 0; s < EPL; ++s) {
             bool gt = key[s] > T;
@@ -89,13 +96,41 @@ __global__ __launch_bounds__(256) void topk_rows_kernel(const float* __restrict_
             unsigned long long meq = __ballot(eq);
             bool keep = gt || (eq && (eq_before + lanes_below(meq)) < need_eq);
             unsigned long long mk = __ballot(keep);
-            if (keep) {
-                int pos = kept_before + lanes_below(mk);
-                vals[base + pos] = val[s];
-                idx[base + pos] = (uint16_t)(s * kWave + lane);
-            }
+            keep_s[s] = keep;
+            pos_s[s] = kept_before + lanes_below(mk);          // position in ascending column order
             kept_before += __popcll(mk);
             eq_before += __popcll(meq);
+        }
+        if constexpr (!RANKED) {
+#pragma unroll
+            for (int s = 0; s < EPL; ++s)
+                if (keep_s[s]) {
+                    vals[base + pos_s[s]] = val[s];
+                    idx[base + pos_s[s]] = (uint16_t)(s * kWave + lane);
+                }
+        } else {
+            // One wavefront executes its LDS accesses in program order, so the reads below see the keys written here
+            // and the next row's writes come after this row's reads; the fences keep the compiler from reordering.
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+#pragma unroll
+            for (int s = 0; s < EPL; ++s)
+                if (keep_s[s]) my_keys[pos_s[s]] = key[s];
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int s = 0; s < EPL; ++s) {
+                if (!keep_s[s]) continue;
+                const uint32_t mine = key[s];
+                const int p_me = pos_s[s];
+                int rank = 0;
+                for (int p = 0; p < k; ++p) {                  // every lane reads the same word: broadcast
+                    const uint32_t other = my_keys[p];
+                    rank += (other > mine || (other == mine && p < p_me)) ? 1 : 0;
+                }
+                vals[base + rank] = val[s];
+                idx[base + rank] = (uint16_t)(s * kWave + lane);
+            }
+            __builtin_amdgcn_wave_barrier();
         }
     };
 
@@ -116,32 +151,44 @@ __global__ __launch_bounds__(256) void topk_rows_kernel(const float* __restrict_
 
 template <int EPL>
 static void launch_epl(const float* X, int n, int D, int k, float* vals, uint16_t* idx, int k2, float* vals2,
-                       uint16_t* idx2, hipStream_t s) {
+                       uint16_t* idx2, bool ranked, hipStream_t s) {
     int waves_per_block = 4;
     long blocks = ((long)n + waves_per_block - 1) / waves_per_block;
     if (blocks > 4096) blocks = 4096;            // two full rounds of 8 waves/SIMD; each wavefront strides over rows
-    if (vals2)
-        hipLaunchKernelGGL((topk_rows_kernel<EPL, true>), dim3((unsigned)blocks), dim3(256), 0, s, X, n, D, k, vals, idx, k2,
-                           vals2, idx2);
+    if (ranked)
+        hipLaunchKernelGGL((topk_rows_kernel<EPL, false, true>), dim3((unsigned)blocks), dim3(256),
+                           sizeof(uint32_t) * 4 * (size_t)k, s, X, n, D, k, vals, idx, 0, nullptr, nullptr);
+    else if (vals2)
+        hipLaunchKernelGGL((topk_rows_kernel<EPL, true, false>), dim3((unsigned)blocks), dim3(256), 0, s, X, n, D, k, vals, idx,
+                           k2, vals2, idx2);
     else
-        hipLaunchKernelGGL((topk_rows_kernel<EPL, false>), dim3((unsigned)blocks), dim3(256), 0, s, X, n, D, k, vals, idx, 0,
-                           nullptr, nullptr);
+        hipLaunchKernelGGL((topk_rows_kernel<EPL, false, false>), dim3((unsigned)blocks), dim3(256), 0, s, X, n, D, k, vals,
+                           idx, 0, nullptr, nullptr);
 }
 
-int launch_topk2(const float* X, int64_t n, int D, int k, float* vals, uint16_t* idx, int k2, float* vals2, uint16_t* idx2,
-                 hipStream_t s) {
+static int launch_any(const float* X, int64_t n, int D, int k, float* vals, uint16_t* idx, int k2, float* vals2, uint16_t* idx2,
+                      bool ranked, hipStream_t s) {
     if (n == 0) return DR_OK;
-    if (D <= 64) launch_epl<1>(X, (int)n, D, k, vals, idx, k2, vals2, idx2, s);
-    else if (D <= 128) launch_epl<2>(X, (int)n, D, k, vals, idx, k2, vals2, idx2, s);
-    else if (D <= 256) launch_epl<4>(X, (int)n, D, k, vals, idx, k2, vals2, idx2, s);
-    else if (D <= 512) launch_epl<8>(X, (int)n, D, k, vals, idx, k2, vals2, idx2, s);
-    else launch_epl<16>(X, (int)n, D, k, vals, idx, k2, vals2, idx2, s);
+    if (D <= 64) launch_epl<1>(X, (int)n, D, k, vals, idx, k2, vals2, idx2, ranked, s);
+    else if (D <= 128) launch_epl<2>(X, (int)n, D, k, vals, idx, k2, vals2, idx2, ranked, s);
+    else if (D <= 256) launch_epl<4>(X, (int)n, D, k, vals, idx, k2, vals2, idx2, ranked, s);
+    else if (D <= 512) launch_epl<8>(X, (int)n, D, k, vals, idx, k2, vals2, idx2, ranked, s);
+    else launch_epl<16>(X, (int)n, D, k, vals, idx, k2, vals2, idx2, ranked, s);
     DRC_HIP(hipGetLastError());
     return DR_OK;
 }
 
+int launch_topk2(const float* X, int64_t n, int D, int k, float* vals, uint16_t* idx, int k2, float* vals2, uint16_t* idx2,
+                 hipStream_t s) {
+    return launch_any(X, n, D, k, vals, idx, k2, vals2, idx2, false, s);
+}
+
 int launch_topk(const float* X, int64_t n, int D, int k, float* vals, uint16_t* idx, hipStream_t s) {
-    return launch_topk2(X, n, D, k, vals, idx, 0, nullptr, nullptr, s);
+    return launch_any(X, n, D, k, vals, idx, 0, nullptr, nullptr, false, s);
+}
+
+int launch_topk_ranked(const float* X, int64_t n, int D, int k, float* vals, uint16_t* idx, hipStream_t s) {
+    return launch_any(X, n, D, k, vals, idx, 0, nullptr, nullptr, true, s);
 }
 
 }  // namespace drc
