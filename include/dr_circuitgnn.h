@@ -115,11 +115,17 @@ int dr_topk_ranked(const float* X, int64_t n, int32_t D, int32_t k, float* vals,
 int dr_spmm_fwd_adaptive(const dr_csr* A, const float* xr_vals, const uint16_t* xr_idx, int32_t D,
                          const dr_degree_classes* cls, float* H, void* stream);
 
-/* Backward: dXr[j,t] (=|+=) sum over edges e of row j of At with t < K(destination of e):
+/* Setup for the backward: the degree class (0 low, 1 medium, 2 high) of the destination of every stored entry of
+ * At = CSR of A^T, read from A's own row pointers A_rowptr[M+1] (device).  edge_class[At->nnz], one byte each.
+ * Only t1 and t2 of cls are used. */
+int dr_degree_edge_classes(const dr_csr* At, const int32_t* A_rowptr, const dr_degree_classes* cls, uint8_t* edge_class,
+                           void* stream);
+
+/* Backward: dXr[j,t] (=|+=) sum over edges e of row j of At with t < K(class of e):
  *     At.vals[e] * dH[At.colidx[e], xr_idx[j,t]],        dXr[N, cls->k1] in the rank order of xr_idx.
- * At = CSR of A^T; A_rowptr = row pointers [M+1] of A itself (device), from which the degree class of every
- * destination is read.  Requires M < 2^30. */
-int dr_spmm_bwd_adaptive(const dr_csr* At, const int32_t* A_rowptr, const float* dH, const uint16_t* xr_idx, int32_t D,
+ * edge_class: what dr_degree_edge_classes wrote for the same At and boundaries (values above 2 are not checked).
+ * Requires M < 2^30. */
+int dr_spmm_bwd_adaptive(const dr_csr* At, const uint8_t* edge_class, const float* dH, const uint16_t* xr_idx, int32_t D,
                          const dr_degree_classes* cls, float* dXr, int accumulate, void* stream);
 
 /*

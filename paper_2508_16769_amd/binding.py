@@ -30,7 +30,7 @@ DR_OVERLAP_OFF = 2
 WEIGHT_NAMES = ("self_near", "neigh_near", "self_pins", "neigh_pins", "pinned")
 EXPORTS = (
     "dr_last_error", "dr_abi_version", "dr_topk", "dr_spmm_fwd", "dr_spmm_bwd",
-    "dr_topk_ranked", "dr_spmm_fwd_adaptive", "dr_spmm_bwd_adaptive",
+    "dr_topk_ranked", "dr_spmm_fwd_adaptive", "dr_degree_edge_classes", "dr_spmm_bwd_adaptive",
     "dr_csr_transpose_workspace_bytes", "dr_csr_transpose",
     "dr_csr_normalize_workspace_bytes", "dr_csr_normalize",
     "heteroconv_create", "heteroconv_create_per_relation", "heteroconv_get_k", "heteroconv_profile_k", "heteroconv_fwd", "heteroconv_bwd", "heteroconv_get_transpose", "heteroconv_destroy",
@@ -176,10 +176,16 @@ def dr_spmm_fwd_adaptive(A: Csr, xr_vals: torch.Tensor, xr_idx: torch.Tensor, D:
                                        _ptr(H), _stream(stream)))
 
 
-def dr_spmm_bwd_adaptive(At: Csr, A_rowptr: torch.Tensor, dH: torch.Tensor, xr_idx: torch.Tensor, D: int,
+def dr_degree_edge_classes(At: Csr, A_rowptr: torch.Tensor, classes: Sequence[int], edge_class: torch.Tensor,
+                           stream=None) -> None:
+    a, c = At.c(), dr_degree_classes(*[int(v) for v in classes])
+    _check(load().dr_degree_edge_classes(ctypes.byref(a), _ptr(A_rowptr), ctypes.byref(c), _ptr(edge_class), _stream(stream)))
+
+
+def dr_spmm_bwd_adaptive(At: Csr, edge_class: torch.Tensor, dH: torch.Tensor, xr_idx: torch.Tensor, D: int,
                          classes: Sequence[int], dXr: torch.Tensor, accumulate: bool = False, stream=None) -> None:
     a, c = At.c(), dr_degree_classes(*[int(v) for v in classes])
-    _check(load().dr_spmm_bwd_adaptive(ctypes.byref(a), _ptr(A_rowptr), _ptr(dH), _ptr(xr_idx), ctypes.c_int32(D),
+    _check(load().dr_spmm_bwd_adaptive(ctypes.byref(a), _ptr(edge_class), _ptr(dH), _ptr(xr_idx), ctypes.c_int32(D),
                                        ctypes.byref(c), _ptr(dXr), ctypes.c_int(1 if accumulate else 0), _stream(stream)))
 
 

@@ -124,18 +124,26 @@ int dr_spmm_fwd_adaptive(const dr_csr* A, const float* xr_vals, const uint16_t* 
     return launch_spmm_fwd_adaptive(A, xr_vals, xr_idx, D, cls, H, as_stream(stream));
 }
 
-int dr_spmm_bwd_adaptive(const dr_csr* At, const int32_t* A_rowptr, const float* dH, const uint16_t* xr_idx, int32_t D,
+int dr_degree_edge_classes(const dr_csr* At, const int32_t* A_rowptr, const dr_degree_classes* cls, uint8_t* edge_class,
+                           void* stream) {
+    if (int rc = check_csr(At, "dr_degree_edge_classes: At", false)) return rc;
+    DRC_REQUIRE(cls != nullptr && cls->t1 >= 0 && cls->t1 <= cls->t2, "dr_degree_edge_classes: class boundaries must satisfy 0 <= t1 <= t2");
+    if (At->nnz == 0) return DR_OK;
+    DRC_REQUIRE(A_rowptr != nullptr && edge_class != nullptr, "dr_degree_edge_classes: null pointer");
+    return launch_edge_classes(At, A_rowptr, cls, edge_class, as_stream(stream));
+}
+
+int dr_spmm_bwd_adaptive(const dr_csr* At, const uint8_t* edge_class, const float* dH, const uint16_t* xr_idx, int32_t D,
                          const dr_degree_classes* cls, float* dXr, int accumulate, void* stream) {
     if (int rc = check_csr(At, "dr_spmm_bwd_adaptive: At", true)) return rc;
     if (int rc = check_classes(cls, D, "dr_spmm_bwd_adaptive")) return rc;
     if (At->n_rows == 0) return DR_OK;
     DRC_REQUIRE(dXr != nullptr && xr_idx != nullptr, "dr_spmm_bwd_adaptive: null dXr or xr_idx");
-    DRC_REQUIRE(At->nnz == 0 || (dH != nullptr && A_rowptr != nullptr), "dr_spmm_bwd_adaptive: null dH or A_rowptr");
-    DRC_REQUIRE(aligned(dH, 4) && aligned(dXr, 4) && aligned(xr_idx, 2) && aligned(A_rowptr, 4),
-                "dr_spmm_bwd_adaptive: misaligned pointer");
+    DRC_REQUIRE(At->nnz == 0 || (dH != nullptr && edge_class != nullptr), "dr_spmm_bwd_adaptive: null dH or edge_class");
+    DRC_REQUIRE(aligned(dH, 4) && aligned(dXr, 4) && aligned(xr_idx, 2), "dr_spmm_bwd_adaptive: misaligned pointer");
     DRC_REQUIRE(At->n_cols < (int64_t(1) << 30), "dr_spmm_bwd_adaptive: 2^30 or more destinations");
     DRC_REQUIRE(At->n_cols * (int64_t)D < (int64_t(1) << 32), "dr_spmm_bwd_adaptive: M*D >= 2^32");
-    return launch_spmm_bwd_adaptive(At, A_rowptr, dH, xr_idx, D, cls, dXr, accumulate, as_stream(stream));
+    return launch_spmm_bwd_adaptive(At, edge_class, dH, xr_idx, D, cls, dXr, accumulate, as_stream(stream));
 }
 
 static size_t align256(size_t b) { return (b + 255) & ~size_t(255); }

@@ -60,8 +60,9 @@ int launch_spmm_bwd(const dr_csr* At, const float* dH, const uint16_t* xs_idx, i
 int launch_topk_ranked(const float* X, int64_t n, int D, int k, float* vals, uint16_t* idx, hipStream_t s);
 int launch_spmm_fwd_adaptive(const dr_csr* A, const float* xr_vals, const uint16_t* xr_idx, int D, const dr_degree_classes* c,
                              float* H, hipStream_t s);
-int launch_spmm_bwd_adaptive(const dr_csr* At, const int32_t* a_rowptr, const float* dH, const uint16_t* xr_idx, int D,
+int launch_spmm_bwd_adaptive(const dr_csr* At, const uint8_t* edge_class, const float* dH, const uint16_t* xr_idx, int D,
                              const dr_degree_classes* c, float* dXr, int accumulate, hipStream_t s);
+int launch_edge_classes(const dr_csr* At, const int32_t* a_rowptr, const dr_degree_classes* c, uint8_t* out, hipStream_t s);
 int launch_csr_transpose(const dr_csr* A, int32_t* t_rowptr, int32_t* t_colidx, float* t_vals, void* ws,
                          hipStream_t s);
 int launch_csr_normalize(int mode, int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t* rowptr,

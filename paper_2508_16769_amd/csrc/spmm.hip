@@ -123,18 +123,16 @@ __device__ __forceinline__ int pass_end(const WavePlan& p, int sa) {
 
 // Stages the records of solo slots [sa, sb) into sRec, laid out in slot order.  Every lane issues its
 // loads (at most kStageIters, all independent) before the first one is consumed.
-// With `deg_rowptr` (adaptive-K backward) the degree class of the edge's other end point, looked up in that row
-// pointer array, travels in the two top bits of the staged column (columns stay below 2^30 there).
+// With `ecls` (adaptive-K backward) the degree class of the edge's other end point, one byte per stored entry,
+// travels in the two top bits of the staged column (columns stay below 2^30 there).
 constexpr unsigned kColMask = 0x3fffffffu;
-__device__ __forceinline__ int tag_class(int col, const int32_t* __restrict__ deg_rowptr, int t1, int t2) {
-    if (!deg_rowptr) return col;
-    const int deg = deg_rowptr[col + 1] - deg_rowptr[col];
-    return col | ((deg <= t1 ? 0 : (deg <= t2 ? 1 : 2)) << 30);
+__device__ __forceinline__ int tag_class(int col, const uint8_t* __restrict__ ecls, int e) {
+    return ecls ? (col | ((int)__builtin_nontemporal_load(ecls + e) << 30)) : col;
 }
 
 __device__ __forceinline__ void stage_solo(const WavePlan& p, const int32_t* __restrict__ colidx,
                                            const float* __restrict__ avals, int sa, int sb,
-                                           const int32_t* __restrict__ deg_rowptr = nullptr, int t1 = 0, int t2 = 0) {
+                                           const uint8_t* __restrict__ ecls = nullptr) {
     const int lane = threadIdx.x;
     const int base = p.sStart[sa];
     const int total = p.sStart[sb] - base;
@@ -149,7 +147,7 @@ __device__ __forceinline__ void stage_solo(const WavePlan& p, const int32_t* __r
             if (p.sStart[mid] - base <= dd) lo = mid; else hi = mid;
         }
         const int e = p.sRp[p.sOrder[lo]] + dd - (p.sStart[lo] - base);
-        r[j] = make_int2(tag_class(__builtin_nontemporal_load(colidx + e), deg_rowptr, t1, t2),
+        r[j] = make_int2(tag_class(__builtin_nontemporal_load(colidx + e), ecls, e),
                          __float_as_int(__builtin_nontemporal_load(avals + e)));
     }
 #pragma unroll
@@ -162,14 +160,14 @@ __device__ __forceinline__ void stage_solo(const WavePlan& p, const int32_t* __r
 // Stages records [c0, c0 + n) of one long row (n <= kCap, n >= 1).
 __device__ __forceinline__ void stage_chunk(const WavePlan& p, const int32_t* __restrict__ colidx,
                                             const float* __restrict__ avals, int c0, int n,
-                                            const int32_t* __restrict__ deg_rowptr = nullptr, int t1 = 0, int t2 = 0) {
+                                            const uint8_t* __restrict__ ecls = nullptr) {
     const int lane = threadIdx.x;
     int2 r[kStageIters];
 #pragma unroll
     for (int j = 0; j < kStageIters; ++j) {
         const int d = lane + kWave * j;
         const int e = c0 + ((d < n) ? d : 0);
-        r[j] = make_int2(tag_class(__builtin_nontemporal_load(colidx + e), deg_rowptr, t1, t2),
+        r[j] = make_int2(tag_class(__builtin_nontemporal_load(colidx + e), ecls, e),
                          __float_as_int(__builtin_nontemporal_load(avals + e)));
     }
 #pragma unroll
@@ -232,8 +230,20 @@ template <int KPL> struct Pairs {
     static constexpr int N = KPL > 0 ? KPL : -KPL;
     float v[N];
     uint16_t c[N];
+    // `k`: pairs of the row that count (the row's stored width, or a prefix of it in the adaptive-K kernels).
+    // PREFIX: with consecutive pairs per lane, send the pairs at or past k to the padding words as well.
+    template <bool PREFIX = false>
     __device__ __forceinline__ void load(const float* __restrict__ vals, const uint16_t* __restrict__ idx, uint32_t rowbase,
                                          int t, int k, int D) {
+        load_raw(vals, idx, rowbase, t, k, D);
+        if constexpr (PREFIX && KPL > 0) {
+#pragma unroll
+            for (int u = 0; u < KPL; ++u)
+                if (KPL * t + u >= k) c[u] = (uint16_t)(D + (t & (kBufPad - 1)));
+        }
+    }
+    __device__ __forceinline__ void load_raw(const float* __restrict__ vals, const uint16_t* __restrict__ idx, uint32_t rowbase,
+                                             int t, int k, int D) {
         if constexpr (KPL < 0) {
 #pragma unroll
             for (int u = 0; u < N; ++u) {
@@ -318,7 +328,7 @@ __device__ __forceinline__ void fwd_issue(FwdBatch<KPL, EPI>& b, Stream& st, con
         b.a[q] = __int_as_float(rec.y);
         int kk = k;                                          // pairs of the gathered row this destination takes
         if constexpr (ADAPT) kk = dk.width(plan.sRp[st.row + 1] - plan.sRp[st.row], k);   // a prefix of the rank order
-        b.p[q].load(xs_vals, xs_idx, col * (uint32_t)k, t, kk, D);
+        b.p[q].template load<ADAPT>(xs_vals, xs_idx, col * (uint32_t)k, t, kk, D);
         b.meta[q] = valid ? st.template advance<STRIDED>(plan, sa, npass, base) : 0u;
     }
 }
@@ -374,7 +384,7 @@ __global__ __launch_bounds__(kWave) void spmm_fwd_kernel(
     const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colidx, const float* __restrict__ avals,
     const float* __restrict__ xs_vals, const uint16_t* __restrict__ xs_idx, float* __restrict__ H,
     int M, int D, int k, int n_tiles, int per_xcd, int vec_store, DegreeK dk) {
-    static_assert(!ADAPT || KPL < 0, "the adaptive-K forward uses the masked strided-pair path");
+    static_assert(!ADAPT || KPL != 0, "the adaptive-K forward needs a path that can mask pairs");
     extern __shared__ float4 smem4[];
     float* rowbuf = reinterpret_cast<float*>(smem4);                 // [kNG][D], 16-byte aligned
     const int tile_id = xcd_contiguous_tile(blockIdx.x, per_xcd);
@@ -487,7 +497,15 @@ int launch_spmm_fwd_adaptive(const dr_csr* A, const float* xr_vals, const uint16
 #define DRC_LAUNCH_FWD_A(V, E)                                                                                            \
     hipLaunchKernelGGL((spmm_fwd_kernel<V, E, true>), grid, block, lds, s, A->rowptr, A->colidx, A->vals, xr_vals, xr_idx, \
                        H, M, D, k, n_tiles, per_xcd, vec_store, dk)
-    switch ((k + kLPE - 1) / kLPE) {           // strided pairs per lane at the largest width
+    // widths that fill the lanes evenly keep the vector loads of the uniform kernel (pairs past the destination's
+    // width are redirected after the load); the others take the strided scalar pairs
+    const bool vec = (k == 8) || (k == 16 && aligned(xr_vals, 8) && aligned(xr_idx, 4)) ||
+                     ((k == 32 || k == 64) && aligned(xr_vals, 16) && aligned(xr_idx, 8));
+    switch (vec ? k / kLPE + 100 : (k + kLPE - 1) / kLPE) {
+        case 101: DRC_LAUNCH_FWD_A(1, 4); break;
+        case 102: DRC_LAUNCH_FWD_A(2, 3); break;
+        case 104: DRC_LAUNCH_FWD_A(4, 2); break;
+        case 108: DRC_LAUNCH_FWD_A(8, 1); break;
         case 1: DRC_LAUNCH_FWD_A(-1, 4); break;
         case 2: DRC_LAUNCH_FWD_A(-2, 3); break;
         case 3: DRC_LAUNCH_FWD_A(-3, 2); break;
@@ -511,16 +529,19 @@ template <int KPL, int EPI> struct BwdBatch {
     unsigned meta[EPI];
 };
 
+// saved columns of the slots lane t owns; ci[KPL] (one extra word) = column of the row's slot 0, which the
+// adaptive-K kernel reads in place of the slots a destination does not take
 template <int KPL>
-__device__ __forceinline__ void load_ci(int (&ci)[KPL], const uint16_t* sIdx, int row, int t) {
+__device__ __forceinline__ void load_ci(int (&ci)[KPL + 1], const uint16_t* sIdx, int row, int t) {
 #pragma unroll
     for (int u = 0; u < KPL; ++u) ci[u] = sIdx[row * (kLPE * KPL) + t + kLPE * u];
+    ci[KPL] = sIdx[row * (kLPE * KPL)];
 }
 
 constexpr unsigned kClassShift = 16;   // adaptive-K backward: degree class of the record's destination in meta bits 16-17
 
 template <int KPL, int EPI, bool STRIDED, bool ADAPT>
-__device__ __forceinline__ void bwd_issue(BwdBatch<KPL, EPI>& b, Stream& st, int (&ci)[KPL], const WavePlan& plan,
+__device__ __forceinline__ void bwd_issue(BwdBatch<KPL, EPI>& b, Stream& st, int (&ci)[KPL + 1], const WavePlan& plan,
                                           const uint16_t* sIdx, const float* __restrict__ dH, int D, int k, int t, int g,
                                           int sa, int npass, int base, const DegreeK& dk) {
 #pragma unroll
@@ -536,9 +557,8 @@ __device__ __forceinline__ void bwd_issue(BwdBatch<KPL, EPI>& b, Stream& st, int
             // slots at or past the destination's width read the column of slot 0 instead (a word the group's first
             // lane reads anyway): no load is conditional, and no further sector of the dH row is touched
             const int kq = dk.width_of_class((int)cls, k);
-            const int c0 = sIdx[st.row * (kLPE * KPL)];
 #pragma unroll
-            for (int u = 0; u < KPL; ++u) b.v[q][u] = rowp[(t + kLPE * u < kq) ? ci[u] : c0];
+            for (int u = 0; u < KPL; ++u) b.v[q][u] = rowp[(t + kLPE * u < kq) ? ci[u] : ci[KPL]];
         } else {
 #pragma unroll
             for (int u = 0; u < KPL; ++u) b.v[q][u] = rowp[ci[u]];
@@ -580,7 +600,7 @@ __device__ __forceinline__ void bwd_consume(const BwdBatch<KPL, EPI>& b, float (
 }
 
 template <int KPL, int EPI, bool STRIDED, bool ADAPT>
-__device__ __forceinline__ void bwd_run(Stream& st, int (&ci)[KPL], float (&acc)[KPL], const WavePlan& plan,
+__device__ __forceinline__ void bwd_run(Stream& st, int (&ci)[KPL + 1], float (&acc)[KPL], const WavePlan& plan,
                                         const uint16_t* sIdx, const float* __restrict__ dH, float* __restrict__ Gblk,
                                         int D, int k, int s0, int t, int g, int sa, int npass, int base,
                                         int accumulate, const DegreeK& dk) {
@@ -600,7 +620,7 @@ template <int KPL, int EPI, bool ADAPT>
 __global__ __launch_bounds__(kWave) void spmm_bwd_kernel(
     const int32_t* __restrict__ t_rowptr, const int32_t* __restrict__ t_colidx, const float* __restrict__ t_vals,
     const float* __restrict__ dH, const uint16_t* __restrict__ xs_idx, float* __restrict__ dXs,
-    int N, int D, int k, int n_tiles, int per_xcd, int accumulate, const int32_t* __restrict__ deg_rowptr, DegreeK dk) {
+    int N, int D, int k, int n_tiles, int per_xcd, int accumulate, const uint8_t* __restrict__ ecls, DegreeK dk) {
     extern __shared__ float4 smem4[];
     constexpr int kWin = kLPE * KPL;                                       // compact slots per pass over the block
     float* part = reinterpret_cast<float*>(smem4);                         // [kNG][kWin] long-row partials
@@ -637,7 +657,7 @@ __global__ __launch_bounds__(kWave) void spmm_bwd_kernel(
         for (unsigned long long m = plan.coop_mask; m; m &= m - 1) {
             const int row = __ffsll((long long)m) - 1;
             const int e0 = plan.sRp[row], e1 = plan.sRp[row + 1];
-            int ci[KPL];
+            int ci[KPL + 1];
             float acc[KPL];
             load_ci<KPL>(ci, sIdx, row, t);
 #pragma unroll
@@ -645,7 +665,7 @@ __global__ __launch_bounds__(kWave) void spmm_bwd_kernel(
             for (int c0 = e0; c0 < e1; c0 += kCap) {
                 const int n = min(kCap, e1 - c0);
                 lds_fence();
-                stage_chunk(plan, t_colidx, t_vals, c0, n, ADAPT ? deg_rowptr : nullptr, dk.t1, dk.t2);
+                stage_chunk(plan, t_colidx, t_vals, c0, n, ADAPT ? ecls : nullptr);
                 lds_fence();
                 Stream st{g, n, row, g >= n ? 1 : 0};
                 bwd_run<KPL, EPI, true, ADAPT>(st, ci, acc, plan, sIdx, dH, Gblk, D, k, s0, t, g, 0, 0, 0, accumulate, dk);
@@ -670,12 +690,13 @@ __global__ __launch_bounds__(kWave) void spmm_bwd_kernel(
             const int sb = pass_end(plan, sa);
             lds_fence();
             if (lane == 0) *plan.sNext = kNG;
-            stage_solo(plan, t_colidx, t_vals, sa, sb, ADAPT ? deg_rowptr : nullptr, dk.t1, dk.t2);
+            stage_solo(plan, t_colidx, t_vals, sa, sb, ADAPT ? ecls : nullptr);
             lds_fence();
             Stream st{0, 0, 0, 0};
             st.take_slot(plan, g, sa, sb - sa, plan.sStart[sa]);
-            int ci[KPL];
+            int ci[KPL + 1];
             float acc[KPL];
+            ci[KPL] = 0;
 #pragma unroll
             for (int u = 0; u < KPL; ++u) { ci[u] = 0; acc[u] = 0.f; }
             if (!st.done) load_ci<KPL>(ci, sIdx, st.row, t);
@@ -687,7 +708,7 @@ __global__ __launch_bounds__(kWave) void spmm_bwd_kernel(
 }
 
 static int launch_bwd_any(const dr_csr* At, const float* dH, const uint16_t* xs_idx, int D, int k, float* dXs, int accumulate,
-                          const int32_t* deg_rowptr, DegreeK dk, hipStream_t s) {
+                          const uint8_t* ecls, DegreeK dk, hipStream_t s) {
     const int N = (int)At->n_rows;
     if (At->nnz == 0) {
         if (accumulate) return DR_OK;
@@ -704,8 +725,8 @@ static int launch_bwd_any(const dr_csr* At, const float* dH, const uint16_t* xs_
                        sizeof(int) * (size_t)plan_ints();
 #define DRC_LAUNCH_BWD(V, E, A)                                                                                            \
     hipLaunchKernelGGL((spmm_bwd_kernel<V, E, A>), grid, block, lds, s, At->rowptr, At->colidx, At->vals, dH, xs_idx, dXs, \
-                       N, D, k, n_tiles, per_xcd, accumulate ? 1 : 0, deg_rowptr, dk)
-    if (deg_rowptr) {
+                       N, D, k, n_tiles, per_xcd, accumulate ? 1 : 0, ecls, dk)
+    if (ecls) {
         switch (kpl) {
             case 1: DRC_LAUNCH_BWD(1, 4, true); break;
             case 2: DRC_LAUNCH_BWD(2, 4, true); break;
@@ -730,9 +751,29 @@ int launch_spmm_bwd(const dr_csr* At, const float* dH, const uint16_t* xs_idx, i
     return launch_bwd_any(At, dH, xs_idx, D, k, dXs, accumulate, nullptr, DegreeK{}, s);
 }
 
-int launch_spmm_bwd_adaptive(const dr_csr* At, const int32_t* a_rowptr, const float* dH, const uint16_t* xr_idx, int D,
+int launch_spmm_bwd_adaptive(const dr_csr* At, const uint8_t* edge_class, const float* dH, const uint16_t* xr_idx, int D,
                              const dr_degree_classes* c, float* dXr, int accumulate, hipStream_t s) {
-    return launch_bwd_any(At, dH, xr_idx, D, c->k1, dXr, accumulate, a_rowptr, DegreeK{c->t1, c->t2, c->k2, c->k3}, s);
+    return launch_bwd_any(At, dH, xr_idx, D, c->k1, dXr, accumulate, edge_class, DegreeK{c->t1, c->t2, c->k2, c->k3}, s);
+}
+
+// class (0 low, 1 medium, 2 high) of the destination of every stored entry of At, from the forward row pointers
+__global__ __launch_bounds__(256) void edge_class_kernel(const int32_t* __restrict__ t_colidx, int nnz,
+                                                         const int32_t* __restrict__ a_rowptr, int t1, int t2,
+                                                         uint8_t* __restrict__ out) {
+    for (int e = blockIdx.x * 256 + threadIdx.x; e < nnz; e += gridDim.x * 256) {
+        const int i = t_colidx[e];
+        const int deg = a_rowptr[i + 1] - a_rowptr[i];
+        out[e] = (uint8_t)(deg <= t1 ? 0 : (deg <= t2 ? 1 : 2));
+    }
+}
+
+int launch_edge_classes(const dr_csr* At, const int32_t* a_rowptr, const dr_degree_classes* c, uint8_t* out, hipStream_t s) {
+    if (At->nnz == 0) return DR_OK;
+    unsigned blocks = (unsigned)((At->nnz + 255) / 256);
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(edge_class_kernel, dim3(blocks), dim3(256), 0, s, At->colidx, (int)At->nnz, a_rowptr, c->t1, c->t2, out);
+    DRC_HIP(hipGetLastError());
+    return DR_OK;
 }
 
 }  // namespace drc

@@ -75,6 +75,17 @@ def _inputs(case, seed):
     return rowptr, colidx, avals, X, oad.DegreeClasses(*cls), rng
 
 
+def _edge_classes(At, A, cls, rowptr):
+    """dr_degree_edge_classes, checked bit for bit: class of the destination of every entry of A^T."""
+    ecls = torch.full((At.nnz,), 255, dtype=torch.uint8, device="cuda")
+    P.dr_degree_edge_classes(At, A.rowptr, tuple(cls), ecls)
+    torch.cuda.synchronize()
+    deg = np.diff(np.asarray(rowptr))
+    want = np.where(deg <= cls.t1, 0, np.where(deg <= cls.t2, 1, 2))[At.colidx.cpu().numpy()]
+    assert np.array_equal(ecls.cpu().numpy(), want.astype(np.uint8))
+    return ecls
+
+
 @pytest.mark.parametrize("case", CASES, ids=_ids())
 def test_spmm_fwd_adaptive_parity(case):
     M, N, _, D, _, _, _ = case
@@ -104,13 +115,14 @@ def test_spmm_bwd_adaptive_parity(case):
     A = P.Csr(M, N, dev(rowptr), dev(colidx), dev(avals))
     At = P.device_transpose(A)
     G = torch.full((N, cls.k1), float("nan"), dtype=torch.float32, device="cuda")
-    P.dr_spmm_bwd_adaptive(At, A.rowptr, dev(dH), idx, D, tuple(cls), G)
+    ecls = _edge_classes(At, A, cls, rowptr)
+    P.dr_spmm_bwd_adaptive(At, ecls, dev(dH), idx, D, tuple(cls), G)
     torch.cuda.synchronize()
     got = G.cpu().numpy()
     assert_row_bound(got, G_o, L1.sum(axis=1), "G")
     assert_elem_bound(got, G_o, L1, "G")
     # accumulate adds to what is there
-    P.dr_spmm_bwd_adaptive(At, A.rowptr, dev(dH), idx, D, tuple(cls), G, accumulate=True)
+    P.dr_spmm_bwd_adaptive(At, ecls, dev(dH), idx, D, tuple(cls), G, accumulate=True)
     torch.cuda.synchronize()
     assert_row_bound(G.cpu().numpy(), 2 * G_o, 2 * L1.sum(axis=1), "G accumulated")
 
@@ -137,7 +149,8 @@ def test_equal_widths_reproduce_the_uniform_kernels():
     dH = dev(rng.standard_normal((M, D)).astype(np.float32))
     Ga = torch.empty((N, k), dtype=torch.float32, device="cuda")
     Gu = torch.empty_like(Ga)
-    P.dr_spmm_bwd_adaptive(At, A.rowptr, dH, ir, D, tuple(cls), Ga)
+    ecls = _edge_classes(At, A, cls, rowptr)
+    P.dr_spmm_bwd_adaptive(At, ecls, dH, ir, D, tuple(cls), Ga)
     P.dr_spmm_bwd(At, dH, ic, D, k, Gu)
     torch.cuda.synchronize()
     assert torch.equal(Ha, Hu)          # distinct columns of a source row: each output element sees the same terms in the same order
@@ -182,7 +195,8 @@ def test_adaptive_on_the_large_graph_sampled():
     H = torch.empty((g.Nc, D), dtype=torch.float32, device="cuda")
     G = torch.empty((g.Nc, cls.k1), dtype=torch.float32, device="cuda")
     P.dr_spmm_fwd_adaptive(A, vals, idx, D, tuple(cls), H)
-    P.dr_spmm_bwd_adaptive(At, A.rowptr, dev(dH), idx, D, tuple(cls), G)
+    ecls = _edge_classes(At, A, cls, rel.rowptr)
+    P.dr_spmm_bwd_adaptive(At, ecls, dev(dH), idx, D, tuple(cls), G)
     torch.cuda.synchronize()
     deg = np.diff(rel.rowptr)
     assert (deg <= cls.t1).any() and ((deg > cls.t1) & (deg <= cls.t2)).any() and (deg > cls.t2).any()
