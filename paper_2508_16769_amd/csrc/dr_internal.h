@@ -77,6 +77,11 @@ struct HeteroDims {
 };
 HeteroDims heteroconv_dims(const dr_heteroconv* c);
 const dr_csr* heteroconv_relations(const dr_heteroconv* c);   // [3] near, pins, pinned as given to the create call
+// A context whose buffers are sized for graphs of up to (Nc, Nn, E[near, pins, pinned]); relations are bound later
+// (and again) with heteroconv_bind.  keep_workspace: also keep the transpose workspaces, which heteroconv_bind needs.
+int heteroconv_create_capacity(dr_heteroconv** ctx, int64_t Nc, int64_t Nn, const int64_t E[3], int32_t D, int32_t k_near,
+                               int32_t k_pins, int32_t k_self, int32_t k_pinned, bool keep_workspace);
+int heteroconv_bind(dr_heteroconv* c, const dr_csr* near, const dr_csr* pins, const dr_csr* pinned, hipStream_t s);
 int heteroconv_create_widths(dr_heteroconv** ctx, const dr_csr* near, const dr_csr* pins, const dr_csr* pinned, int32_t D,
                              int32_t k_near, int32_t k_pins, int32_t k_self, int32_t k_pinned);
 

@@ -31,6 +31,13 @@ struct dr_heteroconv {
     int k_near, k_pins, k_self, k_pinned;
     dr_csr A[3];        // near, pins, pinned (borrowed)
     dr_csr At[3];       // transposes (owned)
+    // what the owned buffers were sized for; a context can be re-bound to any graph within these bounds
+    int64_t cap_Nc, cap_Nn, cap_E[3];
+    int32_t* t_rp[3];   // buffers behind At[]
+    int32_t* t_ci[3];
+    float* t_v[3];
+    void* t_ws[3];      // transpose workspaces (kept only by re-bindable contexts)
+    size_t t_wsb[3];
     void* owned[32];
     int n_owned;
     hipStream_t st[3];  // near, pins, pinned
@@ -125,6 +132,91 @@ struct ScopedTiming {
 
 const dr_csr* drc::heteroconv_relations(const dr_heteroconv* c) { return c->A; }
 
+static int check_widths(int32_t D, int32_t k_near, int32_t k_pins, int32_t k_self, int32_t k_pinned) {
+    DRC_REQUIRE(k_near >= 1 && k_pins >= 1 && k_self >= 1 && k_pinned >= 1, "heteroconv_create: k must be >= 1");
+    DRC_REQUIRE(k_near <= D && k_pins <= D && k_self <= D && k_pinned <= D, "heteroconv_create: k exceeds D");
+    if (!(D == 32 || D == 64 || D == 96 || D == 128))
+        return fail(DR_ERR_UNSUPPORTED, "heteroconv_create: D = %d not in {32,64,96,128}", D);
+    return DR_OK;
+}
+
+int drc::heteroconv_create_capacity(dr_heteroconv** ctx, int64_t Nc, int64_t Nn, const int64_t E[3], int32_t D, int32_t k_near,
+                                    int32_t k_pins, int32_t k_self, int32_t k_pinned, bool keep_workspace) {
+    DRC_REQUIRE(ctx != nullptr, "heteroconv_create: null ctx");
+    *ctx = nullptr;
+    DRC_TRY(check_widths(D, k_near, k_pins, k_self, k_pinned));
+    DRC_REQUIRE(Nc >= 0 && Nn >= 0 && E[0] >= 0 && E[1] >= 0 && E[2] >= 0, "heteroconv_create: negative size");
+    DRC_REQUIRE(E[0] < (int64_t(1) << 31) && E[1] < (int64_t(1) << 31) && E[2] < (int64_t(1) << 31), "heteroconv_create: nnz >= 2^31");
+    DRC_REQUIRE(Nc * (int64_t)D < (int64_t(1) << 31) * 2 && Nn * (int64_t)D < (int64_t(1) << 31) * 2,
+                "heteroconv_create: n*D too large");
+
+    dr_heteroconv* c = new (std::nothrow) dr_heteroconv();
+    DRC_REQUIRE(c != nullptr, "heteroconv_create: out of host memory");
+    c->Nc = Nc; c->Nn = Nn; c->D = D;
+    c->cap_Nc = Nc; c->cap_Nn = Nn;
+    for (int i = 0; i < 3; ++i) c->cap_E[i] = E[i];
+    c->k_near = k_near; c->k_pins = k_pins; c->k_self = k_self; c->k_pinned = k_pinned;
+    c->timed = new (std::nothrow) std::vector<TimedLaunch>();
+    c->event_pool = new (std::nothrow) std::vector<hipEvent_t>();
+
+    int rc = DR_OK;
+    auto bail = [&](int code) { release(c); return code; };
+    if (hipGetDevice(&c->device) != hipSuccess) return bail(hip_fail(hipGetLastError(), "hipGetDevice"));
+    for (int i = 0; i < 3; ++i)
+        if (hipStreamCreateWithFlags(&c->st[i], hipStreamNonBlocking) != hipSuccess)
+            return bail(hip_fail(hipGetLastError(), "hipStreamCreateWithFlags"));
+    hipEvent_t* evs[] = {&c->ev_fork, &c->ev_topk_cell, &c->ev_topk_net, &c->ev_near,
+                         &c->ev_pins, &c->ev_pinned, &c->ev_gnear, &c->ev_gpins};
+    for (hipEvent_t* e : evs)
+        if (hipEventCreateWithFlags(e, hipEventDisableTiming) != hipSuccess)
+            return bail(hip_fail(hipGetLastError(), "hipEventCreateWithFlags"));
+
+    // buffers of the transposed adjacencies: A^T of relation i has as many rows as A has columns
+    const int64_t t_rows[3] = {Nc, Nc, Nn}, a_rows[3] = {Nc, Nn, Nc};
+    for (int i = 0; i < 3; ++i) {
+        if ((rc = dev_alloc(c, (void**)&c->t_rp[i], 4 * (size_t)(t_rows[i] + 1)))) return bail(rc);
+        if ((rc = dev_alloc(c, (void**)&c->t_ci[i], 4 * (size_t)E[i]))) return bail(rc);
+        if ((rc = dev_alloc(c, (void**)&c->t_v[i], 4 * (size_t)E[i]))) return bail(rc);
+        c->t_wsb[i] = dr_csr_transpose_workspace_bytes(a_rows[i], t_rows[i], E[i]);
+        if (keep_workspace && (rc = dev_alloc(c, &c->t_ws[i], c->t_wsb[i]))) return bail(rc);
+    }
+    const int64_t drows[3] = {Nc, Nn, Nc};
+    for (int i = 0; i < 3; ++i) {
+        if ((rc = dev_alloc(c, (void**)&c->dH[i], 4 * (size_t)drows[i] * D))) return bail(rc);
+        if ((rc = dev_alloc(c, (void**)&c->wg_scratch[i], wgrad_scratch_bytes(Nc > Nn ? Nc : Nn, D)))) return bail(rc);
+    }
+    if ((rc = dev_alloc(c, (void**)&c->dXs_cell, 4 * (size_t)Nc * k_near))) return bail(rc);
+    if (k_pins != k_near && (rc = dev_alloc(c, (void**)&c->dXs_cell_b, 4 * (size_t)Nc * k_pins))) return bail(rc);
+    if ((rc = dev_alloc(c, (void**)&c->dXs_net, 4 * (size_t)Nn * k_pinned))) return bail(rc);
+    *ctx = c;
+    return DR_OK;
+}
+
+// Binds three relations (device CSRs within the context's capacity) and enqueues their transposition on `s`.
+// Nothing here waits for the device; work enqueued on the context after `s` has passed this point sees the new graph.
+int drc::heteroconv_bind(dr_heteroconv* c, const dr_csr* near, const dr_csr* pins, const dr_csr* pinned, hipStream_t s) {
+    if (int rc = check_csr(near, "heteroconv_bind: near", true)) return rc;
+    if (int rc = check_csr(pins, "heteroconv_bind: pins", true)) return rc;
+    if (int rc = check_csr(pinned, "heteroconv_bind: pinned", true)) return rc;
+    DRC_REQUIRE(near->n_rows == near->n_cols, "heteroconv_bind: near must be square (cell x cell)");
+    const int64_t Nc = near->n_rows, Nn = pins->n_rows;
+    DRC_REQUIRE(pins->n_cols == Nc, "heteroconv_bind: pins must be Nn x Nc");
+    DRC_REQUIRE(pinned->n_rows == Nc && pinned->n_cols == Nn, "heteroconv_bind: pinned must be Nc x Nn");
+    DRC_REQUIRE(Nc <= c->cap_Nc && Nn <= c->cap_Nn && near->nnz <= c->cap_E[0] && pins->nnz <= c->cap_E[1] &&
+                    pinned->nnz <= c->cap_E[2],
+                "heteroconv_bind: graph (%lld cells, %lld nets, %lld / %lld / %lld edges) exceeds the context's capacity",
+                (long long)Nc, (long long)Nn, (long long)near->nnz, (long long)pins->nnz, (long long)pinned->nnz);
+    c->Nc = Nc; c->Nn = Nn;
+    c->A[0] = *near; c->A[1] = *pins; c->A[2] = *pinned;
+    for (int i = 0; i < 3; ++i) {
+        const dr_csr& A = c->A[i];
+        DRC_REQUIRE(c->t_ws[i] != nullptr, "heteroconv_bind: context without transpose workspace");
+        DRC_TRY(dr_csr_transpose(&A, c->t_rp[i], c->t_ci[i], c->t_v[i], c->t_ws[i], c->t_wsb[i], s));
+        c->At[i] = dr_csr{A.n_cols, A.n_rows, A.nnz, c->t_rp[i], c->t_ci[i], c->t_v[i]};
+    }
+    return DR_OK;
+}
+
 int drc::heteroconv_create_widths(dr_heteroconv** ctx, const dr_csr* near, const dr_csr* pins, const dr_csr* pinned, int32_t D,
                                   int32_t k_near, int32_t k_pins, int32_t k_self, int32_t k_pinned) {
     DRC_REQUIRE(ctx != nullptr, "heteroconv_create: null ctx");
@@ -136,63 +228,24 @@ int drc::heteroconv_create_widths(dr_heteroconv** ctx, const dr_csr* near, const
     const int64_t Nc = near->n_rows, Nn = pins->n_rows;
     DRC_REQUIRE(pins->n_cols == Nc, "heteroconv_create: pins must be Nn x Nc");
     DRC_REQUIRE(pinned->n_rows == Nc && pinned->n_cols == Nn, "heteroconv_create: pinned must be Nc x Nn");
-    DRC_REQUIRE(k_near >= 1 && k_pins >= 1 && k_self >= 1 && k_pinned >= 1, "heteroconv_create: k must be >= 1");
-    DRC_REQUIRE(k_near <= D && k_pins <= D && k_self <= D && k_pinned <= D, "heteroconv_create: k exceeds D");
-    if (!(D == 32 || D == 64 || D == 96 || D == 128))
-        return fail(DR_ERR_UNSUPPORTED, "heteroconv_create: D = %d not in {32,64,96,128}", D);
-    DRC_REQUIRE(Nc * (int64_t)D < (int64_t(1) << 31) * 2 && Nn * (int64_t)D < (int64_t(1) << 31) * 2,
-                "heteroconv_create: n*D too large");
-
-    dr_heteroconv* c = new (std::nothrow) dr_heteroconv();
-    DRC_REQUIRE(c != nullptr, "heteroconv_create: out of host memory");
-    c->Nc = Nc; c->Nn = Nn; c->D = D;
-    c->k_near = k_near; c->k_pins = k_pins; c->k_self = k_self; c->k_pinned = k_pinned;
-    c->A[0] = *near; c->A[1] = *pins; c->A[2] = *pinned;
-    c->timed = new (std::nothrow) std::vector<TimedLaunch>();
-    c->event_pool = new (std::nothrow) std::vector<hipEvent_t>();
-
-    int rc = DR_OK;
-    auto bail = [&](int code) { release(c); return code; };
-    if (hipGetDevice(&c->device) != hipSuccess) return bail(hip_fail(hipGetLastError(), "hipGetDevice"));
+    DRC_TRY(check_widths(D, k_near, k_pins, k_self, k_pinned));
     // the caller may still be producing the CSR arrays on another stream
-    if (hipDeviceSynchronize() != hipSuccess) return bail(hip_fail(hipGetLastError(), "hipDeviceSynchronize"));
-    for (int i = 0; i < 3; ++i)
-        if (hipStreamCreateWithFlags(&c->st[i], hipStreamNonBlocking) != hipSuccess)
-            return bail(hip_fail(hipGetLastError(), "hipStreamCreateWithFlags"));
-    hipEvent_t* evs[] = {&c->ev_fork, &c->ev_topk_cell, &c->ev_topk_net, &c->ev_near,
-                         &c->ev_pins, &c->ev_pinned, &c->ev_gnear, &c->ev_gpins};
-    for (hipEvent_t* e : evs)
-        if (hipEventCreateWithFlags(e, hipEventDisableTiming) != hipSuccess)
-            return bail(hip_fail(hipGetLastError(), "hipEventCreateWithFlags"));
-
-    // transposed adjacencies
-    for (int i = 0; i < 3 && rc == DR_OK; ++i) {
-        const dr_csr& A = c->A[i];
-        int32_t *rp = nullptr, *ci = nullptr;
-        float* v = nullptr;
-        void* ws = nullptr;
-        size_t wsb = dr_csr_transpose_workspace_bytes(A.n_rows, A.n_cols, A.nnz);
-        if ((rc = dev_alloc(c, (void**)&rp, 4 * (size_t)(A.n_cols + 1)))) break;
-        if ((rc = dev_alloc(c, (void**)&ci, 4 * (size_t)A.nnz))) break;
-        if ((rc = dev_alloc(c, (void**)&v, 4 * (size_t)A.nnz))) break;
-        if (hipMalloc(&ws, wsb) != hipSuccess) { rc = hip_fail(hipGetLastError(), "hipMalloc(transpose workspace)"); break; }
-        rc = dr_csr_transpose(&A, rp, ci, v, ws, wsb, c->st[i]);
-        hipError_t e = hipStreamSynchronize(c->st[i]);
-        (void)hipFree(ws);
-        if (rc == DR_OK && e != hipSuccess) rc = hip_fail(e, "hipStreamSynchronize(transpose)");
-        c->At[i] = dr_csr{A.n_cols, A.n_rows, A.nnz, rp, ci, v};
-    }
-    if (rc) return bail(rc);
-
-    const int64_t drows[3] = {Nc, Nn, Nc};
+    DRC_HIP(hipDeviceSynchronize());
+    const int64_t E[3] = {near->nnz, pins->nnz, pinned->nnz};
+    dr_heteroconv* c = nullptr;
+    DRC_TRY(heteroconv_create_capacity(&c, Nc, Nn, E, D, k_near, k_pins, k_self, k_pinned, false));
+    // one-off transposition: the workspaces are released again
+    int rc = DR_OK;
+    for (int i = 0; i < 3 && rc == DR_OK; ++i)
+        if (hipMalloc(&c->t_ws[i], c->t_wsb[i] ? c->t_wsb[i] : 256) != hipSuccess) rc = hip_fail(hipGetLastError(), "hipMalloc(transpose workspace)");
+    if (rc == DR_OK) rc = heteroconv_bind(c, near, pins, pinned, c->st[0]);
+    const hipError_t e = hipDeviceSynchronize();
     for (int i = 0; i < 3; ++i) {
-        if ((rc = dev_alloc(c, (void**)&c->dH[i], 4 * (size_t)drows[i] * D))) return bail(rc);
-        if ((rc = dev_alloc(c, (void**)&c->wg_scratch[i], wgrad_scratch_bytes(Nc > Nn ? Nc : Nn, D)))) return bail(rc);
+        if (c->t_ws[i]) (void)hipFree(c->t_ws[i]);
+        c->t_ws[i] = nullptr;
     }
-    if ((rc = dev_alloc(c, (void**)&c->dXs_cell, 4 * (size_t)Nc * k_near))) return bail(rc);
-    if (k_pins != k_near && (rc = dev_alloc(c, (void**)&c->dXs_cell_b, 4 * (size_t)Nc * k_pins))) return bail(rc);
-    if ((rc = dev_alloc(c, (void**)&c->dXs_net, 4 * (size_t)Nn * k_pinned))) return bail(rc);
-    if (hipDeviceSynchronize() != hipSuccess) return bail(hip_fail(hipGetLastError(), "hipDeviceSynchronize"));
+    if (rc == DR_OK && e != hipSuccess) rc = hip_fail(e, "hipDeviceSynchronize(transpose)");
+    if (rc != DR_OK) { release(c); return rc; }
     *ctx = c;
     return DR_OK;
 }
