@@ -357,6 +357,55 @@ int hgnn_get_layer_buffers(const dr_hgnn* model, int32_t graph, int32_t layer, d
 
 int hgnn_destroy(dr_hgnn* model);
 
+/* ------------------------------------------------------------------------------------------------
+ * Host-side pipeline (paper Section 3.4 and the breakdown of Section 4.4: loading, initialisation and host-to-device
+ * copies of the next sub-graphs run on CPU threads and their own streams while the GPU works on the current ones).
+ * A pipeline owns n_slots slots; each has pinned staging memory, device arrays and a layer context sized for the
+ * largest graph it will see (the capacities given at creation) and one stream.  Nothing is allocated after
+ * dr_pipeline_create.  Per slot the calls go submit -> acquire -> (use the context) -> release -> submit ...
+ * ---------------------------------------------------------------------------------------------- */
+
+typedef struct dr_pipeline dr_pipeline;
+
+typedef struct dr_host_graph {      /* HOST arrays (pageable or pinned), borrowed until dr_pipeline_acquire returns */
+    int64_t n_cells, n_nets;
+    int64_t nnz_near, nnz_pins;
+    const int32_t* near_rowptr;     /* [n_cells+1]  rows = destination cells, columns = source cells */
+    const int32_t* near_colidx;     /* [nnz_near]                                                    */
+    const int32_t* pins_rowptr;     /* [n_nets+1]   rows = nets, columns = cells; pinned is its transpose pattern */
+    const int32_t* pins_colidx;     /* [nnz_pins]                                                    */
+    const float*   X_cell;          /* [n_cells,D] embeddings to upload with the graph, or NULL      */
+    const float*   X_net;           /* [n_nets,D]  or NULL                                           */
+} dr_host_graph;
+
+/* Allocates the slots (device arrays, pinned staging, contexts with one K per node type) and starts n_threads
+ * worker threads.  Synchronises the device. */
+int dr_pipeline_create(dr_pipeline** pipeline, int32_t n_slots, int32_t n_threads, int64_t max_cells, int64_t max_nets,
+                       int64_t max_nnz_near, int64_t max_nnz_pins, int32_t D, int32_t k_cell, int32_t k_net);
+
+/* Hands a host graph to the worker threads and returns at once.  A worker waits (on the host) until the GPU has
+ * finished with the slot's previous graph, stages the arrays in pinned memory and enqueues on the slot's stream:
+ * the uploads, the pinned pattern (transpose of pins), the edge values of the three modules (dr_csr_normalize) and
+ * the transposed adjacencies of the slot's context.  The slot must be idle (never used, or released). */
+int dr_pipeline_submit(dr_pipeline* pipeline, int32_t slot, const dr_host_graph* graph);
+
+/* Waits (host) until the slot's work has been ENQUEUED -- not until the GPU has done it -- and makes `stream` wait
+ * for it on the device.  *ctx: the slot's layer context, bound to the submitted graph, for heteroconv_fwd / bwd,
+ * hgnn_* or heteroconv_profile_k on `stream`.  *X_cell / *X_net (may be NULL): device copies of the uploaded
+ * embeddings, or NULL where none were given.  A failure of the worker is reported here. */
+int dr_pipeline_acquire(dr_pipeline* pipeline, int32_t slot, void* stream, dr_heteroconv** ctx,
+                        const float** X_cell, const float** X_net);
+
+/* The three relations (device CSRs with edge values) of an acquired slot: out[0] near, out[1] pins, out[2] pinned. */
+int dr_pipeline_relations(dr_pipeline* pipeline, int32_t slot, dr_csr* out);
+
+/* Marks the slot reusable once everything enqueued on `stream` so far has finished (an event; the host does not
+ * wait).  The context and the device arrays of the slot must not be used by calls made after this one. */
+int dr_pipeline_release(dr_pipeline* pipeline, int32_t slot, void* stream);
+
+/* Stops the workers (queued submissions are still processed), waits for the device and frees everything. */
+int dr_pipeline_destroy(dr_pipeline* pipeline);
+
 #ifdef __cplusplus
 }
 #endif

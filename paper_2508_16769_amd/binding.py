@@ -36,6 +36,8 @@ EXPORTS = (
     "heteroconv_create", "heteroconv_create_per_relation", "heteroconv_get_k", "heteroconv_profile_k", "heteroconv_fwd", "heteroconv_bwd", "heteroconv_get_transpose", "heteroconv_destroy",
     "heteroconv_profile", "heteroconv_num_kernels", "heteroconv_kernel_name", "heteroconv_kernel_times",
     "heteroconv_set_overlap",
+    "dr_pipeline_create", "dr_pipeline_submit", "dr_pipeline_acquire", "dr_pipeline_relations", "dr_pipeline_release",
+    "dr_pipeline_destroy",
     "hgnn_num_params", "hgnn_create", "hgnn_create_batched", "hgnn_train_step", "hgnn_get_layer_buffers", "hgnn_destroy",
 )
 
@@ -102,8 +104,11 @@ def _check(rc: int) -> None:
         raise DrError(rc, load().dr_last_error().decode())
 
 
-def _ptr(t: Optional[torch.Tensor]):
-    return ctypes.c_void_p(0 if t is None else t.data_ptr())
+def _ptr(t):
+    """Device address of a tensor; None -> NULL; a plain int is taken as an address (library-owned buffers)."""
+    if t is None:
+        return ctypes.c_void_p(0)
+    return ctypes.c_void_p(t if isinstance(t, int) else t.data_ptr())
 
 
 def _stream(stream) -> ctypes.c_void_p:
@@ -314,14 +319,87 @@ class HeteroConv:
         _check(lib.heteroconv_kernel_times(self._ctx, ms, cnt, ctypes.c_int(n)))
         return {lib.heteroconv_kernel_name(i).decode(): (float(ms[i]), int(cnt[i])) for i in range(n)}
 
+    @classmethod
+    def borrowed(cls, ctx: int, Nc: int, Nn: int, D: int, keep=None) -> "HeteroConv":
+        """A view of a context some other object owns (a pipeline slot): same calls, never destroyed from here."""
+        self = cls.__new__(cls)
+        self._keep, self._borrowed = keep, True
+        self.Nc, self.Nn, self.D = Nc, Nn, D
+        self._ctx = ctypes.c_void_p(ctx)
+        self.k_near, self.k_pins, self.k_self, self.k_pinned = self.heteroconv_get_k()
+        self.k_cell, self.k_net = self.k_near, self.k_pinned
+        return self
+
     def heteroconv_destroy(self) -> None:
-        if self._ctx:
+        if self._ctx and not getattr(self, "_borrowed", False):
             _check(load().heteroconv_destroy(self._ctx))
-            self._ctx = ctypes.c_void_p(0)
+        self._ctx = ctypes.c_void_p(0)
 
     def __del__(self):
         try:
             self.heteroconv_destroy()
+        except Exception:
+            pass
+
+
+class dr_host_graph(ctypes.Structure):
+    _fields_ = [("n_cells", ctypes.c_int64), ("n_nets", ctypes.c_int64), ("nnz_near", ctypes.c_int64),
+                ("nnz_pins", ctypes.c_int64), ("near_rowptr", ctypes.c_void_p), ("near_colidx", ctypes.c_void_p),
+                ("pins_rowptr", ctypes.c_void_p), ("pins_colidx", ctypes.c_void_p), ("X_cell", ctypes.c_void_p),
+                ("X_net", ctypes.c_void_p)]
+
+
+class Pipeline:
+    """Owner of a ``dr_pipeline*`` (dr_pipeline_create / dr_pipeline_destroy).  Host arrays are numpy arrays
+    (int32 / float32, C-contiguous); they are kept alive here from submit until acquire."""
+
+    def __init__(self, n_slots: int, n_threads: int, max_cells: int, max_nets: int, max_nnz_near: int,
+                 max_nnz_pins: int, D: int, k_cell: int, k_net: int):
+        self.D = D
+        self._pending = {}
+        self._p = ctypes.c_void_p(0)
+        _check(load().dr_pipeline_create(ctypes.byref(self._p), ctypes.c_int32(n_slots), ctypes.c_int32(n_threads),
+                                         ctypes.c_int64(max_cells), ctypes.c_int64(max_nets),
+                                         ctypes.c_int64(max_nnz_near), ctypes.c_int64(max_nnz_pins), ctypes.c_int32(D),
+                                         ctypes.c_int32(k_cell), ctypes.c_int32(k_net)))
+
+    def dr_pipeline_submit(self, slot: int, near_rowptr, near_colidx, pins_rowptr, pins_colidx, X_cell=None,
+                           X_net=None) -> None:
+        import numpy as np
+        arrs = [np.ascontiguousarray(a, dtype=np.int32) for a in (near_rowptr, near_colidx, pins_rowptr, pins_colidx)]
+        feats = [None if a is None else np.ascontiguousarray(a, dtype=np.float32) for a in (X_cell, X_net)]
+        g = dr_host_graph(arrs[0].shape[0] - 1, arrs[2].shape[0] - 1, arrs[1].shape[0], arrs[3].shape[0],
+                          *[a.ctypes.data for a in arrs], *[0 if a is None else a.ctypes.data for a in feats])
+        _check(load().dr_pipeline_submit(self._p, ctypes.c_int32(slot), ctypes.byref(g)))
+        self._pending[slot] = (arrs, feats, g)
+
+    def dr_pipeline_acquire(self, slot: int, stream=None):
+        """Returns (HeteroConv view of the slot's context, X_cell device address or None, X_net ... or None)."""
+        ctx, xc, xn = ctypes.c_void_p(0), ctypes.c_void_p(0), ctypes.c_void_p(0)
+        try:
+            _check(load().dr_pipeline_acquire(self._p, ctypes.c_int32(slot), _stream(stream), ctypes.byref(ctx),
+                                              ctypes.byref(xc), ctypes.byref(xn)))
+        finally:
+            arrs, feats, g = self._pending.pop(slot, (None, None, None))
+        layer = HeteroConv.borrowed(ctx.value, int(g.n_cells), int(g.n_nets), self.D, keep=self)
+        return layer, xc.value, xn.value
+
+    def dr_pipeline_relations(self, slot: int):
+        out = (dr_csr * 3)()
+        _check(load().dr_pipeline_relations(self._p, ctypes.c_int32(slot), out))
+        return [out[i] for i in range(3)]
+
+    def dr_pipeline_release(self, slot: int, stream=None) -> None:
+        _check(load().dr_pipeline_release(self._p, ctypes.c_int32(slot), _stream(stream)))
+
+    def dr_pipeline_destroy(self) -> None:
+        if self._p:
+            _check(load().dr_pipeline_destroy(self._p))
+            self._p = ctypes.c_void_p(0)
+
+    def __del__(self):
+        try:
+            self.dr_pipeline_destroy()
         except Exception:
             pass
 
