@@ -318,8 +318,11 @@ int64_t hgnn_num_params(int32_t n_layers, int32_t D);
 
 /*
  * Build the model state for n_graphs sub-graphs (one heteroconv context each, all with the same D; every
- * sub-graph keeps the K its context was created with, per node type or per relation) and n_layers layers: allocates every activation, saved-state and gradient buffer and one stream per
- * sub-graph.  The contexts stay owned by the caller and must outlive the model.  Synchronises the device.
+ * sub-graph keeps the K its context was created with, per node type or per relation) and n_layers layers:
+ * allocates every activation, saved-state and gradient buffer and one stream per sub-graph.  The contexts stay
+ * owned by the caller and must outlive the model.  Synchronises the device.
+ * Buffers are sized for what the contexts can hold, and every step works on the graphs bound to them at that
+ * moment: over the contexts of dr_pipeline slots one model trains on a stream of sub-graphs.
  */
 int hgnn_create(dr_hgnn** model, int32_t n_graphs, dr_heteroconv* const* graphs, int32_t n_layers);
 

@@ -441,7 +441,7 @@ class Hgnn:
     def hgnn_train_step(self, X_cell, X_net, target, theta, adam_m, adam_v, lr, beta1, beta2, eps, weight_decay, step,
                         grad_out, loss_out, stream=None) -> None:
         n = len(self._graphs)
-        tabs = [(ctypes.c_void_p * n)(*[t.data_ptr() for t in lst]) for lst in (X_cell, X_net, target)]
+        tabs = [(ctypes.c_void_p * n)(*[t if isinstance(t, int) else t.data_ptr() for t in lst]) for lst in (X_cell, X_net, target)]
         _check(load().hgnn_train_step(self._model, tabs[0], tabs[1], tabs[2], _ptr(theta), _ptr(adam_m), _ptr(adam_v),
                                       ctypes.c_double(lr), ctypes.c_double(beta1), ctypes.c_double(beta2),
                                       ctypes.c_double(eps), ctypes.c_double(weight_decay), ctypes.c_int32(step),

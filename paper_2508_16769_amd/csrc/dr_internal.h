@@ -76,7 +76,8 @@ struct HeteroDims {
     int k_near, k_pins, k_self, k_pinned;   // D-ReLU widths: cells for near / for pins, nets for the pins self term / for pinned
 };
 HeteroDims heteroconv_dims(const dr_heteroconv* c);
-const dr_csr* heteroconv_relations(const dr_heteroconv* c);   // [3] near, pins, pinned as given to the create call
+const dr_csr* heteroconv_relations(const dr_heteroconv* c);
+void heteroconv_capacity(const dr_heteroconv* c, int64_t* cells, int64_t* nets);   // what the context's buffers are sized for   // [3] near, pins, pinned as given to the create call
 // A context whose buffers are sized for graphs of up to (Nc, Nn, E[near, pins, pinned]); relations are bound later
 // (and again) with heteroconv_bind.  keep_workspace: also keep the transpose workspaces, which heteroconv_bind needs.
 int heteroconv_create_capacity(dr_heteroconv** ctx, int64_t Nc, int64_t Nn, const int64_t E[3], int32_t D, int32_t k_near,

@@ -132,6 +132,8 @@ struct ScopedTiming {
 
 const dr_csr* drc::heteroconv_relations(const dr_heteroconv* c) { return c->A; }
 
+void drc::heteroconv_capacity(const dr_heteroconv* c, int64_t* cells, int64_t* nets) { *cells = c->cap_Nc; *nets = c->cap_Nn; }
+
 static int check_widths(int32_t D, int32_t k_near, int32_t k_pins, int32_t k_self, int32_t k_pinned) {
     DRC_REQUIRE(k_near >= 1 && k_pins >= 1 && k_self >= 1 && k_pinned >= 1, "heteroconv_create: k must be >= 1");
     DRC_REQUIRE(k_near <= D && k_pins <= D && k_self <= D && k_pinned <= D, "heteroconv_create: k exceeds D");

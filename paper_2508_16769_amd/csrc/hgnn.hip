@@ -343,7 +343,11 @@ static int create_model(dr_hgnn** model, int32_t n_graphs, dr_heteroconv* const*
         const int ns = m->n_graphs;
         DRC_TRY(alloc_t(m, &m->gall, (size_t)ns * m->PL));
         m->n_head_parts = 0;
-        for (int q = 0; q < ns; ++q) m->n_head_parts += head_blocks(heteroconv_dims(ctxs[q]).Nc);
+        // Buffers are sized for the contexts' capacities: a context that a pipeline re-binds to the next sub-graph keeps
+        // serving the same model, and every step reads the sizes of the graph that is bound at that moment.
+        auto cap_cells = [&](int q) { int64_t c = 0, n = 0; heteroconv_capacity(ctxs[q], &c, &n); return c; };
+        auto cap_nets = [&](int q) { int64_t c = 0, n = 0; heteroconv_capacity(ctxs[q], &c, &n); return n; };
+        for (int q = 0; q < ns; ++q) m->n_head_parts += head_blocks(cap_cells(q));
         DRC_TRY(alloc_t(m, &m->loss_part, (size_t)m->n_head_parts));
         DRC_TRY(alloc_t(m, &m->dwh_part, (size_t)m->n_head_parts * m->D));
         int part0 = 0;
@@ -351,19 +355,20 @@ static int create_model(dr_hgnn** model, int32_t n_graphs, dr_heteroconv* const*
             GraphState& gs = m->g[q];
             const HeteroDims d = heteroconv_dims(ctxs[q]);
             gs.ctx = ctxs[q]; gs.Nc = d.Nc; gs.Nn = d.Nn;
-            DRC_REQUIRE(d.Nc >= 1 && d.Nc < (1ll << 31) / D, "hgnn_create: graph %d has %lld cells", q, (long long)d.Nc);
+            const int64_t capc = cap_cells(q), capn = cap_nets(q);
+            DRC_REQUIRE(capc >= 1 && capc < (1ll << 31) / D, "hgnn_create: graph %d has room for %lld cells", q, (long long)capc);
             m->n_cells_total += d.Nc;
             DRC_HIP(hipStreamCreateWithFlags(&gs.stream, hipStreamNonBlocking));
             DRC_HIP(hipEventCreateWithFlags(&gs.done, hipEventDisableTiming));
             gs.gvec = m->gall + (size_t)q * m->PL;
-            gs.hb = head_blocks(d.Nc);
+            gs.hb = head_blocks(capc);
             gs.loss_part = m->loss_part + (size_t)part0;
             gs.dwh_part = m->dwh_part + (size_t)part0 * D;
             part0 += gs.hb;
             gs.act_c.assign(L, nullptr); gs.act_n.assign(L, nullptr);
             gs.G_c.assign(L + 1, nullptr); gs.G_n.assign(L + 1, nullptr);
             gs.saved.assign(L, dr_heteroconv_saved{});
-            const size_t nc = (size_t)d.Nc, nn = (size_t)d.Nn;
+            const size_t nc = (size_t)capc, nn = (size_t)capn;
             for (int l = 0; l < L; ++l) {
                 DRC_TRY(alloc_t(m, &gs.act_c[l], nc * D));
                 DRC_TRY(alloc_t(m, &gs.act_n[l], nn * D));
@@ -452,6 +457,14 @@ int hgnn_train_step(dr_hgnn* m, const float* const* X_cell, const float* const* 
         DRC_REQUIRE(X_cell[q] && X_net[q] && target[q], "hgnn_train_step: null tensor for graph %d", q);
     hipStream_t user = as_stream(stream);
     for (int q = 0; q < m->n_user; ++q) { m->ux_c[q] = X_cell[q]; m->ux_n[q] = X_net[q]; }
+    if (!m->batched) {          // the graphs bound to the contexts right now (a pipeline may have re-bound them)
+        m->n_cells_total = 0;
+        for (auto& gs : m->g) {
+            const HeteroDims d = heteroconv_dims(gs.ctx);
+            gs.Nc = d.Nc; gs.Nn = d.Nn;
+            m->n_cells_total += d.Nc;
+        }
+    }
     const float *one_c = nullptr, *one_n = nullptr, *one_t = nullptr;      // batched: the stacked inputs
     if (m->batched) {
         DRC_TRY(stacked_input(X_cell, m->n_user, m->off_c, m->D, m->Xc_all, user, &one_c));

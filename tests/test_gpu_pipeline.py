@@ -125,3 +125,55 @@ def test_pipeline_protocol_errors():
     pl.dr_pipeline_destroy()
     with pytest.raises(P.DrError):
         P.Pipeline(n_slots=0, n_threads=1, max_cells=10, max_nets=10, max_nnz_near=10, max_nnz_pins=10, D=D, k_cell=K, k_net=K)
+
+
+def test_training_steps_on_pipeline_slots_equal_steps_on_ordinary_contexts():
+    """One model over the contexts of two pipeline slots trains on a stream of sub-graph pairs (the slots are re-bound
+    between steps, to graphs of other sizes); every step equals, bit for bit, the step of a model built the ordinary
+    way for that pair."""
+    L, D2, k = 2, 64, 16
+    pairs = [(make_graph("tiny", seed=70, Nc=2000, Nn=1300, grid=(50, 40)), make_graph("tiny", seed=71, Nc=1800, Nn=1400, grid=(50, 40))),
+             (make_graph("tiny", seed=72, Nc=1500, Nn=900, grid=(50, 30)), make_graph("tiny", seed=73, Nc=2000, Nn=1400, grid=(50, 40)))]
+    gs = [g for p in pairs for g in p]
+    rng = np.random.default_rng(8)
+    feats = {id(g): (rng.standard_normal((g.Nc, D2)).astype(np.float32), rng.standard_normal((g.Nn, D2)).astype(np.float32),
+                     rng.standard_normal(g.Nc).astype(np.float32)) for g in gs}
+    n_par = P.hgnn_num_params(L, D2)
+    theta0 = rng.uniform(-0.2, 0.2, n_par).astype(np.float32)
+    say("pipeline: training steps on re-bound slot contexts")
+    pl = P.Pipeline(2, 2, 2000, 1400, max(g.near.nnz for g in gs), max(g.pins.nnz for g in gs), D2, k, k)
+
+    def state():
+        return (dev(theta0), torch.zeros(n_par, dtype=torch.float32, device="cuda"), torch.zeros(n_par, dtype=torch.float32, device="cuda"),
+                torch.full((n_par,), float("nan"), dtype=torch.float32, device="cuda"), torch.full((1,), float("nan"), dtype=torch.float32, device="cuda"))
+
+    th, m, v, gr, ls = state()
+    model = None
+    for step, pair in enumerate(pairs, start=1):
+        for slot, g in enumerate(pair):
+            pl.dr_pipeline_submit(slot, g.near.rowptr, g.near.colidx, g.pins.rowptr, g.pins.colidx, feats[id(g)][0], feats[id(g)][1])
+        got = [pl.dr_pipeline_acquire(slot) for slot in range(2)]
+        if model is None:
+            model = P.Hgnn([a[0] for a in got], L)          # the slot contexts; their addresses do not change
+        tg = [dev(feats[id(g)][2]) for g in pair]
+        model.hgnn_train_step([a[1] for a in got], [a[2] for a in got], tg, th, m, v, 2e-4, 0.9, 0.999, 1e-8, 1e-5, step, gr, ls)
+        torch.cuda.synchronize()
+        for slot in range(2):
+            pl.dr_pipeline_release(slot)
+        # the same step on ordinary contexts, from the same parameter state
+        keep = [(P.device_relation(g.near, P.DR_NORM_MEAN), P.device_relation(g.pins, P.DR_NORM_MEAN), P.device_relation(g.pinned, P.DR_NORM_SYM))
+                for g in pair]
+        ctxs = [P.HeteroConv(d[0], d[1], d[2], D2, k, k) for d in keep]
+        ref = P.Hgnn(ctxs, L)
+        if step == 1:
+            th_r, m_r, v_r, gr_r, ls_r = state()
+        ref.hgnn_train_step([dev(feats[id(g)][0]) for g in pair], [dev(feats[id(g)][1]) for g in pair], tg, th_r, m_r, v_r,
+                            2e-4, 0.9, 0.999, 1e-8, 1e-5, step, gr_r, ls_r)
+        torch.cuda.synchronize()
+        assert torch.equal(ls, ls_r) and torch.equal(gr, gr_r) and torch.equal(th, th_r), step
+        assert np.isfinite(float(ls.cpu()[0]))
+        ref.hgnn_destroy()
+        for c in ctxs:
+            c.heteroconv_destroy()
+    model.hgnn_destroy()
+    pl.dr_pipeline_destroy()
