@@ -7,7 +7,7 @@ both node types, the three DR-SpMM forwards, the projections and max-merge, and 
 Graph setup (edge values, transposes) is done once before the timed region.  Inputs are resident in HBM
 when the timed region starts.
 
-Prints ONE JSON line (see the design doc for the byte model behind `value` and `roofline`).
+Prints ONE JSON line; `kernel_models()` below is the byte model behind `value` and `roofline`.
 """
 from __future__ import annotations
 
@@ -138,8 +138,8 @@ def main() -> int:
                          "FETCH_SIZE / WRITE_SIZE readings) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build measures one GPU only (the path is single-GPU; see DESIGN.md for how it "
-              "would shard); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build measures one GPU only (the path is single-GPU; sharding it over several GPUs is "
+              "a design note, not code); run with --gpus 1", file=sys.stderr)
         return 2
 
     import numpy as np
