@@ -115,6 +115,52 @@ def test_heteroconv_create_argument_errors():
     assert lib.heteroconv_destroy(None) == P.DR_OK
 
 
+def test_newer_entry_points_validate_on_the_host():
+    """Per-relation K, K profiling, adaptive K, the batched model and the pipeline: argument errors come back before any
+    HIP call (this test runs without a GPU)."""
+    from paper_2508_16769_amd.binding import dr_degree_classes, dr_host_graph
+    lib = P.load()
+    one = ctypes.c_void_p(16)
+    i64 = ctypes.c_int64
+    ctx = ctypes.c_void_p(0)
+    near, pins, pinned = _null_csr(8, 8, 3), _null_csr(5, 8, 3), _null_csr(8, 5, 3)
+    args = (ctypes.byref(ctx), ctypes.byref(near), ctypes.byref(pins), ctypes.byref(pinned))
+    assert lib.heteroconv_create_per_relation(*args, 64, 16, 0, 16) == P.DR_ERR_INVALID_ARG
+    assert lib.heteroconv_create_per_relation(*args, 64, 16, 16, 65) == P.DR_ERR_INVALID_ARG
+    assert lib.heteroconv_create_per_relation(*args, 48, 16, 16, 16) == P.DR_ERR_UNSUPPORTED
+    assert lib.heteroconv_profile_k(None, one, one, one, 1, 0, 1, one, one, one) == P.DR_ERR_INVALID_ARG
+    assert lib.heteroconv_get_k(None, one, one, one, one) == P.DR_ERR_INVALID_ARG
+    # adaptive K
+    A = _null_csr(nnz=3)
+    for bad in ((3, 2, 8, 4, 2), (-1, 2, 8, 4, 2), (1, 2, 4, 8, 2), (1, 2, 8, 4, 0), (1, 2, 9, 4, 2)):
+        c = dr_degree_classes(*bad)
+        assert lib.dr_spmm_fwd_adaptive(ctypes.byref(A), one, one, 8, ctypes.byref(c), one, None) == P.DR_ERR_INVALID_ARG, bad
+        assert lib.dr_spmm_bwd_adaptive(ctypes.byref(A), one, one, one, 8, ctypes.byref(c), one, 0, None) == P.DR_ERR_INVALID_ARG, bad
+    wide = dr_degree_classes(1, 2, 96, 4, 2)
+    assert lib.dr_spmm_fwd_adaptive(ctypes.byref(A), one, one, 128, ctypes.byref(wide), one, None) == P.DR_ERR_UNSUPPORTED
+    ok = dr_degree_classes(1, 2, 8, 4, 2)
+    assert lib.dr_spmm_fwd_adaptive(ctypes.byref(A), one, one, 8, None, one, None) == P.DR_ERR_INVALID_ARG
+    assert lib.dr_spmm_fwd_adaptive(ctypes.byref(A), None, one, 8, ctypes.byref(ok), one, None) == P.DR_ERR_INVALID_ARG
+    assert lib.dr_spmm_bwd_adaptive(ctypes.byref(A), None, one, one, 8, ctypes.byref(ok), one, 0, None) == P.DR_ERR_INVALID_ARG
+    assert lib.dr_degree_edge_classes(ctypes.byref(A), None, ctypes.byref(ok), one, None) == P.DR_ERR_INVALID_ARG
+    assert lib.dr_topk_ranked(one, i64(4), 8, 9, one, one, None) == P.DR_ERR_INVALID_ARG
+    assert lib.dr_topk_ranked(None, i64(0), 8, 2, None, None, None) == P.DR_OK
+    # batched model and pipeline
+    mdl = ctypes.c_void_p(0)
+    assert lib.hgnn_create_batched(ctypes.byref(mdl), 0, None, 2) == P.DR_ERR_INVALID_ARG
+    assert lib.hgnn_create_batched(ctypes.byref(mdl), 1, None, 2) == P.DR_ERR_INVALID_ARG
+    pl = ctypes.c_void_p(0)
+    assert lib.dr_pipeline_create(ctypes.byref(pl), 0, 1, i64(10), i64(10), i64(10), i64(10), 64, 16, 16) == P.DR_ERR_INVALID_ARG
+    assert lib.dr_pipeline_create(ctypes.byref(pl), 1, 99, i64(10), i64(10), i64(10), i64(10), 64, 16, 16) == P.DR_ERR_INVALID_ARG
+    assert lib.dr_pipeline_create(ctypes.byref(pl), 1, 1, i64(0), i64(10), i64(10), i64(10), 64, 16, 16) == P.DR_ERR_INVALID_ARG
+    assert lib.dr_pipeline_create(None, 1, 1, i64(10), i64(10), i64(10), i64(10), 64, 16, 16) == P.DR_ERR_INVALID_ARG
+    g = dr_host_graph()
+    assert lib.dr_pipeline_submit(None, 0, ctypes.byref(g)) == P.DR_ERR_INVALID_ARG
+    assert lib.dr_pipeline_acquire(None, 0, None, ctypes.byref(ctx), None, None) == P.DR_ERR_INVALID_ARG
+    assert lib.dr_pipeline_release(None, 0, None) == P.DR_ERR_INVALID_ARG
+    assert lib.dr_pipeline_destroy(None) == P.DR_OK
+
+
 def test_binding_refuses_missing_library(monkeypatch, tmp_path):
     """No CPU fallback: if the shared library cannot be loaded the binding raises."""
     from paper_2508_16769_amd import binding, build
