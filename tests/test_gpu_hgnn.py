@@ -484,3 +484,42 @@ def test_rejects_bad_arguments():
         model.hgnn_train_step(x[0], x[1], x[2], z, z.clone(), z.clone(), LR, B1, B2, EPS, WD, 0, z.clone(), z[:1].clone())
     model.hgnn_destroy()
     ctx.heteroconv_destroy()
+
+
+def test_batched_model_with_one_k_per_edge_type():
+    """Stacking also serves contexts that keep one K per edge type (the same triple for the whole batch): same step
+    as the streamed model up to the order of the fp32 sums over rows, same selections."""
+    D, L, kk = 96, 2, (8, 24, 12)
+    rng = np.random.default_rng(9)
+    gs = [make_graph("small", seed=80 + q, Nc=1300 + 90 * q, Nn=800 + 40 * q, grid=(40, 40)) for q in range(3)]
+    say("hgnn batched with k_near/k_pins/k_pinned = %s" % (kk,))
+    Xc = [dev(rng.standard_normal((g.Nc, D)).astype(np.float32)) for g in gs]
+    Xn = [dev(rng.standard_normal((g.Nn, D)).astype(np.float32)) for g in gs]
+    tg = [dev(rng.standard_normal(g.Nc).astype(np.float32)) for g in gs]
+    n_par = P.hgnn_num_params(L, D)
+    theta0 = rng.uniform(-0.15, 0.15, n_par).astype(np.float32)
+    keep = [(P.device_relation(g.near, P.DR_NORM_MEAN), P.device_relation(g.pins, P.DR_NORM_MEAN),
+             P.device_relation(g.pinned, P.DR_NORM_SYM)) for g in gs]
+    ctxs = [P.HeteroConv(*d, D, per_relation=kk) for d in keep]
+    out = []
+    for batched in (False, True):
+        model = P.Hgnn(ctxs, L, batched=batched)
+        th = dev(theta0)
+        m = torch.zeros(n_par, dtype=torch.float32, device="cuda")
+        v = torch.zeros(n_par, dtype=torch.float32, device="cuda")
+        gr = torch.empty(n_par, dtype=torch.float32, device="cuda")
+        ls = torch.empty(1, dtype=torch.float32, device="cuda")
+        model.hgnn_train_step(Xc, Xn, tg, th, m, v, LR, B1, B2, EPS, WD, 1, gr, ls)
+        torch.cuda.synchronize()
+        b = model.hgnn_get_layer_buffers(1, 0)
+        out.append((float(ls.cpu()[0]), gr.cpu().numpy().astype(np.float64), host_idx(b["idx_cell"]), host_idx(b["idx_cell_pins"]),
+                    host_idx(b["idx_net_self"]), b["Y_cell"].cpu().numpy()))
+        model.hgnn_destroy()
+    (la, ga, i1a, i2a, i3a, ya), (lb, gb, i1b, i2b, i3b, yb) = out
+    assert np.array_equal(i1a, i1b) and np.array_equal(i2a, i2b) and np.array_equal(i3a, i3b)
+    assert i1a.shape[1] == kk[0] and i2a.shape[1] == kk[1] and i3a.shape[1] == kk[1]
+    assert np.array_equal(ya, yb)                     # first layer: same inputs, same kernels, same rows
+    assert abs(la - lb) <= 1e-6 * abs(la)
+    assert np.allclose(ga, gb, rtol=1e-4, atol=1e-6 * np.abs(ga).max())
+    for c in ctxs:
+        c.heteroconv_destroy()
