@@ -31,10 +31,11 @@ template <int EPL, bool DUAL, bool RANKED>
 __global__ __launch_bounds__(256) void topk_rows_kernel(const float* __restrict__ X, int n, int D, int k,
                                                         float* __restrict__ vals, uint16_t* __restrict__ idx, int k2,
                                                         float* __restrict__ vals2, uint16_t* __restrict__ idx2) {
-    extern __shared__ uint32_t kept_keys[];                   // RANKED: [4 wavefronts][k] keys of the current row
+    extern __shared__ uint4 kept_keys4[];                     // RANKED: [4 wavefronts][k rounded up to 4] keys of the current row
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
-    uint32_t* const my_keys = kept_keys + wave * k;
+    const int k4 = (k + 3) >> 2;
+    uint32_t* const my_keys = reinterpret_cast<uint32_t*>(kept_keys4 + wave * k4);
     const int stride = gridDim.x * (blockDim.x >> 6);        // rows between consecutive rows of one wavefront
     const int row0 = blockIdx.x * (blockDim.x >> 6) + wave;
 
@@ -112,6 +113,7 @@ __global__ __launch_bounds__(256) void topk_rows_kernel(const float* __restrict_
             // One wavefront executes its LDS accesses in program order, so the reads below see the keys written here
             // and the next row's writes come after this row's reads; the fences keep the compiler from reordering.
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            if (lane < 4 * k4 - k) my_keys[k + lane] = 0u;     // padding keys: below every real key, so they never count
 #pragma unroll
             for (int s = 0; s < EPL; ++s)
                 if (keep_s[s]) my_keys[pos_s[s]] = key[s];
@@ -123,9 +125,13 @@ __global__ __launch_bounds__(256) void topk_rows_kernel(const float* __restrict_
                 const uint32_t mine = key[s];
                 const int p_me = pos_s[s];
                 int rank = 0;
-                for (int p = 0; p < k; ++p) {                  // every lane reads the same word: broadcast
-                    const uint32_t other = my_keys[p];
-                    rank += (other > mine || (other == mine && p < p_me)) ? 1 : 0;
+                for (int p4 = 0; p4 < k4; ++p4) {              // every lane reads the same 16 bytes: broadcast
+                    const uint4 o = reinterpret_cast<const uint4*>(my_keys)[p4];
+                    const int p = 4 * p4;
+                    rank += (o.x > mine || (o.x == mine && p + 0 < p_me)) ? 1 : 0;
+                    rank += (o.y > mine || (o.y == mine && p + 1 < p_me)) ? 1 : 0;
+                    rank += (o.z > mine || (o.z == mine && p + 2 < p_me)) ? 1 : 0;
+                    rank += (o.w > mine || (o.w == mine && p + 3 < p_me)) ? 1 : 0;
                 }
                 vals[base + rank] = val[s];
                 idx[base + rank] = (uint16_t)(s * kWave + lane);
@@ -157,7 +163,7 @@ static void launch_epl(const float* X, int n, int D, int k, float* vals, uint16_
     if (blocks > 4096) blocks = 4096;            // two full rounds of 8 waves/SIMD; each wavefront strides over rows
     if (ranked)
         hipLaunchKernelGGL((topk_rows_kernel<EPL, false, true>), dim3((unsigned)blocks), dim3(256),
-                           sizeof(uint32_t) * 4 * (size_t)k, s, X, n, D, k, vals, idx, 0, nullptr, nullptr);
+                           sizeof(uint4) * 4 * (size_t)((k + 3) / 4), s, X, n, D, k, vals, idx, 0, nullptr, nullptr);
     else if (vals2)
         hipLaunchKernelGGL((topk_rows_kernel<EPL, true, false>), dim3((unsigned)blocks), dim3(256), 0, s, X, n, D, k, vals, idx,
                            k2, vals2, idx2);
