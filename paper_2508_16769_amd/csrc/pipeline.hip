@@ -77,9 +77,9 @@ int process(dr_pipeline* p, Slot& s) {
     const size_t p_rp = 4 * (size_t)(g.n_nets + 1), p_ci = 4 * (size_t)g.nnz_pins;
     const size_t xc = g.X_cell ? 4 * (size_t)g.n_cells * D : 0, xn = g.X_net ? 4 * (size_t)g.n_nets * D : 0;
     std::memcpy(s.stage, g.near_rowptr, n_rp);
-    std::memcpy(s.stage + s.off_near_ci, g.near_colidx, n_ci);
+    if (n_ci) std::memcpy(s.stage + s.off_near_ci, g.near_colidx, n_ci);
     std::memcpy(s.stage + s.off_pins_rp, g.pins_rowptr, p_rp);
-    std::memcpy(s.stage + s.off_pins_ci, g.pins_colidx, p_ci);
+    if (p_ci) std::memcpy(s.stage + s.off_pins_ci, g.pins_colidx, p_ci);
     if (xc) std::memcpy(s.stage + s.off_xc, g.X_cell, xc);
     if (xn) std::memcpy(s.stage + s.off_xn, g.X_net, xn);
     hipStream_t st = s.stream;

@@ -177,3 +177,29 @@ def test_training_steps_on_pipeline_slots_equal_steps_on_ordinary_contexts():
             c.heteroconv_destroy()
     model.hgnn_destroy()
     pl.dr_pipeline_destroy()
+
+
+def test_pipeline_with_an_edgeless_relation():
+    """A sub-graph whose near relation has no edges at all (and nets that pin nothing for a few rows): the slot still
+    delivers a usable context and the layer equals the ordinary one bit for bit."""
+    from circuit_synth.generate import Pattern, transpose_pattern
+    g = make_graph("tiny", seed=90, Nc=600, Nn=400, grid=(30, 20))
+    near = Pattern(g.Nc, g.Nc, np.zeros(g.Nc + 1, dtype=np.int32), np.zeros(0, dtype=np.int32))
+    say("pipeline: edgeless near relation")
+    T = make_tensors(g.Nc, g.Nn, D, seed=91)
+    pl = P.Pipeline(1, 1, g.Nc, g.Nn, 16, g.pins.nnz, D, K, K)
+    pl.dr_pipeline_submit(0, near.rowptr, near.colidx, g.pins.rowptr, g.pins.colidx, T.X_cell, T.X_net)
+    layer, xc, xn = pl.dr_pipeline_acquire(0)
+
+    class G2:
+        Nc, Nn = g.Nc, g.Nn
+    got = _layer_outputs(layer, xc, xn, T, G2)
+    ref = P.HeteroConv(P.device_relation(near, P.DR_NORM_MEAN), P.device_relation(g.pins, P.DR_NORM_MEAN),
+                       P.device_relation(transpose_pattern(g.pins), P.DR_NORM_SYM), D, K, K)
+    want = _layer_outputs(ref, dev(T.X_cell), dev(T.X_net), T, G2)
+    for a, b in zip(got, want):
+        assert torch.equal(a, b)
+    assert torch.isfinite(got[0]).all()
+    ref.heteroconv_destroy()
+    pl.dr_pipeline_release(0)
+    pl.dr_pipeline_destroy()
