@@ -54,6 +54,7 @@ struct GemmParams {
     float* out;
     uint8_t* mask_out;
     SampleSet first, second;      // kEpiSampleDense(2): selections and compact gradients of the write-out
+    int relu;                     // kEpiStore / kEpiMaxMerge: clamp what is written at zero
 };
 constexpr int kEpiSampleDense2 = 3;   // kEpiSampleDense with a second selection and/or no compact on the first
 
@@ -239,6 +240,12 @@ __global__ __launch_bounds__(kPT, (EPI == kEpiStore ? (AK == kACbsrDense ? 2 : 4
     };
     auto store_tile = [&](int tile) {                  // out[rows, D] = C
         if (!mm) return;
+        if (p.relu) {
+#pragma unroll
+            for (int j = 0; j < SPW; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[j][r] = fmaxf(acc[j][r], 0.0f);
+        }
         // one pointer per sub-tile; the 16 rows a lane holds sit at fixed offsets from it
         const int row0 = tile * BM + rg * SPW * 32 + 4 * (lane >> 5);
         float* const o = p.out + (size_t)row0 * D + 32 * ct + (lane & 31);
@@ -343,9 +350,12 @@ __global__ __launch_bounds__(kPT, (EPI == kEpiStore ? (AK == kACbsrDense ? 2 : 4
                             const int dr = j * 32 + 8 * (r >> 2) + (r & 3);
                             const float c = acc[j][r];
                             const bool near_wins = prev[j][r] >= c;
+                            // with the activation folded in, a negative near value that stays has to be rewritten too
+                            const bool rewrite = !near_wins || (p.relu && prev[j][r] < 0.0f);
+                            const float v = near_wins ? prev[j][r] : c;
                             if (full || row0 + dr < p.rows) {
                                 mo[dr * D] = near_wins ? 1 : 0;
-                                if (!near_wins) o[dr * D] = c;
+                                if (rewrite) o[dr * D] = p.relu ? fmaxf(v, 0.0f) : v;
                             }
                         }
                 }
@@ -399,6 +409,30 @@ __global__ __launch_bounds__(kPT, (EPI == kEpiStore ? (AK == kACbsrDense ? 2 : 4
                             }
 #pragma unroll
                             for (int u = 0; u < 4; ++u) orow[cc[u]] += v[u];
+                        }
+                    }
+                }
+                if constexpr (kSample2) {
+                    // ReLU in front of the layer: the gradient of a selected input that was not positive is zero
+                    // (outside the selections the row is zero anyway); the values are fetched here, late
+                    for (int pass = 0; pass < 2; ++pass) {
+                        const SampleSet& ss = pass ? p.second : p.first;
+                        if (!ss.gate || !ss.idx) continue;
+                        __builtin_amdgcn_wave_barrier();
+                        const int kg = ss.k;
+                        const size_t baseg = (size_t)min(tile * BM + prow, p.rows - 1) * kg;
+                        for (int u0 = 0; u0 * TPR < kg; u0 += 4) {
+                            float gv[4];
+                            int gc[4];
+#pragma unroll
+                            for (int u = 0; u < 4; ++u) {
+                                const int t = ppart + TPR * (u0 + u);
+                                gv[u] = ss.gate[baseg + min(t, kg - 1)];
+                                gc[u] = t < kg ? (int)ss.idx[baseg + min(t, kg - 1)] : D;
+                            }
+#pragma unroll
+                            for (int u = 0; u < 4; ++u)
+                                if (!(gv[u] > 0.0f)) orow[gc[u]] = 0.0f;
                         }
                     }
                 }
@@ -464,7 +498,7 @@ static int launch_proj_nt(const GemmParams& p, int ak, hipStream_t s) {
 }
 
 int launch_gemm(const GemmOperand* segs, int nseg, int64_t rows, int D, GemmEpilogue epi, float* out,
-                uint8_t* mask_out, SampleSet first, SampleSet second, hipStream_t s) {
+                uint8_t* mask_out, SampleSet first, SampleSet second, hipStream_t s, int relu_out) {
     if (rows == 0) return DR_OK;
     GemmParams p{};
     for (int i = 0; i < nseg; ++i) p.seg[i] = segs[i];
@@ -475,11 +509,12 @@ int launch_gemm(const GemmOperand* segs, int nseg, int64_t rows, int D, GemmEpil
     p.mask_out = mask_out;
     p.first = first;
     p.second = second;
+    p.relu = relu_out;
     if (epi == kEpiSampleDense) {
         if (first.k < 1 || !first.idx) return fail(DR_ERR_INVALID_ARG, "sampling epilogue without indices");
         if (second.idx && (second.k < 1 || !second.compact))
             return fail(DR_ERR_INVALID_ARG, "sampling epilogue: second selection without its compact gradient");
-        if (second.idx || !first.compact) p.epi = kEpiSampleDense2;
+        if (second.idx || !first.compact || first.gate || second.gate) p.epi = kEpiSampleDense2;
     }
     int ak;
     if (nseg == 2) {

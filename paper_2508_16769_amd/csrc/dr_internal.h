@@ -83,6 +83,13 @@ void heteroconv_capacity(const dr_heteroconv* c, int64_t* cells, int64_t* nets);
 int heteroconv_create_capacity(dr_heteroconv** ctx, int64_t Nc, int64_t Nn, const int64_t E[3], int32_t D, int32_t k_near,
                                int32_t k_pins, int32_t k_self, int32_t k_pinned, bool keep_workspace);
 int heteroconv_bind(dr_heteroconv* c, const dr_csr* near, const dr_csr* pins, const dr_csr* pinned, hipStream_t s);
+// heteroconv_fwd / heteroconv_bwd with the activation of a stacked model folded in: relu_out clamps Y_cell and Y_net
+// at zero as they are written; gate_inputs zeroes dX where the layer's (already clamped) input was not positive.
+int heteroconv_forward(dr_heteroconv* c, const float* X_cell, const float* X_net, const dr_heteroconv_weights* W, float* Y_cell,
+                       float* Y_net, const dr_heteroconv_saved* S, void* stream, bool relu_out);
+int heteroconv_backward(dr_heteroconv* c, const float* dY_cell, const float* dY_net, const dr_heteroconv_weights* W,
+                        const dr_heteroconv_saved* S, float* dX_cell, float* dX_net, const dr_heteroconv_wgrads* dW, void* stream,
+                        bool gate_inputs);
 int heteroconv_create_widths(dr_heteroconv** ctx, const dr_csr* near, const dr_csr* pins, const dr_csr* pinned, int32_t D,
                              int32_t k_near, int32_t k_pins, int32_t k_self, int32_t k_pinned);
 
@@ -102,14 +109,16 @@ struct SampleSet {                // a top-k selection [rows, k] and a compact g
     const uint16_t* idx;
     int k;
     const float* compact;         // [rows, k]; may be null in `first` (nothing to add to the sampled C)
-};
+    const float* gate;            // optional [rows, k]: the selected input values; out is zeroed where they are <= 0
+};                                //   (the ReLU in front of the layer, applied to the layer's input gradient)
 // C[rows, D] = sum over segments; epilogue:
 //   kEpiStore       : out[rows,D] = C
 //   kEpiMaxMerge    : mask_out = (out >= C); out = max(out, C)        (out holds the near branch on entry)
+//   relu_out (kEpiStore, kEpiMaxMerge): what is written is clamped at zero (the mask still compares the raw values)
 //   kEpiSampleDense : out[row,:] = 0, then out[row, first.idx[row,t]] = C[row, first.idx[row,t]] + first.compact[row,t],
 //                     then (if second.idx) out[row, second.idx[row,t]] += second.compact[row,t]
 int launch_gemm(const GemmOperand* segs, int nseg, int64_t rows, int D, GemmEpilogue epi, float* out,
-                uint8_t* mask_out, SampleSet first, SampleSet second, hipStream_t s);
+                uint8_t* mask_out, SampleSet first, SampleSet second, hipStream_t s, int relu_out = 0);
 
 struct WgradOperand {             // dW[D,D] = A^T B over `rows` rows
     const float* a_dense;         // [rows, D] or nullptr

@@ -445,6 +445,19 @@ static CbsrSets cbsr_sets(const dr_heteroconv* c, const dr_heteroconv_saved* S) 
 
 int heteroconv_fwd(dr_heteroconv* c, const float* X_cell, const float* X_net, const dr_heteroconv_weights* W,
                    float* Y_cell, float* Y_net, const dr_heteroconv_saved* S, void* stream) {
+    return heteroconv_forward(c, X_cell, X_net, W, Y_cell, Y_net, S, stream, false);
+}
+
+int heteroconv_bwd(dr_heteroconv* c, const float* dY_cell, const float* dY_net, const dr_heteroconv_weights* W,
+                   const dr_heteroconv_saved* S, float* dX_cell, float* dX_net, const dr_heteroconv_wgrads* dW,
+                   void* stream) {
+    return heteroconv_backward(c, dY_cell, dY_net, W, S, dX_cell, dX_net, dW, stream, false);
+}
+
+}  // extern "C"
+
+int drc::heteroconv_forward(dr_heteroconv* c, const float* X_cell, const float* X_net, const dr_heteroconv_weights* W,
+                            float* Y_cell, float* Y_net, const dr_heteroconv_saved* S, void* stream, bool relu_out) {
     DRC_REQUIRE(c != nullptr, "heteroconv_fwd: null context");
     DRC_REQUIRE(X_cell && X_net && Y_cell && Y_net, "heteroconv_fwd: null tensor");
     DRC_REQUIRE(aligned(X_cell, 16) && aligned(X_net, 16) && aligned(Y_cell, 16) && aligned(Y_net, 16),
@@ -499,14 +512,14 @@ int heteroconv_fwd(dr_heteroconv* c, const float* X_cell, const float* X_net, co
         GemmOperand seg[2] = {};
         seg[0].cbsr_vals = q.v_self; seg[0].cbsr_idx = q.i_self; seg[0].k = c->k_self; seg[0].W = W->self_pins;
         seg[1].dense = S->H_pins; seg[1].W = W->neigh_pins;
-        { ScopedTiming tm(c, kProjPins, s_pins); DRC_TRY(launch_gemm(seg, 2, c->Nn, D, kEpiStore, Y_net, nullptr, SampleSet{}, SampleSet{}, s_pins)); }
+        { ScopedTiming tm(c, kProjPins, s_pins); DRC_TRY(launch_gemm(seg, 2, c->Nn, D, kEpiStore, Y_net, nullptr, SampleSet{}, SampleSet{}, s_pins, relu_out ? 1 : 0)); }
     }
     DRC_HIP(hipEventRecord(c->ev_pins, s_pins));
     DRC_HIP(hipStreamWaitEvent(s_pinned, c->ev_near, 0));
     {
         GemmOperand seg[1] = {};
         seg[0].dense = S->H_pinned; seg[0].W = W->pinned;
-        { ScopedTiming tm(c, kProjPinnedMerge, s_pinned); DRC_TRY(launch_gemm(seg, 1, c->Nc, D, kEpiMaxMerge, Y_cell, S->mask, SampleSet{}, SampleSet{}, s_pinned)); }
+        { ScopedTiming tm(c, kProjPinnedMerge, s_pinned); DRC_TRY(launch_gemm(seg, 1, c->Nc, D, kEpiMaxMerge, Y_cell, S->mask, SampleSet{}, SampleSet{}, s_pinned, relu_out ? 1 : 0)); }
     }
     DRC_HIP(hipEventRecord(c->ev_pinned, s_pinned));
 
@@ -515,9 +528,9 @@ int heteroconv_fwd(dr_heteroconv* c, const float* X_cell, const float* X_net, co
     return DR_OK;
 }
 
-int heteroconv_bwd(dr_heteroconv* c, const float* dY_cell, const float* dY_net, const dr_heteroconv_weights* W,
-                   const dr_heteroconv_saved* S, float* dX_cell, float* dX_net, const dr_heteroconv_wgrads* dW,
-                   void* stream) {
+int drc::heteroconv_backward(dr_heteroconv* c, const float* dY_cell, const float* dY_net, const dr_heteroconv_weights* W,
+                             const dr_heteroconv_saved* S, float* dX_cell, float* dX_net, const dr_heteroconv_wgrads* dW,
+                             void* stream, bool gate_inputs) {
     DRC_REQUIRE(c != nullptr, "heteroconv_bwd: null context");
     DRC_REQUIRE(dY_cell && dY_net && dX_cell && dX_net, "heteroconv_bwd: null tensor");
     DRC_REQUIRE(aligned(dY_cell, 16) && aligned(dY_net, 16) && aligned(dX_cell, 16) && aligned(dX_net, 16),
@@ -573,8 +586,8 @@ int heteroconv_bwd(dr_heteroconv* c, const float* dY_cell, const float* dY_net, 
         GemmOperand seg[1] = {};
         seg[0].dense = dY_cell; seg[0].mask = S->mask; seg[0].mask_keep = 1;
         seg[0].W = W->self_near; seg[0].transpose_w = 1;
-        const SampleSet first{q.i_near, c->k_near, c->dXs_cell};
-        const SampleSet second = q.cell_split ? SampleSet{q.i_pins, c->k_pins, c->dXs_cell_b} : SampleSet{};
+        const SampleSet first{q.i_near, c->k_near, c->dXs_cell, gate_inputs ? q.v_near : nullptr};
+        const SampleSet second = q.cell_split ? SampleSet{q.i_pins, c->k_pins, c->dXs_cell_b, gate_inputs ? q.v_pins : nullptr} : SampleSet{};
         { ScopedTiming tm(c, kSelfNearSample, s_pins); DRC_TRY(launch_gemm(seg, 1, c->Nc, D, kEpiSampleDense, dX_cell, nullptr, first, second, s_pins)); }
     }
     {
@@ -599,8 +612,10 @@ int heteroconv_bwd(dr_heteroconv* c, const float* dY_cell, const float* dY_net, 
     {
         GemmOperand seg[1] = {};
         seg[0].dense = dY_net; seg[0].W = W->self_pins; seg[0].transpose_w = 1;
-        const SampleSet first = q.net_split ? SampleSet{q.i_self, c->k_self, nullptr} : SampleSet{q.i_pinned, c->k_pinned, c->dXs_net};
-        const SampleSet second = q.net_split ? SampleSet{q.i_pinned, c->k_pinned, c->dXs_net} : SampleSet{};
+        const float* g_self = gate_inputs ? q.v_self : nullptr;
+        const float* g_pinned = gate_inputs ? q.v_pinned : nullptr;
+        const SampleSet first = q.net_split ? SampleSet{q.i_self, c->k_self, nullptr, g_self} : SampleSet{q.i_pinned, c->k_pinned, c->dXs_net, g_pinned};
+        const SampleSet second = q.net_split ? SampleSet{q.i_pinned, c->k_pinned, c->dXs_net, g_pinned} : SampleSet{};
         { ScopedTiming tm(c, kSelfPinsSample, s_pinned); DRC_TRY(launch_gemm(seg, 1, c->Nn, D, kEpiSampleDense, dX_net, nullptr, first, second, s_pinned)); }
     }
     {
@@ -615,5 +630,3 @@ int heteroconv_bwd(dr_heteroconv* c, const float* dY_cell, const float* dY_net, 
     DRC_HIP(hipStreamWaitEvent(user, c->ev_pinned, 0));
     return DR_OK;
 }
-
-}  // extern "C"

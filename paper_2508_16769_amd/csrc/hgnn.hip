@@ -5,7 +5,7 @@
 // that), and the streams are joined only before the parameter update.
 //
 // What is new here next to the layer is element-wise or a small reduction:
-//   relu_inplace / relu_bwd_inplace   activation and its gate, in place on the layer outputs / gradients
+//   (the ReLU between layers and its gate are folded into the layer kernels that write Y and dX)
 //   head_fwd_kernel                    one wavefront per cell: dot product, residual, loss partials
 //   head_bwd_kernel                    dY = dpred (x) w_head, per-workgroup partials of dw_head = Y^T dpred
 //   loss_reduce_kernel, adam_kernel    fixed-order sums over sub-graphs and partials, then the update
@@ -32,24 +32,6 @@ inline int head_blocks(int64_t n) {
     return (int)(b < 64 ? 64 : (b > 2048 ? 2048 : b));
 }
 constexpr int kMaxWorkers = 8;    // host threads that enqueue sub-graphs side by side
-
-__global__ __launch_bounds__(256) void relu_inplace(float4* __restrict__ y, size_t n4) {
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (size_t)gridDim.x * 256) {
-        float4 v = y[i];
-        v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f); v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f);
-        y[i] = v;
-    }
-}
-
-// dx = act > 0 ? dx : 0   (act is the ReLU output, so act > 0 exactly where its input was > 0)
-__global__ __launch_bounds__(256) void relu_bwd_inplace(float4* __restrict__ dx, const float4* __restrict__ act, size_t n4) {
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (size_t)gridDim.x * 256) {
-        float4 g = dx[i];
-        const float4 a = act[i];
-        g.x = a.x > 0.f ? g.x : 0.f; g.y = a.y > 0.f ? g.y : 0.f; g.z = a.z > 0.f ? g.z : 0.f; g.w = a.w > 0.f ? g.w : 0.f;
-        dx[i] = g;
-    }
-}
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
@@ -246,11 +228,6 @@ dr_heteroconv_wgrads layer_wgrads(float* gvec, int l, int D) {
     float* b = gvec + (size_t)l * 5 * D * D;
     const size_t dd = (size_t)D * D;
     return dr_heteroconv_wgrads{b, b + dd, b + 2 * dd, b + 3 * dd, b + 4 * dd};
-}
-
-unsigned ew_blocks(size_t n4) {
-    size_t b = (n4 + 255) / 256;
-    return (unsigned)(b > 4096 ? 4096 : (b < 1 ? 1 : b));
 }
 
 }  // namespace
@@ -484,16 +461,12 @@ int hgnn_train_step(dr_hgnn* m, const float* const* X_cell, const float* const* 
         DRC_HIP(hipStreamWaitEvent(s, m->fork, 0));
         gs.X_cell = X_cell[q]; gs.X_net = X_net[q];
         const int n = (int)gs.Nc;
-        const size_t c4 = (size_t)gs.Nc * D / 4, n4 = (size_t)gs.Nn * D / 4;
         // ---- forward ----
         const float *xc = X_cell[q], *xn = X_net[q];
         for (int l = 0; l < L; ++l) {
             const dr_heteroconv_weights W = layer_weights(theta, l, D);
-            DRC_TRY(heteroconv_fwd(gs.ctx, xc, xn, &W, gs.act_c[l], gs.act_n[l], &gs.saved[l], s));
-            if (l < L - 1) {
-                hipLaunchKernelGGL(relu_inplace, dim3(ew_blocks(c4)), dim3(256), 0, s, reinterpret_cast<float4*>(gs.act_c[l]), c4);
-                hipLaunchKernelGGL(relu_inplace, dim3(ew_blocks(n4)), dim3(256), 0, s, reinterpret_cast<float4*>(gs.act_n[l]), n4);
-            }
+            // the ReLU between layers is folded into the kernels that write the layer's outputs
+            DRC_TRY(heteroconv_forward(gs.ctx, xc, xn, &W, gs.act_c[l], gs.act_n[l], &gs.saved[l], s, l < L - 1));
             xc = gs.act_c[l]; xn = gs.act_n[l];
         }
         // ---- read-out, loss, gradient of the last layer's output ----
@@ -508,13 +481,9 @@ int hgnn_train_step(dr_hgnn* m, const float* const* X_cell, const float* const* 
         for (int l = L - 1; l >= 0; --l) {
             const dr_heteroconv_weights W = layer_weights(theta, l, D);
             const dr_heteroconv_wgrads dW = layer_wgrads(gs.gvec, l, D);
-            DRC_TRY(heteroconv_bwd(gs.ctx, gs.G_c[l + 1], gs.G_n[l + 1], &W, &gs.saved[l], gs.G_c[l], gs.G_n[l], &dW, s));
-            if (l >= 1) {   // gate by the ReLU in front of layer l: its output is the input of layer l
-                hipLaunchKernelGGL(relu_bwd_inplace, dim3(ew_blocks(c4)), dim3(256), 0, s, reinterpret_cast<float4*>(gs.G_c[l]),
-                                   reinterpret_cast<const float4*>(gs.act_c[l - 1]), c4);
-                hipLaunchKernelGGL(relu_bwd_inplace, dim3(ew_blocks(n4)), dim3(256), 0, s, reinterpret_cast<float4*>(gs.G_n[l]),
-                                   reinterpret_cast<const float4*>(gs.act_n[l - 1]), n4);
-            }
+            // layers above the first sit behind a ReLU: its gate on the input gradient is folded into the kernels
+            // that write dX (the saved D-ReLU values are the layer's inputs at every position dX can be non-zero)
+            DRC_TRY(heteroconv_backward(gs.ctx, gs.G_c[l + 1], gs.G_n[l + 1], &W, &gs.saved[l], gs.G_c[l], gs.G_n[l], &dW, s, l >= 1));
         }
         DRC_HIP(hipGetLastError());
         DRC_HIP(hipEventRecord(gs.done, s));
