@@ -310,7 +310,8 @@ typedef struct dr_hgnn_layer_buffers {        /* device pointers owned by the mo
     const float* dY_cell;                     /* [Nc,D] gradient that entered the layer's backward               */
     const float* dY_net;                      /* [Nn,D]                                                          */
     const float* dX_cell;                     /* [Nc,D] gradient the layer's backward produced; for layers > 0   */
-    const float* dX_net;                      /* [Nn,D] already gated by the ReLU in front of the layer          */
+    const float* dX_net;                      /* [Nn,D] already gated by the ReLU in front of the layer; NULL    */
+                                              /* for layer 0 unless hgnn_set_input_gradients(model, 1) was called */
     dr_heteroconv_wgrads dW;                  /* this sub-graph's share of the layer's weight gradients          */
 } dr_hgnn_layer_buffers;
 
@@ -352,6 +353,11 @@ int hgnn_train_step(dr_hgnn* model, const float* const* X_cell, const float* con
                     const float* const* target, float* theta, float* adam_m, float* adam_v,
                     double lr, double beta1, double beta2, double eps, double weight_decay, int32_t step,
                     float* grad_out, float* loss_out, void* stream);
+
+/* A training step needs no gradient of the input features, so the first layer's backward computes its weight
+ * gradients only (no dH projections, transposed SpMMs or dX write-outs).  enable != 0 makes later steps compute
+ * dX of the first layer as well (for inspection, or for a model that is itself a layer of something larger). */
+int hgnn_set_input_gradients(dr_hgnn* model, int enable);
 
 /* Buffers of sub-graph `graph`, layer `layer` (valid after a step).  pred / dpred: [Nc] of that sub-graph
  * (layer argument ignored), may be NULL. */

@@ -38,7 +38,7 @@ EXPORTS = (
     "heteroconv_set_overlap",
     "dr_pipeline_create", "dr_pipeline_submit", "dr_pipeline_acquire", "dr_pipeline_relations", "dr_pipeline_release",
     "dr_pipeline_destroy",
-    "hgnn_num_params", "hgnn_create", "hgnn_create_batched", "hgnn_train_step", "hgnn_get_layer_buffers", "hgnn_destroy",
+    "hgnn_num_params", "hgnn_create", "hgnn_create_batched", "hgnn_train_step", "hgnn_set_input_gradients", "hgnn_get_layer_buffers", "hgnn_destroy",
 )
 
 
@@ -447,6 +447,9 @@ class Hgnn:
                                       ctypes.c_double(eps), ctypes.c_double(weight_decay), ctypes.c_int32(step),
                                       _ptr(grad_out), _ptr(loss_out), _stream(stream)))
 
+    def hgnn_set_input_gradients(self, enable: bool) -> None:
+        _check(load().hgnn_set_input_gradients(self._model, ctypes.c_int(1 if enable else 0)))
+
     def hgnn_get_layer_buffers(self, graph: int, layer: int) -> Dict[str, torch.Tensor]:
         """Copies of the model's buffers for one sub-graph and layer (synchronises)."""
         torch.cuda.synchronize()
@@ -461,7 +464,8 @@ class Hgnn:
             X_cell=_view(b.X_cell, (Nc, D), f32), X_net=_view(b.X_net, (Nn, D), f32),
             Y_cell=_view(b.Y_cell, (Nc, D), f32), Y_net=_view(b.Y_net, (Nn, D), f32),
             dY_cell=_view(b.dY_cell, (Nc, D), f32), dY_net=_view(b.dY_net, (Nn, D), f32),
-            dX_cell=_view(b.dX_cell, (Nc, D), f32), dX_net=_view(b.dX_net, (Nn, D), f32),
+            dX_cell=None if not b.dX_cell else _view(b.dX_cell, (Nc, D), f32),
+            dX_net=None if not b.dX_net else _view(b.dX_net, (Nn, D), f32),
             pred=_view(pred.value, (Nc,), f32), dpred=_view(dpred.value, (Nc,), f32),
             vals_cell=_view(b.saved.vals_cell, (Nc, g.k_near), f32),
             idx_cell=_view(b.saved.idx_cell, (Nc, g.k_near), torch.int16),

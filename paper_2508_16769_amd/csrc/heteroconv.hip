@@ -451,7 +451,7 @@ int heteroconv_fwd(dr_heteroconv* c, const float* X_cell, const float* X_net, co
 int heteroconv_bwd(dr_heteroconv* c, const float* dY_cell, const float* dY_net, const dr_heteroconv_weights* W,
                    const dr_heteroconv_saved* S, float* dX_cell, float* dX_net, const dr_heteroconv_wgrads* dW,
                    void* stream) {
-    return heteroconv_backward(c, dY_cell, dY_net, W, S, dX_cell, dX_net, dW, stream, false);
+    return heteroconv_backward(c, dY_cell, dY_net, W, S, dX_cell, dX_net, dW, stream, BackwardOptions{});
 }
 
 }  // extern "C"
@@ -530,9 +530,14 @@ int drc::heteroconv_forward(dr_heteroconv* c, const float* X_cell, const float* 
 
 int drc::heteroconv_backward(dr_heteroconv* c, const float* dY_cell, const float* dY_net, const dr_heteroconv_weights* W,
                              const dr_heteroconv_saved* S, float* dX_cell, float* dX_net, const dr_heteroconv_wgrads* dW,
-                             void* stream, bool gate_inputs) {
+                             void* stream, BackwardOptions opt) {
+    // opt.skip_dx: only the weight gradients are wanted (first layer of a model: nobody reads the gradient of the
+    // input features), so the projections to dH, the transposed SpMMs and the dX write-outs are not launched.
+    // opt.dy_net_zero: dY_net holds zeros (last layer of a model whose loss reads the cells only): everything it
+    // would feed is zero, so the pins module's dH, transposed SpMM and weight-gradient kernels are replaced by fills.
+    const bool gate_inputs = opt.gate_inputs, need_dx = !opt.skip_dx, net_zero = opt.dy_net_zero;
     DRC_REQUIRE(c != nullptr, "heteroconv_bwd: null context");
-    DRC_REQUIRE(dY_cell && dY_net && dX_cell && dX_net, "heteroconv_bwd: null tensor");
+    DRC_REQUIRE(dY_cell && dY_net && (!need_dx || (dX_cell && dX_net)), "heteroconv_bwd: null tensor");
     DRC_REQUIRE(aligned(dY_cell, 16) && aligned(dY_net, 16) && aligned(dX_cell, 16) && aligned(dX_net, 16),
                 "heteroconv_bwd: misaligned tensor");
     DRC_TRY(check_weights(W, "heteroconv_bwd"));
@@ -551,14 +556,14 @@ int drc::heteroconv_backward(dr_heteroconv* c, const float* dY_cell, const float
     const CbsrSets q = cbsr_sets(c, S);
 
     // ---- near stream: dH_near, its transposed SpMM (first piece of dXs_cell), near weight gradients ----
-    {
+    if (need_dx) {
         GemmOperand seg[1] = {};
         seg[0].dense = dY_cell; seg[0].mask = S->mask; seg[0].mask_keep = 1;
         seg[0].W = W->neigh_near; seg[0].transpose_w = 1;
         { ScopedTiming tm(c, kDhNear, s_near); DRC_TRY(launch_gemm(seg, 1, c->Nc, D, kEpiStore, c->dH[0], nullptr, SampleSet{}, SampleSet{}, s_near)); }
+        { ScopedTiming tm(c, kBwdNear, s_near); DRC_TRY(launch_spmm_bwd(&c->At[0], c->dH[0], q.i_near, D, c->k_near, c->dXs_cell, 0, s_near)); }
+        DRC_HIP(hipEventRecord(c->ev_gnear, s_near));
     }
-    { ScopedTiming tm(c, kBwdNear, s_near); DRC_TRY(launch_spmm_bwd(&c->At[0], c->dH[0], q.i_near, D, c->k_near, c->dXs_cell, 0, s_near)); }
-    DRC_HIP(hipEventRecord(c->ev_gnear, s_near));
     {
         WgradOperand op = {};
         op.a_dense = S->H_near; op.b = dY_cell; op.b_mask = S->mask; op.b_mask_keep = 1;
@@ -573,24 +578,29 @@ int drc::heteroconv_backward(dr_heteroconv* c, const float* dY_cell, const float
     // ---- pins stream: dH_pins, second piece of the cell gradient, near self term, dense dX_cell, pins weight gradients.
     // With one width for the cells the pins piece is added into dXs_cell; with two it keeps its own buffer and
     // the write-out kernel adds it at its own positions. ----
-    {
+    const bool pins_piece = need_dx && !net_zero;           // the pins module's contribution to the cell gradient
+    if (pins_piece) {
         GemmOperand seg[1] = {};
         seg[0].dense = dY_net; seg[0].W = W->neigh_pins; seg[0].transpose_w = 1;
         { ScopedTiming tm(c, kDhPins, s_pins); DRC_TRY(launch_gemm(seg, 1, c->Nn, D, kEpiStore, c->dH[1], nullptr, SampleSet{}, SampleSet{}, s_pins)); }
+        if (!q.cell_split) DRC_HIP(hipStreamWaitEvent(s_pins, c->ev_gnear, 0));
+        { ScopedTiming tm(c, kBwdPins, s_pins); DRC_TRY(launch_spmm_bwd(&c->At[1], c->dH[1], q.i_pins, D, c->k_pins, q.cell_split ? c->dXs_cell_b : c->dXs_cell,
+                                                                        q.cell_split ? 0 : 1, s_pins)); }
     }
-    if (!q.cell_split) DRC_HIP(hipStreamWaitEvent(s_pins, c->ev_gnear, 0));
-    { ScopedTiming tm(c, kBwdPins, s_pins); DRC_TRY(launch_spmm_bwd(&c->At[1], c->dH[1], q.i_pins, D, c->k_pins, q.cell_split ? c->dXs_cell_b : c->dXs_cell,
-                                                                    q.cell_split ? 0 : 1, s_pins)); }
-    if (q.cell_split) DRC_HIP(hipStreamWaitEvent(s_pins, c->ev_gnear, 0));
-    {
+    if (need_dx) {
+        if (q.cell_split || !pins_piece) DRC_HIP(hipStreamWaitEvent(s_pins, c->ev_gnear, 0));
         GemmOperand seg[1] = {};
         seg[0].dense = dY_cell; seg[0].mask = S->mask; seg[0].mask_keep = 1;
         seg[0].W = W->self_near; seg[0].transpose_w = 1;
         const SampleSet first{q.i_near, c->k_near, c->dXs_cell, gate_inputs ? q.v_near : nullptr};
-        const SampleSet second = q.cell_split ? SampleSet{q.i_pins, c->k_pins, c->dXs_cell_b, gate_inputs ? q.v_pins : nullptr} : SampleSet{};
+        const SampleSet second = (q.cell_split && pins_piece) ? SampleSet{q.i_pins, c->k_pins, c->dXs_cell_b, gate_inputs ? q.v_pins : nullptr}
+                                                             : SampleSet{};
         { ScopedTiming tm(c, kSelfNearSample, s_pins); DRC_TRY(launch_gemm(seg, 1, c->Nc, D, kEpiSampleDense, dX_cell, nullptr, first, second, s_pins)); }
     }
-    {
+    if (net_zero) {
+        DRC_TRY(launch_fill_u32(reinterpret_cast<uint32_t*>(dW->neigh_pins), (size_t)D * D, 0u, s_pins));
+        DRC_TRY(launch_fill_u32(reinterpret_cast<uint32_t*>(dW->self_pins), (size_t)D * D, 0u, s_pins));
+    } else {
         WgradOperand op = {};
         op.a_dense = S->H_pins; op.b = dY_net;
         { ScopedTiming tm(c, kWgNeighPins, s_pins); DRC_TRY(launch_wgrad(op, c->Nn, D, dW->neigh_pins, c->wg_scratch[1], s_pins)); }
@@ -602,21 +612,19 @@ int drc::heteroconv_backward(dr_heteroconv* c, const float* dY_cell, const float
 
     // ---- pinned stream: dH_pinned, dXs_net, pins self term, dense dX_net, pinned weight gradient.  With two widths
     // for the nets the self term is sampled at its own selection and the pinned piece added at the other. ----
-    {
+    if (need_dx) {
         GemmOperand seg[1] = {};
         seg[0].dense = dY_cell; seg[0].mask = S->mask; seg[0].mask_keep = 0;
         seg[0].W = W->pinned; seg[0].transpose_w = 1;
         { ScopedTiming tm(c, kDhPinned, s_pinned); DRC_TRY(launch_gemm(seg, 1, c->Nc, D, kEpiStore, c->dH[2], nullptr, SampleSet{}, SampleSet{}, s_pinned)); }
-    }
-    { ScopedTiming tm(c, kBwdPinned, s_pinned); DRC_TRY(launch_spmm_bwd(&c->At[2], c->dH[2], q.i_pinned, D, c->k_pinned, c->dXs_net, 0, s_pinned)); }
-    {
-        GemmOperand seg[1] = {};
-        seg[0].dense = dY_net; seg[0].W = W->self_pins; seg[0].transpose_w = 1;
+        { ScopedTiming tm(c, kBwdPinned, s_pinned); DRC_TRY(launch_spmm_bwd(&c->At[2], c->dH[2], q.i_pinned, D, c->k_pinned, c->dXs_net, 0, s_pinned)); }
+        GemmOperand sg[1] = {};
+        sg[0].dense = dY_net; sg[0].W = W->self_pins; sg[0].transpose_w = 1;
         const float* g_self = gate_inputs ? q.v_self : nullptr;
         const float* g_pinned = gate_inputs ? q.v_pinned : nullptr;
         const SampleSet first = q.net_split ? SampleSet{q.i_self, c->k_self, nullptr, g_self} : SampleSet{q.i_pinned, c->k_pinned, c->dXs_net, g_pinned};
         const SampleSet second = q.net_split ? SampleSet{q.i_pinned, c->k_pinned, c->dXs_net, g_pinned} : SampleSet{};
-        { ScopedTiming tm(c, kSelfPinsSample, s_pinned); DRC_TRY(launch_gemm(seg, 1, c->Nn, D, kEpiSampleDense, dX_net, nullptr, first, second, s_pinned)); }
+        { ScopedTiming tm(c, kSelfPinsSample, s_pinned); DRC_TRY(launch_gemm(sg, 1, c->Nn, D, kEpiSampleDense, dX_net, nullptr, first, second, s_pinned)); }
     }
     {
         WgradOperand op = {};

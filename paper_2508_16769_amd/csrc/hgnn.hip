@@ -176,6 +176,7 @@ struct dr_hgnn {
     int n_graphs, L, D;                        // n_graphs: states that are stepped (1 for a batched model)
     int n_user;                                // sub-graphs the caller sees
     bool batched;
+    bool input_grads;                          // also compute dX of the first layer (off: only its weight gradients)
     std::vector<int64_t> off_c, off_n;         // [n_user + 1] first cell / net row of sub-graph q in the stacked graph
     std::vector<const float*> ux_c, ux_n;      // [n_user] caller's inputs of the last step (for inspection)
     dr_heteroconv* big;                        // batched: context of the stacked graph (owned)
@@ -258,7 +259,7 @@ static int create_model(dr_hgnn** model, int32_t n_graphs, dr_heteroconv* const*
     }
     dr_hgnn* m = new (std::nothrow) dr_hgnn();
     if (!m) return fail(DR_ERR_HIP, "hgnn_create: out of host memory");
-    m->n_user = n_graphs; m->batched = batched;
+    m->n_user = n_graphs; m->batched = batched; m->input_grads = false;
     m->n_graphs = batched ? 1 : n_graphs; m->L = n_layers; m->D = d0.D;
     m->PL = (int64_t)n_layers * 5 * d0.D * d0.D;
     m->n_cells_total = 0;
@@ -483,7 +484,11 @@ int hgnn_train_step(dr_hgnn* m, const float* const* X_cell, const float* const* 
             const dr_heteroconv_wgrads dW = layer_wgrads(gs.gvec, l, D);
             // layers above the first sit behind a ReLU: its gate on the input gradient is folded into the kernels
             // that write dX (the saved D-ReLU values are the layer's inputs at every position dX can be non-zero)
-            DRC_TRY(heteroconv_backward(gs.ctx, gs.G_c[l + 1], gs.G_n[l + 1], &W, &gs.saved[l], gs.G_c[l], gs.G_n[l], &dW, s, l >= 1));
+            BackwardOptions opt;
+            opt.gate_inputs = l >= 1;
+            opt.skip_dx = l == 0 && !m->input_grads;       // nobody reads the gradient of the input features
+            opt.dy_net_zero = l == L - 1;                  // the loss reads the cells only: G_n[L] is the zero fill above
+            DRC_TRY(heteroconv_backward(gs.ctx, gs.G_c[l + 1], gs.G_n[l + 1], &W, &gs.saved[l], gs.G_c[l], gs.G_n[l], &dW, s, opt));
         }
         DRC_HIP(hipGetLastError());
         DRC_HIP(hipEventRecord(gs.done, s));
@@ -547,11 +552,18 @@ int hgnn_get_layer_buffers(const dr_hgnn* m, int32_t graph, int32_t layer, dr_hg
     if (S.vals_net_self) { o.vals_net_self = S.vals_net_self + on * d.k_self; o.idx_net_self = S.idx_net_self + on * d.k_self; }
     out->dY_cell = gs.G_c[layer + 1] + oc * D;
     out->dY_net = gs.G_n[layer + 1] + on * D;
-    out->dX_cell = gs.G_c[layer] + oc * D;
-    out->dX_net = gs.G_n[layer] + on * D;
+    const bool has_dx = layer > 0 || m->input_grads;
+    out->dX_cell = has_dx ? gs.G_c[layer] + oc * D : nullptr;
+    out->dX_net = has_dx ? gs.G_n[layer] + on * D : nullptr;
     out->dW = layer_wgrads(gs.gvec, layer, m->D);       // batched: of the whole batch, whichever sub-graph is asked for
     if (pred) *pred = gs.pred + oc;
     if (dpred) *dpred = gs.dpred + oc;
+    return DR_OK;
+}
+
+int hgnn_set_input_gradients(dr_hgnn* m, int enable) {
+    DRC_REQUIRE(m != nullptr, "hgnn_set_input_gradients: null model");
+    m->input_grads = enable != 0;
     return DR_OK;
 }
 

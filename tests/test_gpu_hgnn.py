@@ -102,6 +102,7 @@ def test_train_step_parity(case):
     graphs, rels, ctxs, keep, Xc, Xn, tg, theta0 = _setup(**case)
     say(f"hgnn: {n_graphs} sub-graphs, D={D}, k={k}, L={L}")
     model = P.Hgnn(ctxs, L)
+    model.hgnn_set_input_gradients(True)              # the first layer's dX is checked too
     n_par = P.hgnn_num_params(L, D)
     theta = dev(theta0)
     m = torch.zeros(n_par, dtype=torch.float32, device="cuda")
@@ -153,6 +154,15 @@ def test_train_step_parity(case):
     assert abs(loss_gpu - free["loss"]) <= 1e-3 * free["loss"], (loss_gpu, free["loss"])
     cos = float(gg @ free["grad"] / (np.linalg.norm(gg) * np.linalg.norm(free["grad"])))
     assert cos > 0.999, cos
+    # the default model skips the first layer's input gradient (and what only feeds it): same loss, gradient and update
+    fast = P.Hgnn(ctxs, L)
+    th_f, m_f, v_f = dev(theta0), torch.zeros_like(m), torch.zeros_like(v)
+    gr_f, ls_f = torch.full_like(grad, float("nan")), torch.full_like(loss, float("nan"))
+    fast.hgnn_train_step(dXc, dXn, dtg, th_f, m_f, v_f, LR, B1, B2, EPS, WD, 1, gr_f, ls_f)
+    torch.cuda.synchronize()
+    assert torch.equal(gr_f, grad) and torch.equal(ls_f, loss) and torch.equal(th_f, theta)
+    assert fast.hgnn_get_layer_buffers(0, 0)["dX_cell"] is None and fast.hgnn_get_layer_buffers(0, L - 1)["dX_cell"] is not None or L == 1
+    fast.hgnn_destroy()
     # a second step runs from the updated state and lowers nothing it should not touch
     model.hgnn_train_step(dXc, dXn, dtg, theta, m, v, LR, B1, B2, EPS, WD, 2, grad, loss)
     torch.cuda.synchronize()
@@ -217,6 +227,7 @@ def test_train_step_with_own_k_per_subgraph():
             P.HeteroConv(*keep[2], D, 24, 24)]
     say("hgnn: three sub-graphs with their own K")
     model = P.Hgnn(ctxs, L)
+    model.hgnn_set_input_gradients(True)
     n_par = P.hgnn_num_params(L, D)
     theta = dev(theta0)
     m = torch.zeros(n_par, dtype=torch.float32, device="cuda")
@@ -437,6 +448,7 @@ def test_batched_model_stacks_the_subgraphs_on_the_device(contiguous):
     keep, ctxs = contexts(gs)
     xs = tensors()
     batched = P.Hgnn(ctxs, L, batched=True)
+    batched.hgnn_set_input_gradients(True)
     loss_b, grad_b, theta_b = run(batched, xs)
     # (a) the host-side block-diagonal graph as one sub-graph: identical launches, identical bits
     keep1, ctx1 = contexts([block_diagonal(gs)])
