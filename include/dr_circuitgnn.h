@@ -305,13 +305,13 @@ typedef struct dr_hgnn_layer_buffers {        /* device pointers owned by the mo
     const float* X_cell;                      /* [Nc,D] input of the layer (caller's X for layer 0)              */
     const float* X_net;                       /* [Nn,D]                                                          */
     const float* Y_cell;                      /* [Nc,D] output of the layer, after ReLU unless it is the last    */
-    const float* Y_net;                       /* [Nn,D]                                                          */
+    const float* Y_net;                       /* [Nn,D]; NULL (like saved.H_pins) for the last layer without inspection */
     dr_heteroconv_saved saved;                /* what the layer's forward saved                                  */
     const float* dY_cell;                     /* [Nc,D] gradient that entered the layer's backward               */
     const float* dY_net;                      /* [Nn,D]                                                          */
     const float* dX_cell;                     /* [Nc,D] gradient the layer's backward produced; for layers > 0   */
     const float* dX_net;                      /* [Nn,D] already gated by the ReLU in front of the layer; NULL    */
-                                              /* for layer 0 unless hgnn_set_input_gradients(model, 1) was called */
+                                              /* for layer 0 unless hgnn_set_inspection(model, 1) was called     */
     dr_heteroconv_wgrads dW;                  /* this sub-graph's share of the layer's weight gradients          */
 } dr_hgnn_layer_buffers;
 
@@ -354,10 +354,13 @@ int hgnn_train_step(dr_hgnn* model, const float* const* X_cell, const float* con
                     double lr, double beta1, double beta2, double eps, double weight_decay, int32_t step,
                     float* grad_out, float* loss_out, void* stream);
 
-/* A training step needs no gradient of the input features, so the first layer's backward computes its weight
- * gradients only (no dH projections, transposed SpMMs or dX write-outs).  enable != 0 makes later steps compute
- * dX of the first layer as well (for inspection, or for a model that is itself a layer of something larger). */
-int hgnn_set_input_gradients(dr_hgnn* model, int enable);
+/* A training step does not need everything a layer can compute: the gradient of the input features is read by
+ * nobody, so the first layer's backward computes its weight gradients only (no dH projections, transposed SpMMs or
+ * dX write-outs); the read-out uses the cells only, so the last layer does not evaluate its pins module (no H_pins,
+ * no Y_net), and its backward replaces what the all-zero dY_net would feed by fills.  Loss, gradient and update are
+ * the same bits either way.  enable != 0 makes later steps compute those parts as well, for inspection through
+ * hgnn_get_layer_buffers (which reports NULL for them otherwise). */
+int hgnn_set_inspection(dr_hgnn* model, int enable);
 
 /* Buffers of sub-graph `graph`, layer `layer` (valid after a step).  pred / dpred: [Nc] of that sub-graph
  * (layer argument ignored), may be NULL. */

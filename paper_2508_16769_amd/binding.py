@@ -38,7 +38,7 @@ EXPORTS = (
     "heteroconv_set_overlap",
     "dr_pipeline_create", "dr_pipeline_submit", "dr_pipeline_acquire", "dr_pipeline_relations", "dr_pipeline_release",
     "dr_pipeline_destroy",
-    "hgnn_num_params", "hgnn_create", "hgnn_create_batched", "hgnn_train_step", "hgnn_set_input_gradients", "hgnn_get_layer_buffers", "hgnn_destroy",
+    "hgnn_num_params", "hgnn_create", "hgnn_create_batched", "hgnn_train_step", "hgnn_set_inspection", "hgnn_get_layer_buffers", "hgnn_destroy",
 )
 
 
@@ -447,8 +447,8 @@ class Hgnn:
                                       ctypes.c_double(eps), ctypes.c_double(weight_decay), ctypes.c_int32(step),
                                       _ptr(grad_out), _ptr(loss_out), _stream(stream)))
 
-    def hgnn_set_input_gradients(self, enable: bool) -> None:
-        _check(load().hgnn_set_input_gradients(self._model, ctypes.c_int(1 if enable else 0)))
+    def hgnn_set_inspection(self, enable: bool) -> None:
+        _check(load().hgnn_set_inspection(self._model, ctypes.c_int(1 if enable else 0)))
 
     def hgnn_get_layer_buffers(self, graph: int, layer: int) -> Dict[str, torch.Tensor]:
         """Copies of the model's buffers for one sub-graph and layer (synchronises)."""
@@ -462,7 +462,7 @@ class Hgnn:
         f32 = torch.float32
         out = dict(
             X_cell=_view(b.X_cell, (Nc, D), f32), X_net=_view(b.X_net, (Nn, D), f32),
-            Y_cell=_view(b.Y_cell, (Nc, D), f32), Y_net=_view(b.Y_net, (Nn, D), f32),
+            Y_cell=_view(b.Y_cell, (Nc, D), f32), Y_net=None if not b.Y_net else _view(b.Y_net, (Nn, D), f32),
             dY_cell=_view(b.dY_cell, (Nc, D), f32), dY_net=_view(b.dY_net, (Nn, D), f32),
             dX_cell=None if not b.dX_cell else _view(b.dX_cell, (Nc, D), f32),
             dX_net=None if not b.dX_net else _view(b.dX_net, (Nn, D), f32),
@@ -471,7 +471,8 @@ class Hgnn:
             idx_cell=_view(b.saved.idx_cell, (Nc, g.k_near), torch.int16),
             vals_net=_view(b.saved.vals_net, (Nn, g.k_pinned), f32),
             idx_net=_view(b.saved.idx_net, (Nn, g.k_pinned), torch.int16),
-            H_near=_view(b.saved.H_near, (Nc, D), f32), H_pins=_view(b.saved.H_pins, (Nn, D), f32),
+            H_near=_view(b.saved.H_near, (Nc, D), f32),
+            H_pins=None if not b.saved.H_pins else _view(b.saved.H_pins, (Nn, D), f32),
             H_pinned=_view(b.saved.H_pinned, (Nc, D), f32), mask=_view(b.saved.mask, (Nc, D), torch.uint8),
         )
         if g.k_pins != g.k_near:

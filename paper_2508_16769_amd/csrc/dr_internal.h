@@ -83,10 +83,13 @@ void heteroconv_capacity(const dr_heteroconv* c, int64_t* cells, int64_t* nets);
 int heteroconv_create_capacity(dr_heteroconv** ctx, int64_t Nc, int64_t Nn, const int64_t E[3], int32_t D, int32_t k_near,
                                int32_t k_pins, int32_t k_self, int32_t k_pinned, bool keep_workspace);
 int heteroconv_bind(dr_heteroconv* c, const dr_csr* near, const dr_csr* pins, const dr_csr* pinned, hipStream_t s);
-// heteroconv_fwd / heteroconv_bwd with what a stacked model knows folded in: relu_out clamps Y_cell and Y_net at zero
-// as they are written; the backward options are described at BackwardOptions.
+// heteroconv_fwd / heteroconv_bwd with what a stacked model knows folded in (see ForwardOptions / BackwardOptions).
+struct ForwardOptions {
+    bool relu_out = false;          // clamp Y_cell and Y_net at zero as they are written (the mask compares raw values)
+    bool skip_net_output = false;   // Y_net (and H_pins) are not wanted: the pins module is not evaluated
+};
 int heteroconv_forward(dr_heteroconv* c, const float* X_cell, const float* X_net, const dr_heteroconv_weights* W, float* Y_cell,
-                       float* Y_net, const dr_heteroconv_saved* S, void* stream, bool relu_out);
+                       float* Y_net, const dr_heteroconv_saved* S, void* stream, ForwardOptions opt);
 struct BackwardOptions {
     bool gate_inputs = false;     // zero dX where the layer's input was not positive (ReLU in front of the layer)
     bool skip_dx = false;         // weight gradients only: dX_cell / dX_net are not written (and may be null)

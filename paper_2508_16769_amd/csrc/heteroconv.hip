@@ -445,7 +445,7 @@ static CbsrSets cbsr_sets(const dr_heteroconv* c, const dr_heteroconv_saved* S) 
 
 int heteroconv_fwd(dr_heteroconv* c, const float* X_cell, const float* X_net, const dr_heteroconv_weights* W,
                    float* Y_cell, float* Y_net, const dr_heteroconv_saved* S, void* stream) {
-    return heteroconv_forward(c, X_cell, X_net, W, Y_cell, Y_net, S, stream, false);
+    return heteroconv_forward(c, X_cell, X_net, W, Y_cell, Y_net, S, stream, ForwardOptions{});
 }
 
 int heteroconv_bwd(dr_heteroconv* c, const float* dY_cell, const float* dY_net, const dr_heteroconv_weights* W,
@@ -457,7 +457,10 @@ int heteroconv_bwd(dr_heteroconv* c, const float* dY_cell, const float* dY_net, 
 }  // extern "C"
 
 int drc::heteroconv_forward(dr_heteroconv* c, const float* X_cell, const float* X_net, const dr_heteroconv_weights* W,
-                            float* Y_cell, float* Y_net, const dr_heteroconv_saved* S, void* stream, bool relu_out) {
+                            float* Y_cell, float* Y_net, const dr_heteroconv_saved* S, void* stream, ForwardOptions opt) {
+    // opt.skip_net_output: Y_net is not wanted (last layer of a model whose read-out uses the cells only): the pins
+    // module -- its DR-SpMM and its projection -- is not launched, and H_pins / Y_net are left untouched.
+    const bool relu_out = opt.relu_out, pins_module = !opt.skip_net_output;
     DRC_REQUIRE(c != nullptr, "heteroconv_fwd: null context");
     DRC_REQUIRE(X_cell && X_net && Y_cell && Y_net, "heteroconv_fwd: null tensor");
     DRC_REQUIRE(aligned(X_cell, 16) && aligned(X_net, 16) && aligned(Y_cell, 16) && aligned(Y_net, 16),
@@ -496,7 +499,7 @@ int drc::heteroconv_forward(dr_heteroconv* c, const float* X_cell, const float* 
     }
     DRC_HIP(hipEventRecord(c->ev_topk_cell, s_near));
     DRC_HIP(hipStreamWaitEvent(s_pins, c->ev_topk_cell, 0));
-    { ScopedTiming tm(c, kFwdPins, s_pins); DRC_TRY(launch_spmm_fwd(&c->A[1], q.v_pins, q.i_pins, D, c->k_pins, S->H_pins, s_pins)); }
+    if (pins_module) { ScopedTiming tm(c, kFwdPins, s_pins); DRC_TRY(launch_spmm_fwd(&c->A[1], q.v_pins, q.i_pins, D, c->k_pins, S->H_pins, s_pins)); }
     { ScopedTiming tm(c, kFwdNear, s_near); DRC_TRY(launch_spmm_fwd(&c->A[0], q.v_near, q.i_near, D, c->k_near, S->H_near, s_near)); }
 
     // projections: near (self + neighbour), pins (self + neighbour), pinned merged into Y_cell by max
@@ -508,7 +511,7 @@ int drc::heteroconv_forward(dr_heteroconv* c, const float* X_cell, const float* 
     }
     DRC_HIP(hipEventRecord(c->ev_near, s_near));
     DRC_HIP(hipStreamWaitEvent(s_pins, c->ev_topk_net, 0));
-    {
+    if (pins_module) {
         GemmOperand seg[2] = {};
         seg[0].cbsr_vals = q.v_self; seg[0].cbsr_idx = q.i_self; seg[0].k = c->k_self; seg[0].W = W->self_pins;
         seg[1].dense = S->H_pins; seg[1].W = W->neigh_pins;

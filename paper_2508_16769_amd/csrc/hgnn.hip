@@ -176,7 +176,7 @@ struct dr_hgnn {
     int n_graphs, L, D;                        // n_graphs: states that are stepped (1 for a batched model)
     int n_user;                                // sub-graphs the caller sees
     bool batched;
-    bool input_grads;                          // also compute dX of the first layer (off: only its weight gradients)
+    bool inspect;                              // also compute what training does not need: dX of the first layer, Y_net of the last
     std::vector<int64_t> off_c, off_n;         // [n_user + 1] first cell / net row of sub-graph q in the stacked graph
     std::vector<const float*> ux_c, ux_n;      // [n_user] caller's inputs of the last step (for inspection)
     dr_heteroconv* big;                        // batched: context of the stacked graph (owned)
@@ -259,7 +259,7 @@ static int create_model(dr_hgnn** model, int32_t n_graphs, dr_heteroconv* const*
     }
     dr_hgnn* m = new (std::nothrow) dr_hgnn();
     if (!m) return fail(DR_ERR_HIP, "hgnn_create: out of host memory");
-    m->n_user = n_graphs; m->batched = batched; m->input_grads = false;
+    m->n_user = n_graphs; m->batched = batched; m->inspect = false;
     m->n_graphs = batched ? 1 : n_graphs; m->L = n_layers; m->D = d0.D;
     m->PL = (int64_t)n_layers * 5 * d0.D * d0.D;
     m->n_cells_total = 0;
@@ -467,7 +467,10 @@ int hgnn_train_step(dr_hgnn* m, const float* const* X_cell, const float* const* 
         for (int l = 0; l < L; ++l) {
             const dr_heteroconv_weights W = layer_weights(theta, l, D);
             // the ReLU between layers is folded into the kernels that write the layer's outputs
-            DRC_TRY(heteroconv_forward(gs.ctx, xc, xn, &W, gs.act_c[l], gs.act_n[l], &gs.saved[l], s, l < L - 1));
+            ForwardOptions fo;
+            fo.relu_out = l < L - 1;
+            fo.skip_net_output = l == L - 1 && !m->inspect;   // the read-out uses the cells only
+            DRC_TRY(heteroconv_forward(gs.ctx, xc, xn, &W, gs.act_c[l], gs.act_n[l], &gs.saved[l], s, fo));
             xc = gs.act_c[l]; xn = gs.act_n[l];
         }
         // ---- read-out, loss, gradient of the last layer's output ----
@@ -486,7 +489,7 @@ int hgnn_train_step(dr_hgnn* m, const float* const* X_cell, const float* const* 
             // that write dX (the saved D-ReLU values are the layer's inputs at every position dX can be non-zero)
             BackwardOptions opt;
             opt.gate_inputs = l >= 1;
-            opt.skip_dx = l == 0 && !m->input_grads;       // nobody reads the gradient of the input features
+            opt.skip_dx = l == 0 && !m->inspect;       // nobody reads the gradient of the input features
             opt.dy_net_zero = l == L - 1;                  // the loss reads the cells only: G_n[L] is the zero fill above
             DRC_TRY(heteroconv_backward(gs.ctx, gs.G_c[l + 1], gs.G_n[l + 1], &W, &gs.saved[l], gs.G_c[l], gs.G_n[l], &dW, s, opt));
         }
@@ -540,19 +543,20 @@ int hgnn_get_layer_buffers(const dr_hgnn* m, int32_t graph, int32_t layer, dr_hg
     out->X_cell = layer == 0 ? m->ux_c[graph] : gs.act_c[layer - 1] + oc * D;
     out->X_net = layer == 0 ? m->ux_n[graph] : gs.act_n[layer - 1] + on * D;
     out->Y_cell = gs.act_c[layer] + oc * D;
-    out->Y_net = gs.act_n[layer] + on * D;
+    const bool has_net_out = layer < m->L - 1 || m->inspect;
+    out->Y_net = has_net_out ? gs.act_n[layer] + on * D : nullptr;
     const dr_heteroconv_saved& S = gs.saved[layer];
     dr_heteroconv_saved& o = out->saved;
     o = dr_heteroconv_saved{};
     o.vals_cell = S.vals_cell + oc * d.k_near;   o.idx_cell = S.idx_cell + oc * d.k_near;
     o.vals_net = S.vals_net + on * d.k_pinned;   o.idx_net = S.idx_net + on * d.k_pinned;
-    o.H_near = S.H_near + oc * D; o.H_pins = S.H_pins + on * D; o.H_pinned = S.H_pinned + oc * D;
+    o.H_near = S.H_near + oc * D; o.H_pins = has_net_out ? S.H_pins + on * D : nullptr; o.H_pinned = S.H_pinned + oc * D;
     o.mask = S.mask + oc * D;
     if (S.vals_cell_pins) { o.vals_cell_pins = S.vals_cell_pins + oc * d.k_pins; o.idx_cell_pins = S.idx_cell_pins + oc * d.k_pins; }
     if (S.vals_net_self) { o.vals_net_self = S.vals_net_self + on * d.k_self; o.idx_net_self = S.idx_net_self + on * d.k_self; }
     out->dY_cell = gs.G_c[layer + 1] + oc * D;
     out->dY_net = gs.G_n[layer + 1] + on * D;
-    const bool has_dx = layer > 0 || m->input_grads;
+    const bool has_dx = layer > 0 || m->inspect;
     out->dX_cell = has_dx ? gs.G_c[layer] + oc * D : nullptr;
     out->dX_net = has_dx ? gs.G_n[layer] + on * D : nullptr;
     out->dW = layer_wgrads(gs.gvec, layer, m->D);       // batched: of the whole batch, whichever sub-graph is asked for
@@ -561,9 +565,9 @@ int hgnn_get_layer_buffers(const dr_hgnn* m, int32_t graph, int32_t layer, dr_hg
     return DR_OK;
 }
 
-int hgnn_set_input_gradients(dr_hgnn* m, int enable) {
-    DRC_REQUIRE(m != nullptr, "hgnn_set_input_gradients: null model");
-    m->input_grads = enable != 0;
+int hgnn_set_inspection(dr_hgnn* m, int enable) {
+    DRC_REQUIRE(m != nullptr, "hgnn_set_inspection: null model");
+    m->inspect = enable != 0;
     return DR_OK;
 }
 
