@@ -712,8 +712,18 @@ __global__ __launch_bounds__(512) void wgrad_reduce_kernel(const float* __restri
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int q = blockIdx.x * 64 + lane;
     float s = 0.0f;
-    if (q < dd)
-        for (int b = wave; b < nb; b += 8) s += scratch[(size_t)b * dd + q];
+    if (q < dd) {
+        // eight loads in flight at a time (the adds keep their order): the kernel is bound by load latency otherwise
+        int b = wave;
+        for (; b + 56 < nb; b += 64) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = scratch[(size_t)(b + 8 * u) * dd + q];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s += v[u];
+        }
+        for (; b < nb; b += 8) s += scratch[(size_t)b * dd + q];
+    }
     part[wave][lane] = s;
     __syncthreads();
     if (wave == 0 && q < dd) {

@@ -99,10 +99,27 @@ __global__ __launch_bounds__(64) void loss_reduce_kernel(const float* __restrict
     if (threadIdx.x == 0) *loss_out = s * inv_n;
 }
 
+// dwh[c] = sum over all read-out partials (fixed order: thread t takes partials t, t + 256, ..., then a tree over
+// the 256 thread sums); one workgroup per column
+__global__ __launch_bounds__(256) void head_reduce_kernel(const float* __restrict__ dwh_part, int n_parts, int D,
+                                                          float* __restrict__ dwh) {
+    __shared__ float sh[256];
+    const int c = blockIdx.x;
+    float s = 0.f;
+    for (int q = threadIdx.x; q < n_parts; q += 256) s += dwh_part[(size_t)q * D + c];
+    sh[threadIdx.x] = s;
+    __syncthreads();
+    for (int w = 128; w >= 1; w >>= 1) {
+        if ((int)threadIdx.x < w) sh[threadIdx.x] += sh[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) dwh[c] = sh[0];
+}
+
 // g = sum over sub-graphs (fixed order) of the gradient pieces; Adam with L2 weight decay, bias-corrected
 __global__ __launch_bounds__(256) void adam_kernel(float* __restrict__ theta, float* __restrict__ m, float* __restrict__ v,
                                                    float* __restrict__ grad_out, const float* __restrict__ gall,
-                                                   const float* __restrict__ dwh_part, int n_graphs, int n_head_parts, int64_t PL, int D,
+                                                   const float* __restrict__ dwh, int n_graphs, int64_t PL, int D,
                                                    float lr, float beta1, float beta2, float omb1, float omb2,
                                                    float eps, float wd, float inv_bc1, float inv_bc2) {
     const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -111,8 +128,7 @@ __global__ __launch_bounds__(256) void adam_kernel(float* __restrict__ theta, fl
     if (e < PL) {
         for (int q = 0; q < n_graphs; ++q) g += gall[(size_t)q * PL + e];
     } else {
-        const int c = (int)(e - PL);
-        for (int q = 0; q < n_head_parts; ++q) g += dwh_part[(size_t)q * D + c];
+        g = dwh[e - PL];
     }
     grad_out[e] = g;
     const float th = theta[e];
@@ -186,7 +202,7 @@ struct dr_hgnn {
     int64_t n_cells_total;
     std::vector<drc::GraphState> g;
     std::vector<void*> owned;
-    float *gall, *loss_part, *dwh_part;
+    float *gall, *loss_part, *dwh_part, *dwh;  // dwh[D]: the read-out weight gradient, summed over all partials
     int n_head_parts;                          // read-out partials of all states together
     hipEvent_t fork;
     int device;
@@ -263,7 +279,7 @@ static int create_model(dr_hgnn** model, int32_t n_graphs, dr_heteroconv* const*
     m->n_graphs = batched ? 1 : n_graphs; m->L = n_layers; m->D = d0.D;
     m->PL = (int64_t)n_layers * 5 * d0.D * d0.D;
     m->n_cells_total = 0;
-    m->gall = m->loss_part = m->dwh_part = nullptr;
+    m->gall = m->loss_part = m->dwh_part = m->dwh = nullptr;
     m->Xc_all = m->Xn_all = m->tg_all = nullptr;
     m->big = nullptr;
     m->fork = nullptr;
@@ -328,6 +344,7 @@ static int create_model(dr_hgnn** model, int32_t n_graphs, dr_heteroconv* const*
         for (int q = 0; q < ns; ++q) m->n_head_parts += head_blocks(cap_cells(q));
         DRC_TRY(alloc_t(m, &m->loss_part, (size_t)m->n_head_parts));
         DRC_TRY(alloc_t(m, &m->dwh_part, (size_t)m->n_head_parts * m->D));
+        DRC_TRY(alloc_t(m, &m->dwh, (size_t)m->D));
         int part0 = 0;
         for (int q = 0; q < ns; ++q) {
             GraphState& gs = m->g[q];
@@ -520,11 +537,12 @@ int hgnn_train_step(dr_hgnn* m, const float* const* X_cell, const float* const* 
     // ---- loss and parameter update, after every sub-graph has delivered its gradient ----
     hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(kWave), 0, user, m->loss_part, m->n_head_parts,
                        (float)(1.0 / (double)m->n_cells_total), loss_out);
+    hipLaunchKernelGGL(head_reduce_kernel, dim3((unsigned)D), dim3(256), 0, user, m->dwh_part, m->n_head_parts, D, m->dwh);
     const int64_t P = m->PL + D;
     const float inv_bc1 = (float)(1.0 / (1.0 - std::pow(beta1, (double)step)));
     const float inv_bc2 = (float)(1.0 / (1.0 - std::pow(beta2, (double)step)));
     hipLaunchKernelGGL(adam_kernel, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, user, theta, adam_m, adam_v, grad_out,
-                       m->gall, m->dwh_part, m->n_graphs, m->n_head_parts, m->PL, D, (float)lr, (float)beta1, (float)beta2, (float)(1.0 - beta1),
+                       m->gall, m->dwh, m->n_graphs, m->PL, D, (float)lr, (float)beta1, (float)beta2, (float)(1.0 - beta1),
                        (float)(1.0 - beta2), (float)eps, (float)weight_decay, inv_bc1, inv_bc2);
     DRC_HIP(hipGetLastError());
     return DR_OK;
