@@ -554,44 +554,53 @@ struct WgradParams {
     float* scratch;
 };
 
-template <int NT, bool ACBSR, bool MASKED>
-__global__ __launch_bounds__(kPT, (NT == 4 ? 3 : 2)) void wgrad_partial_kernel(WgradParams p) {
+// AK: 0 = A dense, 1 = A as CBSR, 2 = both at once against the same B (two products, two partials: the dense
+// operand's first, the CBSR operand's nb partials after it)
+template <int NT, int AK, bool MASKED>
+__global__ __launch_bounds__(kPT, (NT == 4 && AK != 2 ? 3 : 2)) void wgrad_partial_kernel(WgradParams p) {
+    constexpr bool ADENSE = AK != 1, ACBSR = AK != 0;
+    constexpr int NA = AK == 2 ? 2 : 1;          // products accumulated
     constexpr int kWgRC = wg_rows(NT);           // shadows the slab granule: rows per staged chunk here
     constexpr int kWgTPR = kPT / kWgRC;          // threads sharing one chunk row when A arrives as CBSR
     constexpr int D = NT * 32;
     constexpr int LD = D + 4;
     constexpr int F4 = kWgRC * D / 4 / kPT;      // float4 per thread per operand chunk
+    constexpr int kBuf = (NA + 1) * kWgRC * LD;  // one staging buffer: dense A | B | CBSR A (when both)
     extern __shared__ __align__(16) float smem[];
-    float* const sA0 = smem;
-    float* const sB0 = sA0 + kWgRC * LD;
-    float* const sA1 = sB0 + kWgRC * LD;
-    float* const sB1 = sA1 + kWgRC * LD;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int rb = blockIdx.x * p.rows_per_block;
     const int re = min(rb + p.rows_per_block, p.rows);
     const bool mm = wave < NT;                   // wavefront w owns dW rows [32w, 32w+32)
     const int prow = tid / kWgTPR, ppart = tid % kWgTPR;
 
-    floatx16 acc[NT];
+    floatx16 acc[NA][NT];
 #pragma unroll
-    for (int j = 0; j < NT; ++j)
+    for (int a = 0; a < NA; ++a)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[j][r] = 0.0f;
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][j][r] = 0.0f;
 
-    // loads only (mask bytes raw); masking and range checks happen when the chunk is written to LDS
-    float4 preA[F4], preB[F4];
-    uint32_t prem[F4];
-    float pv[kWgCP];
-    uint32_t pc[kWgCP];
-    auto prefetch = [&](int rr) {
+    // loads only (mask bytes raw); masking and range checks happen when the chunk is written to LDS.  Two register
+    // sets: a chunk's loads are issued two chunks ahead of its multiply (a whole multiply phase lies between a load
+    // and the LDS write that consumes it, which covers the memory latency under load); rows past the slab's end
+    // are clamped, so every load and every LDS write is unconditional.
+    struct Pre {
+        float4 a[F4], b[F4];
+        uint32_t m[F4];
+        float pv[kWgCP];
+        uint32_t pc[kWgCP];
+    };
+    Pre P0, P1;
+    auto prefetch = [&](int rr, Pre& P) {
 #pragma unroll
         for (int it = 0; it < F4; ++it) {
             const int q = it * kPT + tid;
             const int row = q / (D / 4), c4 = (q % (D / 4)) * 4;
             const size_t off = (size_t)min(rr + row, re - 1) * D + c4;
-            preB[it] = *reinterpret_cast<const float4*>(p.op.b + off);
-            if (MASKED) prem[it] = *reinterpret_cast<const uint32_t*>(p.op.b_mask + off);
-            if (!ACBSR) preA[it] = *reinterpret_cast<const float4*>(p.op.a_dense + off);
+            P.b[it] = *reinterpret_cast<const float4*>(p.op.b + off);
+            if (MASKED) P.m[it] = *reinterpret_cast<const uint32_t*>(p.op.b_mask + off);
+            if (ADENSE) P.a[it] = *reinterpret_cast<const float4*>(p.op.a_dense + off);
         }
         if (ACBSR) {
             const int k = p.op.k;
@@ -599,12 +608,15 @@ __global__ __launch_bounds__(kPT, (NT == 4 ? 3 : 2)) void wgrad_partial_kernel(W
 #pragma unroll
             for (int u = 0; u < kWgCP; ++u) {
                 const int t = min(ppart + kWgTPR * u, k - 1);
-                pv[u] = p.op.a_cbsr_vals[base + t];
-                pc[u] = p.op.a_cbsr_idx[base + t];
+                P.pv[u] = p.op.a_cbsr_vals[base + t];
+                P.pc[u] = p.op.a_cbsr_idx[base + t];
             }
         }
     };
-    auto commit = [&](int rr, float* sA, float* sB) {
+    auto commit = [&](int rr, float* buf, const Pre& P) {
+        float* const sA = buf;
+        float* const sB = buf + kWgRC * LD;
+        float* const sC = buf + (NA == 2 ? 2 * kWgRC * LD : 0);
         const uint32_t keep = (uint32_t)p.op.b_mask_keep;
         const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
@@ -612,9 +624,9 @@ __global__ __launch_bounds__(kPT, (NT == 4 ? 3 : 2)) void wgrad_partial_kernel(W
             const int q = it * kPT + tid;
             const int row = q / (D / 4), c4 = (q % (D / 4)) * 4;
             const bool in = rr + row < re;
-            float4 vb = preB[it];
+            float4 vb = P.b[it];
             if (MASKED) {
-                const uint32_t m = prem[it];
+                const uint32_t m = P.m[it];
                 vb.x = (((m >> 0) & 0xffu) == keep) ? vb.x : 0.f;
                 vb.y = (((m >> 8) & 0xffu) == keep) ? vb.y : 0.f;
                 vb.z = (((m >> 16) & 0xffu) == keep) ? vb.z : 0.f;
@@ -622,8 +634,8 @@ __global__ __launch_bounds__(kPT, (NT == 4 ? 3 : 2)) void wgrad_partial_kernel(W
             }
             if (!in) vb = make_float4(0.f, 0.f, 0.f, 0.f);
             *reinterpret_cast<float4*>(sB + row * LD + c4) = vb;
-            if (!ACBSR) {
-                float4 va = preA[it];
+            if (ADENSE) {
+                float4 va = P.a[it];
                 if (!in) va = make_float4(0.f, 0.f, 0.f, 0.f);
                 *reinterpret_cast<float4*>(sA + row * LD + c4) = va;
             }
@@ -632,7 +644,7 @@ __global__ __launch_bounds__(kPT, (NT == 4 ? 3 : 2)) void wgrad_partial_kernel(W
             // row-owned: the kWgTPR threads of a row share a wavefront, which zeroes the row and then
             // scatters the pairs into it (LDS keeps a wavefront's accesses in order); every write is
             // unconditional, pairs past k go to the padding column
-            float* rowp = sA + prow * LD;
+            float* rowp = sC + prow * LD;
 #pragma unroll
             for (int i = 0; i < D / kWgTPR / 4; ++i)
                 *reinterpret_cast<float4*>(rowp + ppart * (D / kWgTPR) + 4 * i) = z;
@@ -642,7 +654,7 @@ __global__ __launch_bounds__(kPT, (NT == 4 ? 3 : 2)) void wgrad_partial_kernel(W
 #pragma unroll
             for (int u = 0; u < kWgCP; ++u) {
                 const int t = ppart + kWgTPR * u;
-                rowp[t < k ? (int)pc[u] : D] = rin ? pv[u] : 0.f;
+                rowp[t < k ? (int)P.pc[u] : D] = rin ? P.pv[u] : 0.f;
             }
             const size_t base = (size_t)min(rr + prow, re - 1) * k;
             for (int u = kWgCP; u * kWgTPR < k; ++u) {
@@ -653,54 +665,74 @@ __global__ __launch_bounds__(kPT, (NT == 4 ? 3 : 2)) void wgrad_partial_kernel(W
             }
         }
     };
-
-    if (rb < re) {
-        int cur = 0;
-        prefetch(rb);
-        commit(rb, sA0, sB0);
-        __syncthreads();
-        for (int rr = rb; rr < re; rr += kWgRC) {
-            const bool has_next = rr + kWgRC < re;
-            const float* sA = cur ? sA1 : sA0;
-            const float* sB = cur ? sB1 : sB0;
-            if (has_next) prefetch(rr + kWgRC);
-            __builtin_amdgcn_sched_barrier(0);   // consumers of the prefetched registers stay below the multiply
-            if (mm) {
-                // operands of k-step i+1 are read from LDS before the MFMAs of k-step i are issued
-                const float* pa = sA + (lane >> 5) * LD + wave * 32 + (lane & 31);
-                const float* pb = sB + (lane >> 5) * LD + (lane & 31);
-                float av[2], b[2][NT];
-                av[0] = pa[0];
+    auto multiply = [&](const float* buf) {
+        if (mm) {
+            // operands of k-step i+1 are read from LDS before the MFMAs of k-step i are issued
+            const float* pa = buf + (lane >> 5) * LD + wave * 32 + (lane & 31);
+            const float* pb = buf + kWgRC * LD + (lane >> 5) * LD + (lane & 31);
+            float av[2][NA], b[2][NT];
 #pragma unroll
-                for (int j = 0; j < NT; ++j) b[0][j] = pb[j * 32];
+            for (int a = 0; a < NA; ++a) av[0][a] = pa[a * 2 * kWgRC * LD];
 #pragma unroll
-                for (int i = 0; i < kWgRC / 2; ++i) {
-                    if (i + 1 < kWgRC / 2) {
-                        av[(i + 1) & 1] = pa[(2 * i + 2) * LD];
+            for (int j = 0; j < NT; ++j) b[0][j] = pb[j * 32];
 #pragma unroll
-                        for (int j = 0; j < NT; ++j) b[(i + 1) & 1][j] = pb[(2 * i + 2) * LD + j * 32];
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
+            for (int i = 0; i < kWgRC / 2; ++i) {
+                if (i + 1 < kWgRC / 2) {
+#pragma unroll
+                    for (int a = 0; a < NA; ++a) av[(i + 1) & 1][a] = pa[a * 2 * kWgRC * LD + (2 * i + 2) * LD];
+#pragma unroll
+                    for (int j = 0; j < NT; ++j) b[(i + 1) & 1][j] = pb[(2 * i + 2) * LD + j * 32];
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int a = 0; a < NA; ++a)
 #pragma unroll
                     for (int j = 0; j < NT; ++j)
-                        acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i & 1], b[i & 1][j], acc[j], 0, 0, 0);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
+                        acc[a][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i & 1][a], b[i & 1][j], acc[a][j], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
             }
-            __builtin_amdgcn_sched_barrier(0);
-            if (has_next) commit(rr + kWgRC, cur ? sA0 : sA1, cur ? sB0 : sB1);
-            __syncthreads();
-            cur ^= 1;
         }
+    };
+
+    if (rb < re) {
+        float* const buf0 = smem;
+        float* const buf1 = smem + kBuf;
+        prefetch(rb, P0);
+        prefetch(rb + kWgRC, P1);
+        commit(rb, buf0, P0);
+        __syncthreads();
+        // buf0 holds chunk rr, P1 the loads of chunk rr + kWgRC; sched_barriers keep the consumers of the
+        // prefetched registers below the multiply
+        // (two chunks per trip, one exit at the bottom: the register sets stay where they are across the back edge;
+        // a slab with an odd number of chunks stages one chunk of zeros and skips its multiply)
+        int rr = rb;
+        do {
+            prefetch(rr + 2 * kWgRC, P0);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(buf0);
+            __builtin_amdgcn_sched_barrier(0);
+            commit(rr + kWgRC, buf1, P1);
+            __syncthreads();
+            prefetch(rr + 3 * kWgRC, P1);
+            __builtin_amdgcn_sched_barrier(0);
+            if (rr + kWgRC < re) multiply(buf1);
+            __builtin_amdgcn_sched_barrier(0);
+            commit(rr + 2 * kWgRC, buf0, P0);
+            __syncthreads();
+            rr += 2 * kWgRC;
+        } while (rr < re);
     }
 
-    float* out = p.scratch + (size_t)blockIdx.x * D * D;
     if (mm) {
 #pragma unroll
-        for (int j = 0; j < NT; ++j)
+        for (int a = 0; a < NA; ++a) {
+            float* out = p.scratch + ((size_t)a * gridDim.x + blockIdx.x) * D * D;
 #pragma unroll
-            for (int r = 0; r < 16; ++r)
-                out[(size_t)(wave * 32 + mfma_row(lane, r)) * D + j * 32 + (lane & 31)] = acc[j][r];
+            for (int j = 0; j < NT; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    out[(size_t)(wave * 32 + mfma_row(lane, r)) * D + j * 32 + (lane & 31)] = acc[a][j][r];
+        }
     }
 }
 
@@ -741,32 +773,39 @@ static int wgrad_blocks(int64_t rows) {
     return (int)nb;
 }
 
-size_t wgrad_scratch_bytes(int64_t rows, int D) { return sizeof(float) * (size_t)wgrad_blocks(rows) * D * D; }
+// room for the two partial sets of a paired launch
+size_t wgrad_scratch_bytes(int64_t rows, int D) { return sizeof(float) * 2 * (size_t)wgrad_blocks(rows) * D * D; }
 
-template <int NT, bool ACBSR, bool MASKED>
+template <int NT, int AK, bool MASKED>
 static int launch_wgrad_kernel(const WgradParams& p, int nb, hipStream_t s) {
-    constexpr size_t lds = sizeof(float) * 4 * wg_rows(NT) * (NT * 32 + 4);
+    constexpr size_t lds = sizeof(float) * 2 * (AK == 2 ? 3 : 2) * wg_rows(NT) * (NT * 32 + 4);
     static std::atomic<bool> configured{false};
     if (!configured.load(std::memory_order_acquire)) {
-        DRC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&wgrad_partial_kernel<NT, ACBSR, MASKED>),
+        DRC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&wgrad_partial_kernel<NT, AK, MASKED>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         configured.store(true, std::memory_order_release);
     }
-    hipLaunchKernelGGL((wgrad_partial_kernel<NT, ACBSR, MASKED>), dim3((unsigned)nb), dim3(kPT), lds, s, p);
+    hipLaunchKernelGGL((wgrad_partial_kernel<NT, AK, MASKED>), dim3((unsigned)nb), dim3(kPT), lds, s, p);
     DRC_HIP(hipGetLastError());
     return DR_OK;
 }
 
 template <int NT>
 static int launch_wgrad_nt(const WgradParams& p, int nb, hipStream_t s) {
-    const bool cbsr = p.op.a_dense == nullptr, masked = p.op.b_mask != nullptr;
-    if (cbsr) return masked ? launch_wgrad_kernel<NT, true, true>(p, nb, s) : launch_wgrad_kernel<NT, true, false>(p, nb, s);
-    return masked ? launch_wgrad_kernel<NT, false, true>(p, nb, s) : launch_wgrad_kernel<NT, false, false>(p, nb, s);
+    const bool dense = p.op.a_dense != nullptr, cbsr = p.op.a_cbsr_vals != nullptr, masked = p.op.b_mask != nullptr;
+    if (dense && cbsr) return masked ? launch_wgrad_kernel<NT, 2, true>(p, nb, s) : launch_wgrad_kernel<NT, 2, false>(p, nb, s);
+    if (cbsr) return masked ? launch_wgrad_kernel<NT, 1, true>(p, nb, s) : launch_wgrad_kernel<NT, 1, false>(p, nb, s);
+    return masked ? launch_wgrad_kernel<NT, 0, true>(p, nb, s) : launch_wgrad_kernel<NT, 0, false>(p, nb, s);
 }
 
-int launch_wgrad(const WgradOperand& op, int64_t rows, int D, float* dW, void* scratch, hipStream_t s) {
-    if (!op.a_dense && (!op.a_cbsr_vals || !op.a_cbsr_idx || op.k < 1))
-        return fail(DR_ERR_INVALID_ARG, "weight gradient without an A operand");
+// dW = A^T B.  With both a dense and a CBSR A operand in `op` the two products are formed in one pass over B:
+// the dense operand's goes to dW, the CBSR operand's to dW_cbsr (unused otherwise).
+int launch_wgrad(const WgradOperand& op, int64_t rows, int D, float* dW, float* dW_cbsr, void* scratch, hipStream_t s) {
+    const bool cbsr = op.a_cbsr_vals != nullptr;
+    if (cbsr && (!op.a_cbsr_idx || op.k < 1)) return fail(DR_ERR_INVALID_ARG, "weight gradient: incomplete CBSR operand");
+    if (!op.a_dense && !cbsr) return fail(DR_ERR_INVALID_ARG, "weight gradient without an A operand");
+    const bool pair = op.a_dense && cbsr;
+    if (pair && !dW_cbsr) return fail(DR_ERR_INVALID_ARG, "paired weight gradient without its second output");
     int nb = wgrad_blocks(rows);
     int rpb = (int)((rows + nb - 1) / nb);
     rpb = (rpb + kWgRC - 1) / kWgRC * kWgRC;
@@ -786,6 +825,9 @@ int launch_wgrad(const WgradOperand& op, int64_t rows, int D, float* dW, void* s
     const int dd = D * D;
     hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((dd + 63) / 64)), dim3(512), 0, s,
                        static_cast<float*>(scratch), nb, dd, dW);
+    if (pair)
+        hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((dd + 63) / 64)), dim3(512), 0, s,
+                           static_cast<float*>(scratch) + (size_t)nb * dd, nb, dd, dW_cbsr);
     DRC_HIP(hipGetLastError());
     return DR_OK;
 }

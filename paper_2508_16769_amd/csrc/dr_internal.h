@@ -138,6 +138,6 @@ struct WgradOperand {             // dW[D,D] = A^T B over `rows` rows
     int b_mask_keep;
 };
 size_t wgrad_scratch_bytes(int64_t rows, int D);
-int launch_wgrad(const WgradOperand& op, int64_t rows, int D, float* dW, void* scratch, hipStream_t s);
+int launch_wgrad(const WgradOperand& op, int64_t rows, int D, float* dW, float* dW_cbsr, void* scratch, hipStream_t s);
 
 }  // namespace drc

@@ -11,14 +11,14 @@ namespace {
 // kernel ids for the optional per-kernel timing (heteroconv_profile / heteroconv_kernel_times)
 enum KernelId {
     kTopkCell, kTopkNet, kFwdNear, kFwdPins, kFwdPinned, kProjNear, kProjPins, kProjPinnedMerge,
-    kDhNear, kBwdNear, kWgNeighNear, kWgSelfNear, kDhPins, kBwdPins, kSelfNearSample,
-    kWgNeighPins, kWgSelfPins, kDhPinned, kBwdPinned, kSelfPinsSample, kWgPinned, kNumKernels
+    kDhNear, kBwdNear, kWgNear, kDhPins, kBwdPins, kSelfNearSample,
+    kWgPins, kDhPinned, kBwdPinned, kSelfPinsSample, kWgPinned, kNumKernels
 };
 const char* const kKernelNames[kNumKernels] = {
     "dr_topk.cell", "dr_topk.net", "dr_spmm_fwd.near", "dr_spmm_fwd.pins", "dr_spmm_fwd.pinned",
     "proj.near", "proj.pins", "proj.pinned+merge",
-    "dproj.near", "dr_spmm_bwd.near", "wgrad.neigh_near", "wgrad.self_near", "dproj.pins", "dr_spmm_bwd.pins",
-    "dself.near+dX", "wgrad.neigh_pins", "wgrad.self_pins", "dproj.pinned",
+    "dproj.near", "dr_spmm_bwd.near", "wgrad.near", "dproj.pins", "dr_spmm_bwd.pins",
+    "dself.near+dX", "wgrad.pins", "dproj.pinned",
     "dr_spmm_bwd.pinned", "dself.pins+dX", "wgrad.pinned"};
 struct TimedLaunch { int id; hipEvent_t start, stop; bool start_shared; };   // start_shared: start is the previous launch's stop
 }  // namespace
@@ -568,13 +568,11 @@ int drc::heteroconv_backward(dr_heteroconv* c, const float* dY_cell, const float
         DRC_HIP(hipEventRecord(c->ev_gnear, s_near));
     }
     {
+        // both near weight gradients share dZ_near: one pass forms H_near^T dZ and Xs_cell^T dZ together
         WgradOperand op = {};
-        op.a_dense = S->H_near; op.b = dY_cell; op.b_mask = S->mask; op.b_mask_keep = 1;
-        { ScopedTiming tm(c, kWgNeighNear, s_near); DRC_TRY(launch_wgrad(op, c->Nc, D, dW->neigh_near, c->wg_scratch[0], s_near)); }
-        WgradOperand os = {};
-        os.a_cbsr_vals = q.v_near; os.a_cbsr_idx = q.i_near; os.k = c->k_near;
-        os.b = dY_cell; os.b_mask = S->mask; os.b_mask_keep = 1;
-        { ScopedTiming tm(c, kWgSelfNear, s_near); DRC_TRY(launch_wgrad(os, c->Nc, D, dW->self_near, c->wg_scratch[0], s_near)); }
+        op.a_dense = S->H_near; op.a_cbsr_vals = q.v_near; op.a_cbsr_idx = q.i_near; op.k = c->k_near;
+        op.b = dY_cell; op.b_mask = S->mask; op.b_mask_keep = 1;
+        { ScopedTiming tm(c, kWgNear, s_near); DRC_TRY(launch_wgrad(op, c->Nc, D, dW->neigh_near, dW->self_near, c->wg_scratch[0], s_near)); }
     }
     DRC_HIP(hipEventRecord(c->ev_near, s_near));
 
@@ -605,11 +603,8 @@ int drc::heteroconv_backward(dr_heteroconv* c, const float* dY_cell, const float
         DRC_TRY(launch_fill_u32(reinterpret_cast<uint32_t*>(dW->self_pins), (size_t)D * D, 0u, s_pins));
     } else {
         WgradOperand op = {};
-        op.a_dense = S->H_pins; op.b = dY_net;
-        { ScopedTiming tm(c, kWgNeighPins, s_pins); DRC_TRY(launch_wgrad(op, c->Nn, D, dW->neigh_pins, c->wg_scratch[1], s_pins)); }
-        WgradOperand os = {};
-        os.a_cbsr_vals = q.v_self; os.a_cbsr_idx = q.i_self; os.k = c->k_self; os.b = dY_net;
-        { ScopedTiming tm(c, kWgSelfPins, s_pins); DRC_TRY(launch_wgrad(os, c->Nn, D, dW->self_pins, c->wg_scratch[1], s_pins)); }
+        op.a_dense = S->H_pins; op.a_cbsr_vals = q.v_self; op.a_cbsr_idx = q.i_self; op.k = c->k_self; op.b = dY_net;
+        { ScopedTiming tm(c, kWgPins, s_pins); DRC_TRY(launch_wgrad(op, c->Nn, D, dW->neigh_pins, dW->self_pins, c->wg_scratch[1], s_pins)); }
     }
     DRC_HIP(hipEventRecord(c->ev_pins, s_pins));
 
@@ -632,7 +627,7 @@ int drc::heteroconv_backward(dr_heteroconv* c, const float* dY_cell, const float
     {
         WgradOperand op = {};
         op.a_dense = S->H_pinned; op.b = dY_cell; op.b_mask = S->mask; op.b_mask_keep = 0;
-        { ScopedTiming tm(c, kWgPinned, s_pinned); DRC_TRY(launch_wgrad(op, c->Nc, D, dW->pinned, c->wg_scratch[2], s_pinned)); }
+        { ScopedTiming tm(c, kWgPinned, s_pinned); DRC_TRY(launch_wgrad(op, c->Nc, D, dW->pinned, nullptr, c->wg_scratch[2], s_pinned)); }
     }
     DRC_HIP(hipEventRecord(c->ev_pinned, s_pinned));
 

@@ -32,12 +32,10 @@ SCHEDULE = (
     ("dr_topk.cell", "topk_rows"), ("dr_spmm_fwd.pins", "spmm_fwd"), ("dr_spmm_fwd.near", "spmm_fwd"),
     ("proj.near", "proj_kernel"), ("proj.pins", "proj_kernel"), ("proj.pinned+merge", "proj_kernel"),
     ("dproj.near", "proj_kernel"), ("dr_spmm_bwd.near", "spmm_bwd"),
-    ("wgrad.neigh_near", "wgrad_partial"), ("wgrad.neigh_near.reduce", "wgrad_reduce"),
-    ("wgrad.self_near", "wgrad_partial"), ("wgrad.self_near.reduce", "wgrad_reduce"),
+    ("wgrad.near", "wgrad_partial"), ("wgrad.near.reduce_neigh", "wgrad_reduce"), ("wgrad.near.reduce_self", "wgrad_reduce"),
     ("dproj.pins", "proj_kernel"), ("dr_spmm_bwd.pins", "spmm_bwd"),
     ("dself.near+dX", "proj_kernel"),
-    ("wgrad.neigh_pins", "wgrad_partial"), ("wgrad.neigh_pins.reduce", "wgrad_reduce"),
-    ("wgrad.self_pins", "wgrad_partial"), ("wgrad.self_pins.reduce", "wgrad_reduce"),
+    ("wgrad.pins", "wgrad_partial"), ("wgrad.pins.reduce_neigh", "wgrad_reduce"), ("wgrad.pins.reduce_self", "wgrad_reduce"),
     ("dproj.pinned", "proj_kernel"), ("dr_spmm_bwd.pinned", "spmm_bwd"),
     ("dself.pins+dX", "proj_kernel"),
     ("wgrad.pinned", "wgrad_partial"), ("wgrad.pinned.reduce", "wgrad_reduce"),
