@@ -17,8 +17,10 @@ namespace drc {
 
 __device__ __forceinline__ uint32_t order_key(float v) {
     uint32_t u = __float_as_uint(v);
-    if (u == 0x80000000u) u = 0u;                       // -0.0 ties with +0.0
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);  // larger float <=> larger key; all keys > 0
+    u = (u == 0x80000000u) ? 0u : u;                    // -0.0 ties with +0.0
+    // larger float <=> larger key; all keys > 0.  Negative values flip every bit, the others the sign bit only
+    // (written without a branch: the scalar unit is what bounds this kernel).
+    return u ^ ((uint32_t)((int32_t)u >> 31) | 0x80000000u);
 }
 
 __device__ __forceinline__ int lanes_below(unsigned long long m) {
@@ -52,7 +54,10 @@ __global__ __launch_bounds__(256) void topk_rows_kernel(const float* __restrict_
                           uint32_t& t_hint) {
         uint32_t key[EPL];
 #pragma unroll
-        for (int s = 0; s < EPL; ++s) key[s] = (s * kWave + lane < D) ? order_key(val[s]) : 0u;   // padding key 0 < real keys
+        for (int s = 0; s < EPL; ++s) {
+            const uint32_t real = order_key(val[s]);
+            key[s] = (s * kWave + lane < D) ? real : 0u;      // padding key 0 < real keys
+        }
         // T = largest threshold with count(key >= T) >= k  == the k-th largest key.  The search stops as
         // soon as a probe separates exactly k elements: then {key >= T} is already the answer, which on
         // tie-free data happens after about a dozen of the 32 bits.
@@ -61,12 +66,14 @@ __global__ __launch_bounds__(256) void topk_rows_kernel(const float* __restrict_
         uint32_t T = 0;
         int top = 31;
         {
-            const uint32_t lo = t_hint & 0xff800000u, hi = lo + 0x00800000u;     // hi wraps to 0 in the last binade
+            // (for finite inputs a threshold never lies in the last binade; if hi did wrap to 0, c_hi would count
+            // every element and the full search below would run)
+            const uint32_t lo = t_hint & 0xff800000u, hi = lo + 0x00800000u;
             int c_lo = 0, c_hi = 0;
 #pragma unroll
             for (int s = 0; s < EPL; ++s) {
-                c_lo += __popcll(__ballot(key[s] >= lo));
-                c_hi += hi ? __popcll(__ballot(key[s] >= hi)) : 0;
+                c_lo += __popcll(__builtin_amdgcn_ballot_w64(key[s] >= lo));
+                c_hi += __popcll(__builtin_amdgcn_ballot_w64(key[s] >= hi));
             }
             if (c_lo >= k && c_hi < k) {
                 T = lo;
@@ -77,14 +84,14 @@ __global__ __launch_bounds__(256) void topk_rows_kernel(const float* __restrict_
             uint32_t cand = T | (1u << bit);
             int cnt = 0;
 #pragma unroll
-            for (int s = 0; s < EPL; ++s) cnt += __popcll(__ballot(key[s] >= cand));
+            for (int s = 0; s < EPL; ++s) cnt += __popcll(__builtin_amdgcn_ballot_w64(key[s] >= cand));
             if (cnt >= k) T = cand;
             if (cnt == k) break;
         }
         t_hint = T;
         int n_gt = 0;
 #pragma unroll
-        for (int s = 0; s < EPL; ++s) n_gt += __popcll(__ballot(key[s] > T));
+        for (int s = 0; s < EPL; ++s) n_gt += __popcll(__builtin_amdgcn_ballot_w64(key[s] > T));
         const int need_eq = k - n_gt;                   // >= 1 ties to take, lowest columns first
         int kept_before = 0, eq_before = 0;
         const size_t base = (size_t)row * k;
@@ -94,22 +101,24 @@ __global__ __launch_bounds__(256) void topk_rows_kernel(const float* __restrict_
         for (int s = 0; s < EPL; ++s) {
             bool gt = key[s] > T;
             bool eq = key[s] == T;
-            unsigned long long meq = __ballot(eq);
-            bool keep = gt || (eq && (eq_before + lanes_below(meq)) < need_eq);
-            unsigned long long mk = __ballot(keep);
-            keep_s[s] = keep;
-            pos_s[s] = kept_before + lanes_below(mk);          // position in ascending column order
+            unsigned long long meq = __builtin_amdgcn_ballot_w64(eq);
+            const bool tie_taken = (eq_before + lanes_below(meq)) < need_eq;     // evaluated by every lane: no branch
+            const bool keep = gt || (eq && tie_taken);
+            unsigned long long mk = __builtin_amdgcn_ballot_w64(keep);
+            const int pos = kept_before + lanes_below(mk);     // position in ascending column order
             kept_before += __popcll(mk);
             eq_before += __popcll(meq);
-        }
-        if constexpr (!RANKED) {
-#pragma unroll
-            for (int s = 0; s < EPL; ++s)
-                if (keep_s[s]) {
-                    vals[base + pos_s[s]] = val[s];
-                    idx[base + pos_s[s]] = (uint16_t)(s * kWave + lane);
+            if constexpr (!RANKED) {
+                if (keep) {                                    // stored at once: the predicate stays a lane mask
+                    vals[base + pos] = val[s];
+                    idx[base + pos] = (uint16_t)(s * kWave + lane);
                 }
-        } else {
+            } else {
+                keep_s[s] = keep;
+                pos_s[s] = pos;
+            }
+        }
+        if constexpr (RANKED) {
             // One wavefront executes its LDS accesses in program order, so the reads below see the keys written here
             // and the next row's writes come after this row's reads; the fences keep the compiler from reordering.
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
