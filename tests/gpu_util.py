@@ -45,6 +45,16 @@ def assert_elem_bound(got, want, l1elem, what, tol=ELEM_TOL):
     assert np.all(got[zero] == 0), (what, "non-zero output where no term contributes")
 
 
+def cells_with_agreeing_masks(near_rowptr, near_colidx, mask_a, mask_b):
+    """Cells whose input gradient does not depend on a max-merge decision on which the two masks differ: the cell's own
+    row and the rows of every `near` destination it feeds agree (near: rows = destinations, columns = sources)."""
+    row_bad = (mask_a != mask_b).any(axis=1)
+    dst = np.repeat(np.arange(len(row_bad)), np.diff(near_rowptr.astype(np.int64)))
+    feeds_bad = np.zeros(len(row_bad), np.int64)
+    np.add.at(feeds_bad, near_colidx.astype(np.int64), row_bad[dst].astype(np.int64))
+    return ~row_bad & (feeds_bad == 0)
+
+
 def random_csr(rng, M, N, max_deg, dup=False, empty_frac=0.2, evil_rows=(), evil_deg=0):
     deg = rng.integers(0, max_deg + 1, size=M)
     deg[rng.random(M) < empty_frac] = 0

@@ -1,5 +1,7 @@
-"""Parity at the benchmark's full size (1.2 M cells, 0.9 M nets, D = 128, k swept over 8, 16, 32, 64, the
-launch configuration bench.py times); see sampled_checks.py for how single outputs are recomputed."""
+"""Parity of the whole layer at the benchmark's full size (1.2 M cells, 0.9 M nets, D = 128, k swept over 8, 16, 32,
+64, the launch configuration bench.py times): sampled nodes against the oracle's layer on induced sub-problems, all
+five weight gradients entry by entry (see sampled_checks.py); test_gpu_large_exhaustive.py compares every element of
+the D-ReLU / DR-SpMM kernels at k = 32."""
 import pytest
 
 import sampled_checks as sc
@@ -31,5 +33,5 @@ def test_large_backward_sampled_rows(run):
     sc.check_backward(run)
 
 
-def test_large_weight_gradients_follow_from_sampled_identity(run):
+def test_large_weight_gradients_sampled_entries_and_probe_identity(run):
     sc.check_weight_gradients(run)

@@ -30,5 +30,5 @@ def test_medium_backward_sampled_rows(run):
     sc.check_backward(run)
 
 
-def test_medium_weight_gradients_follow_from_sampled_identity(run):
+def test_medium_weight_gradients_sampled_entries_and_probe_identity(run):
     sc.check_weight_gradients(run)

@@ -8,7 +8,8 @@ import torch
 import oracle
 import paper_2508_16769_amd as P
 from circuit_synth import make_graph, make_tensors, workload
-from gpu_util import (HostPattern, assert_elem_bound, assert_row_bound, dev, host_idx, random_csr, say)
+from gpu_util import (HostPattern, assert_elem_bound, assert_row_bound, cells_with_agreeing_masks, dev, host_idx, random_csr,
+                      say)
 
 pytestmark = pytest.mark.gpu
 
@@ -324,9 +325,11 @@ def test_heteroconv_fwd_bwd_parity(name, seed, override):
     # backward on the GPU's own saved state agrees with the oracle wherever the masks agree row-wise
     layer.heteroconv_bwd(dev(T.dY_cell), dev(T.dY_net), Wd, saved, dX_cell, dX_net, dW)
     torch.cuda.synchronize()
-    if np.array_equal(mask, of["mask"]):
-        gc2 = np.take_along_axis(dX_cell.cpu().numpy(), of["idx_cell"].astype(np.int64), axis=1)
-        assert_row_bound(gc2, ob["dXs_cell"], ob["l1_dxs_cell"].sum(axis=1), "dX_cell (own saved)")
+    ok = cells_with_agreeing_masks(o_near.rowptr, o_near.colidx, mask, of["mask"])
+    assert ok.sum() >= 0.9 * g.Nc, f"only {int(ok.sum())} of {g.Nc} cells have a neighbourhood whose masks agree"
+    say(f"   backward on the layer's own saved state: {int(ok.sum())} of {g.Nc} cells compared")
+    gc2 = np.take_along_axis(dX_cell.cpu().numpy(), of["idx_cell"].astype(np.int64), axis=1)
+    assert_row_bound(gc2[ok], ob["dXs_cell"][ok], ob["l1_dxs_cell"].sum(axis=1)[ok], "dX_cell (own saved)")
     layer.heteroconv_destroy()
 
 
