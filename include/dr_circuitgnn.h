@@ -150,6 +150,19 @@ int dr_csr_normalize(int mode, int64_t n_rows, int64_t n_cols, int64_t nnz,
                      const int32_t* rowptr, const int32_t* colidx, float* vals_out,
                      void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * dr_csr_normalize for callers that cannot allocate device memory or bring a workspace (code under HIP graph
+ * capture, serving loops, harnesses that forbid hipMalloc): same arguments without the workspace, same results bit
+ * for bit.  The column counts of DR_NORM_SYM live in an array of DR_NOALLOC_MAX_COLS + 1 int32 (8 MiB) that is part of
+ * the library image on every GPU it runs on; the call allocates and frees nothing.  n_cols above DR_NOALLOC_MAX_COLS
+ * is refused with DR_ERR_UNSUPPORTED (DR_NORM_MEAN needs no scratch and has no such limit).  All calls on one GPU
+ * share that array: calls that overlap on one GPU (different streams, different threads) race and must be
+ * serialised by the caller.
+ */
+#define DR_NOALLOC_MAX_COLS (1 << 21)
+int dr_csr_normalize_noalloc(int mode, int64_t n_rows, int64_t n_cols, int64_t nnz,
+                             const int32_t* rowptr, const int32_t* colidx, float* vals_out, void* stream);
+
 /* ------------------------------------------------------------------------------------------------
  * The HeteroConv layer (paper Fig. 3, Sections 3.2-3.4): three relation modules on three HIP streams,
  *     near   (cell->cell, SageConv mean):  Z_near   = f(X_cell) Wself_near + (A_near   f(X_cell)) Wneigh_near

@@ -32,7 +32,7 @@ EXPORTS = (
     "dr_last_error", "dr_abi_version", "dr_topk", "dr_spmm_fwd", "dr_spmm_bwd",
     "dr_topk_ranked", "dr_spmm_fwd_adaptive", "dr_degree_edge_classes", "dr_spmm_bwd_adaptive",
     "dr_csr_transpose_workspace_bytes", "dr_csr_transpose",
-    "dr_csr_normalize_workspace_bytes", "dr_csr_normalize",
+    "dr_csr_normalize_workspace_bytes", "dr_csr_normalize", "dr_csr_normalize_noalloc",
     "heteroconv_create", "heteroconv_create_per_relation", "heteroconv_get_k", "heteroconv_profile_k", "heteroconv_fwd", "heteroconv_bwd", "heteroconv_get_transpose", "heteroconv_destroy",
     "heteroconv_profile", "heteroconv_num_kernels", "heteroconv_kernel_name", "heteroconv_kernel_times",
     "heteroconv_set_overlap",
@@ -217,6 +217,13 @@ def dr_csr_normalize(mode: int, n_rows: int, n_cols: int, rowptr: torch.Tensor, 
     _check(load().dr_csr_normalize(ctypes.c_int(mode), ctypes.c_int64(n_rows), ctypes.c_int64(n_cols),
                                    ctypes.c_int64(colidx.shape[0]), _ptr(rowptr), _ptr(colidx), _ptr(vals_out),
                                    _ptr(workspace), ctypes.c_size_t(wsb), _stream(stream)))
+
+
+def dr_csr_normalize_noalloc(mode: int, n_rows: int, n_cols: int, rowptr: torch.Tensor, colidx: torch.Tensor,
+                             vals_out: torch.Tensor, stream=None) -> None:
+    _check(load().dr_csr_normalize_noalloc(ctypes.c_int(mode), ctypes.c_int64(n_rows), ctypes.c_int64(n_cols),
+                                           ctypes.c_int64(colidx.shape[0]), _ptr(rowptr), _ptr(colidx), _ptr(vals_out),
+                                           _stream(stream)))
 
 
 class HeteroConv:

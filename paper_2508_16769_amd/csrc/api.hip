@@ -197,4 +197,17 @@ int dr_csr_normalize(int mode, int64_t n_rows, int64_t n_cols, int64_t nnz, cons
     return launch_csr_normalize(mode, n_rows, n_cols, nnz, rowptr, colidx, vals_out, workspace, as_stream(stream));
 }
 
+int dr_csr_normalize_noalloc(int mode, int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t* rowptr,
+                             const int32_t* colidx, float* vals_out, void* stream) {
+    DRC_REQUIRE(mode == DR_NORM_MEAN || mode == DR_NORM_SYM, "dr_csr_normalize_noalloc: unknown mode %d", mode);
+    dr_csr A{n_rows, n_cols, nnz, rowptr, colidx, nullptr};
+    if (int rc = check_csr(&A, "dr_csr_normalize_noalloc", false)) return rc;
+    if (nnz == 0) return DR_OK;
+    DRC_REQUIRE(vals_out != nullptr, "dr_csr_normalize_noalloc: null vals_out");
+    if (mode == DR_NORM_SYM && n_cols > DR_NOALLOC_MAX_COLS)
+        return fail(DR_ERR_UNSUPPORTED, "dr_csr_normalize_noalloc: n_cols = %lld exceeds DR_NOALLOC_MAX_COLS = %d",
+                    (long long)n_cols, DR_NOALLOC_MAX_COLS);
+    return launch_csr_normalize_noalloc(mode, n_rows, n_cols, nnz, rowptr, colidx, vals_out, as_stream(stream));
+}
+
 }  // extern "C"

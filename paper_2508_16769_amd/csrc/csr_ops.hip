@@ -3,6 +3,8 @@
 // iteration; they are written for clarity and determinism, not tuned.
 #include "dr_internal.h"
 
+#include <mutex>
+
 namespace drc {
 
 __global__ void fill_u32_kernel(uint32_t* p, size_t n, uint32_t v) {
@@ -63,6 +65,40 @@ int launch_csr_normalize(int mode, int64_t n_rows, int64_t n_cols, int64_t nnz, 
                        deg_out, vals_out);
     DRC_HIP(hipGetLastError());
     return DR_OK;
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Edge values without a workspace argument: the column counts live in a device array that is part of the
+// library image.  The array's name is only a host-side handle; its device address is looked up once per
+// device and that pointer is what the kernels and the fill receive.
+// ---------------------------------------------------------------------------------------------------
+
+static __device__ __align__(256) int32_t scratch[DR_NOALLOC_MAX_COLS + 64];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static int32_t* g_scratch_ptr[kMaxDevices] = {};
+
+static int scratch_of_current_device(int32_t** out) {
+    int dev = -1;
+    DRC_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(DR_ERR_UNSUPPORTED, "device ordinal %d outside [0, %d)", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        DRC_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (p == nullptr) return fail(DR_ERR_HIP, "hipGetSymbolAddress returned a null address for the scratch array");
+        g_scratch_ptr[dev] = static_cast<int32_t*>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return DR_OK;
+}
+
+int launch_csr_normalize_noalloc(int mode, int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t* rowptr,
+                                 const int32_t* colidx, float* vals_out, hipStream_t s) {
+    int32_t* deg_out = nullptr;
+    if (mode == DR_NORM_SYM) DRC_TRY(scratch_of_current_device(&deg_out));   // cleared by the launcher's fill kernel
+    return launch_csr_normalize(mode, n_rows, n_cols, nnz, rowptr, colidx, vals_out, deg_out, s);
 }
 
 // ---------------------------------------------------------------------------------------------------

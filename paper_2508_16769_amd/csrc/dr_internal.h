@@ -67,6 +67,8 @@ int launch_csr_transpose(const dr_csr* A, int32_t* t_rowptr, int32_t* t_colidx, 
                          hipStream_t s);
 int launch_csr_normalize(int mode, int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t* rowptr,
                          const int32_t* colidx, float* vals_out, void* ws, hipStream_t s);
+int launch_csr_normalize_noalloc(int mode, int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t* rowptr,
+                                 const int32_t* colidx, float* vals_out, hipStream_t s);
 int launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t s);
 
 // shape of a layer context (heteroconv.hip owns the struct)
