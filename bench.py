@@ -1,13 +1,19 @@
 #!/usr/bin/env python3
 """Benchmark of the HeteroConv DR-SpMM hot path on one MI355X.
 
-A *step* is one HeteroConv forward + backward over one seeded synthetic circuit graph: D-ReLU top-k of
-both node types, the three DR-SpMM forwards, the projections and max-merge, and the whole backward
-(projection gradients, the three transposed DR-SpMMs gated by the saved indices, weight gradients).
-Graph setup (edge values, transposes) is done once before the timed region.  Inputs are resident in HBM
-when the timed region starts.
+A *step* (what `value`, `ms_per_step`, `steps` and `warmup` refer to) is one pass of the D-ReLU / DR-SpMM kernels of
+a HeteroConv layer, forward and backward, over one seeded synthetic circuit graph: `dr_topk` of both node types,
+`dr_spmm_fwd` of the three relations and `dr_spmm_bwd` of the three transposed relations -- eight launches through
+the C ABI, forked from the caller's stream onto three streams (one per relation, paper Section 3.4) and joined by
+events, with no host wait in between.  `value` = the compulsory bytes of those eight kernels (every array once)
+divided by the time of that region.  Graph setup (edge values, transposes) is done once before the timed region;
+every input is resident in HBM when it starts.
 
-Prints ONE JSON line; `operation_models()` / `kernel_models()` below are the byte models behind `value` and `roofline`.
+Reported beside it on the same JSON line: `dr_kernels` (each of the eight kernels alone on its stream, HIP events
+around every launch), `roofline` (the longest of them against the HBM roof), `layer_step` (the whole layer,
+heteroconv_fwd + heteroconv_bwd with projections, merge and weight gradients), `k_sweep` (the region at k = 8, 16, 32,
+64 on the `large` workload) and `cpu_baseline` (the oracle's functions for the same eight operations on the same
+inputs, one host thread).  `operation_models()` / `kernel_models()` below are the byte models.
 """
 from __future__ import annotations
 
@@ -93,9 +99,136 @@ DR_KERNELS = ("dr_topk.cell", "dr_topk.net", "dr_spmm_fwd.near", "dr_spmm_fwd.pi
               "dr_spmm_bwd.near", "dr_spmm_bwd.pins", "dr_spmm_bwd.pinned")
 
 
-def cpu_baseline(name: str, D: int, ks, scale: int):
+REL_TYPES = dict(near=("cell", "cell"), pins=("cell", "net"), pinned=("net", "cell"))   # relation -> (source, destination) type
+
+
+class DrRegion:
+    """Buffers and launch sequence of the eight D-ReLU / DR-SpMM kernels of one layer pass.  The backward kernels read
+    seeded N(0,1) upstream gradients of the destination type (in the layer they come from the projection gradients,
+    which are not part of this region) and write one compact gradient each."""
+
+    def __init__(self, P, torch, rel, rel_t, X, dH, D, k):
+        self.P, self.torch, self.rel, self.rel_t, self.X, self.dH, self.D, self.k = P, torch, rel, rel_t, X, dH, D, k
+        f32, i16 = torch.float32, torch.int16
+        n = dict(cell=X["cell"].shape[0], net=X["net"].shape[0])
+        self.vals = {t: torch.empty((n[t], k), dtype=f32, device="cuda") for t in n}
+        self.idx = {t: torch.empty((n[t], k), dtype=i16, device="cuda") for t in n}
+        self.H = {r: torch.empty((n[REL_TYPES[r][1]], D), dtype=f32, device="cuda") for r in REL_TYPES}
+        self.G = {r: torch.empty((n[REL_TYPES[r][0]], k), dtype=f32, device="cuda") for r in REL_TYPES}
+        self.side = (torch.cuda.Stream(), torch.cuda.Stream())          # default priority
+        self.ev = {n_: torch.cuda.Event() for n_ in ("fork", "cell", "pins", "pinned")}
+
+    def kernels(self):
+        """{name: callable(stream)} -- one launch each through the C ABI."""
+        P, D, k = self.P, self.D, self.k
+        out = {}
+        for t in ("cell", "net"):
+            out[f"dr_topk.{t}"] = (lambda s, t=t: P.dr_topk(self.X[t], k, self.vals[t], self.idx[t], stream=s))
+        for r, (src, dst) in REL_TYPES.items():
+            out[f"dr_spmm_fwd.{r}"] = (lambda s, r=r, src=src: P.dr_spmm_fwd(self.rel[r], self.vals[src], self.idx[src], D, k,
+                                                                               self.H[r], stream=s))
+            out[f"dr_spmm_bwd.{r}"] = (lambda s, r=r, src=src, dst=dst: P.dr_spmm_bwd(self.rel_t[r], self.dH[dst], self.idx[src],
+                                                                                       D, k, self.G[r], stream=s))
+        return out
+
+    def run(self, concurrent=True):
+        """One pass.  concurrent: near on the caller's stream, pins and pinned on two side streams; pins waits for the
+        cells' D-ReLU.  Otherwise all eight launches on the caller's stream."""
+        K = self.kernels()
+        main = self.torch.cuda.current_stream()
+        if not concurrent:
+            for n_ in ("dr_topk.cell", "dr_spmm_fwd.near", "dr_spmm_bwd.near", "dr_spmm_fwd.pins", "dr_spmm_bwd.pins",
+                       "dr_topk.net", "dr_spmm_fwd.pinned", "dr_spmm_bwd.pinned"):
+                K[n_](main)
+            return
+        s_pins, s_pinned = self.side
+        ev = self.ev
+        ev["fork"].record(main)
+        s_pins.wait_event(ev["fork"])
+        s_pinned.wait_event(ev["fork"])
+        K["dr_topk.cell"](main)
+        ev["cell"].record(main)
+        K["dr_topk.net"](s_pinned)
+        s_pins.wait_event(ev["cell"])
+        K["dr_spmm_fwd.pins"](s_pins)
+        K["dr_spmm_fwd.near"](main)
+        K["dr_spmm_fwd.pinned"](s_pinned)
+        K["dr_spmm_bwd.pins"](s_pins)
+        K["dr_spmm_bwd.near"](main)
+        K["dr_spmm_bwd.pinned"](s_pinned)
+        ev["pins"].record(s_pins)
+        ev["pinned"].record(s_pinned)
+        main.wait_event(ev["pins"])
+        main.wait_event(ev["pinned"])
+
+    def time_region(self, warmup, steps, concurrent=True):
+        """(wall ms per pass between device synchronisations, HIP-event ms per pass on the caller's stream)."""
+        torch = self.torch
+        for _ in range(warmup):
+            self.run(concurrent)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        a.record()
+        for _ in range(steps):
+            self.run(concurrent)
+        b.record()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) * 1e3 / steps
+        return wall, a.elapsed_time(b) / steps
+
+    def time_kernels(self, warmup, iters):
+        """Each kernel alone on the caller's stream: HIP events around every launch; {name: (mean, median, min) ms}."""
+        torch = self.torch
+        main = torch.cuda.current_stream()
+        self.run(False)                                     # every buffer a kernel reads holds valid contents
+        out = {}
+        for name, launch in self.kernels().items():
+            for _ in range(warmup):
+                launch(main)
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+            for a, b in evs:
+                a.record(main)
+                launch(main)
+                b.record(main)
+            torch.cuda.synchronize()
+            ms = sorted(a.elapsed_time(b) for a, b in evs)
+            out[name] = (sum(ms) / len(ms), ms[len(ms) // 2], ms[0])
+        return out
+
+
+def dr_models(Nc, Nn, E, D, k):
+    m = operation_models(Nc, Nn, E, D, (k, k, k, k))
+    return {n: m[n] for n in DR_KERNELS}
+
+
+def cpu_baseline_dr(g, T, D, k):
+    """The oracle's functions for the eight operations of the timed region -- orc_topk x2, orc_spmm_fwd x3,
+    orc_spmm_bwd x3 -- on the benchmark's own graph and tensors, one after the other on one host thread."""
+    import numpy as np
+    import oracle
+    rel = dict(near=oracle.relation(g.near, oracle.NORM_MEAN), pins=oracle.relation(g.pins, oracle.NORM_MEAN),
+               pinned=oracle.relation(g.pinned, oracle.NORM_SYM))
+    tr = {n: oracle.csr_transpose(rel[n].M, rel[n].N, rel[n].rowptr, rel[n].colidx, rel[n].vals) for n in rel}   # setup, not timed
+    X = dict(cell=T.X_cell, net=T.X_net)
+    dH = dict(cell=T.dY_cell, net=T.dY_net)
+    secs, cb = {}, {}
+    for t in ("cell", "net"):
+        t0 = time.perf_counter()
+        cb[t] = oracle.topk(X[t], k)
+        secs[f"dr_topk.{t}"] = time.perf_counter() - t0
+    for r, (src, dst) in REL_TYPES.items():
+        t0 = time.perf_counter()
+        oracle.spmm_fwd(rel[r].rowptr, rel[r].colidx, rel[r].vals, cb[src][0], cb[src][1], D)
+        secs[f"dr_spmm_fwd.{r}"] = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        oracle.spmm_bwd(*tr[r], dH[dst], cb[src][1])
+        secs[f"dr_spmm_bwd.{r}"] = time.perf_counter() - t0
+    return secs
+
+
+def cpu_baseline_layer(name: str, D: int, ks, scale: int):
     """The oracle's layer forward + backward on a 1/scale-size graph drawn from the same laws."""
-    import numpy as np  # noqa: F401
     import oracle
     from oracle import per_relation as opr
     from circuit_synth import make_graph, make_tensors, workload
@@ -121,31 +254,34 @@ def cpu_baseline(name: str, D: int, ks, scale: int):
     dt = time.perf_counter() - t0
     models = operation_models(Nc, Nn, dict(near=g.near.nnz, pins=g.pins.nnz, pinned=g.pinned.nnz), D, ks)
     step_bytes = sum(b for b, _ in models.values())
-    return dict(value=round(step_bytes / dt / 1e9, 4), unit="GB/s", cores=1, kind="oracle",
-                sample=f"oracle HeteroConv fwd+bwd (fp64, 1 thread) on a 1/{scale}-scale '{name}' graph: "
-                       f"{Nc} cells, {Nn} nets, E_near={g.near.nnz}, E_pins={g.pins.nnz}, D={D}, "
-                       f"k={ks[0] if one_k and ks[0] == ks[3] else '/'.join(map(str, ks))}; "
-                       f"{dt:.2f} s for {step_bytes / 1e6:.1f} MB of algorithmic traffic",
-                seconds=round(dt, 3), host_cores_available=len(os.sched_getaffinity(0)))
+    return dict(value=round(step_bytes / dt / 1e9, 4), unit="GB/s", seconds=round(dt, 3),
+                sample=f"oracle HeteroConv layer fwd+bwd (fp64, 1 thread) on a 1/{scale}-scale '{name}' graph: {Nc} cells, "
+                       f"{Nn} nets, E_near={g.near.nnz}, E_pins={g.pins.nnz}, D={D}; {step_bytes / 1e6:.1f} MB of the layer's "
+                       f"algorithmic bytes")
 
 
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="large", help="tiny | small | medium | large | subgraph")
-    ap.add_argument("--k", type=int, default=None, help="D-ReLU k (default: the workload's; large sweeps 8..64)")
+    ap.add_argument("--k", type=int, default=None, help="D-ReLU k of the headline (default: the workload's)")
+    ap.add_argument("--only", choices=("all", "dr", "layer"), default="all",
+                    help="dr: only the timed D-ReLU / DR-SpMM region; layer: only the whole-layer steps (for profiler runs)")
+    ap.add_argument("--serial", action="store_true", help="the region's eight launches on one stream (for counter runs)")
+    ap.add_argument("--no-k-sweep", action="store_true")
+    ap.add_argument("--kernel-iters", type=int, default=50, help="launches per kernel in the per-kernel timing pass")
+    ap.add_argument("--layer-steps", type=int, default=20)
     ap.add_argument("--k-per-relation", default=None,
-                    help="one K per edge type: 'k_near,k_pins,k_pinned', or 'best' = what --profile-k picks")
+                    help="layer step with one K per edge type: 'k_near,k_pins,k_pinned', or 'best' = what --profile-k picks")
     ap.add_argument("--profile-k", action="store_true",
-                    help="optimal-K profiling of the workload's graph over K = 2..64 before the timed steps "
-                         "(reported as k_profile)")
+                    help="optimal-K profiling of the workload's graph over K = 2..64 (reported as k_profile)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-scale", type=int, default=None, help="oracle sample = 1/scale of the workload")
-    ap.add_argument("--no-profile-events", action="store_true", help="do not bracket kernels with HIP events")
+    ap.add_argument("--cpu-scale", type=int, default=None, help="oracle layer sample = 1/scale of the workload")
+    ap.add_argument("--no-profile-events", action="store_true", help="layer steps without per-kernel HIP events")
     ap.add_argument("--overlap", choices=("auto", "on", "off"), default="auto",
-                    help="relation concurrency: three streams (on), one stream (off), or the library's size rule")
+                    help="layer step: three streams (on), one stream (off), or the library's size rule")
     ap.add_argument("--permute-cells", action="store_true",
                     help="sensitivity run: relabel the cells at random (removes the grid locality of `near`)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -193,146 +329,173 @@ def main() -> int:
     def dev(a):
         return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
-    near = P.device_relation(g.near, P.DR_NORM_MEAN)
-    pins = P.device_relation(g.pins, P.DR_NORM_MEAN)
-    pinned = P.device_relation(g.pinned, P.DR_NORM_SYM)
+    rel = dict(near=P.device_relation(g.near, P.DR_NORM_MEAN), pins=P.device_relation(g.pins, P.DR_NORM_MEAN),
+               pinned=P.device_relation(g.pinned, P.DR_NORM_SYM))
     torch.cuda.synchronize()
     t_graph = time.perf_counter()
-    layer = P.HeteroConv(near, pins, pinned, D, k, k)     # device transposes + scratch
-    t_ctx = time.perf_counter() - t_graph
-    X_cell, X_net = dev(T.X_cell), dev(T.X_net)
-    k_profile = None
-    if args.profile_k or args.k_per_relation == "best":
-        cand = [c for c in (2, 4, 8, 16, 32, 64) if c <= D]
-        tp = time.perf_counter()
-        ms_f, ms_b, best = layer.heteroconv_profile_k(X_cell, X_net, cand, warmup=2, reps=5)
-        k_profile = dict(candidates=cand, relations=["near", "pins", "pinned"],
-                         ms_fwd=[[round(v, 4) for v in r] for r in ms_f], ms_bwd=[[round(v, 4) for v in r] for r in ms_b],
-                         best=list(best), seconds=round(time.perf_counter() - tp, 3))
-    if args.k_per_relation:
-        kk = k_profile["best"] if args.k_per_relation == "best" else [int(v) for v in args.k_per_relation.split(",")]
-        if len(kk) != 3:
-            print("bench.py: --k-per-relation takes k_near,k_pins,k_pinned", file=sys.stderr)
-            return 2
-        layer.heteroconv_destroy()
-        layer = P.HeteroConv(near, pins, pinned, D, per_relation=kk)
-    ks = layer.heteroconv_get_k()
-    klabel = str(k) if not args.k_per_relation else "k_near/k_pins/k_pinned=" + "/".join(str(v) for v in (ks[0], ks[1], ks[3]))
-    layer.heteroconv_set_overlap({"auto": P.DR_OVERLAP_AUTO, "on": P.DR_OVERLAP_ON, "off": P.DR_OVERLAP_OFF}[args.overlap])
-    saved = layer.alloc_saved()
-    Wd = {n: dev(T.W[n]) for n in P.WEIGHT_NAMES}
-    dY_cell, dY_net = dev(T.dY_cell), dev(T.dY_net)
-    Y_cell = torch.empty((g.Nc, D), dtype=torch.float32, device="cuda")
-    Y_net = torch.empty((g.Nn, D), dtype=torch.float32, device="cuda")
-    dX_cell, dX_net = torch.empty_like(Y_cell), torch.empty_like(Y_net)
-    dW = {n: torch.empty((D, D), dtype=torch.float32, device="cuda") for n in P.WEIGHT_NAMES}
-    del T
+    rel_t = {r: P.device_transpose(rel[r]) for r in rel}
+    torch.cuda.synchronize()
+    t_transposes = time.perf_counter() - t_graph
+    X = dict(cell=dev(T.X_cell), net=dev(T.X_net))
+    dY = dict(cell=dev(T.dY_cell), net=dev(T.dY_net))
     torch.cuda.synchronize()
     t_setup = time.perf_counter() - t_setup
-
-    def step():
-        layer.heteroconv_fwd(X_cell, X_net, Wd, Y_cell, Y_net, saved)
-        layer.heteroconv_bwd(dY_cell, dY_net, Wd, saved, dX_cell, dX_net, dW)
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    if not args.no_profile_events:
-        layer.heteroconv_profile(True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    times = {} if args.no_profile_events else layer.heteroconv_kernel_times()
-    layer.heteroconv_profile(False)
-
-    models = kernel_models(g.Nc, g.Nn, E, D, ks)
-    step_bytes = sum(b for b, _ in operation_models(g.Nc, g.Nn, E, D, ks).values())
-    dr_bytes = sum(models[n][0] for n in DR_KERNELS if n in models)
-    value = step_bytes / (ms_per_step * 1e-3) / 1e9
-
-    kernels = {}
-    for name, (ms_sum, cnt) in times.items():
-        if cnt == 0:
-            continue
-        avg = ms_sum / cnt
-        b, f = models[name]
-        kernels[name] = dict(ms=round(avg, 4), GBs=round(b / (avg * 1e-3) / 1e9, 1),
-                             GFLOPs=round(f / (avg * 1e-3) / 1e9, 1), MB=round(b / 1e6, 2))
-    roofline = None
-    dr_region = None
-    if kernels:
-        # dominant kernel: the kernel symbol with the largest share of the step (launches of one instantiation are
-        # named family.relation), represented by its longest launch
-        fam = {}
-        for n in kernels:
-            fam[n.split(".")[0]] = fam.get(n.split(".")[0], 0.0) + kernels[n]["ms"]
-        top = max(fam, key=fam.get)
-        dom = max((n for n in kernels if n.split(".")[0] == top), key=lambda n: kernels[n]["ms"])
-        b, f = models[dom]
-        avg_s = kernels[dom]["ms"] * 1e-3
-        traffic = None
-        tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-        if os.path.exists(tpath):
-            try:
-                tkey = f"{args.workload}.k{k}" if not args.k_per_relation else None
-                traffic = json.load(open(tpath)).get(tkey, {}).get(dom)
-            except Exception:
-                traffic = None
-        intensity = f / b
-        if intensity > MFMA_FP32_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9):
-            ach = f / avg_s / 1e12
-            roofline = dict(bound="mfma", achieved=round(ach, 2), peak=MFMA_FP32_PEAK_TFLOPS, unit="TFLOP/s",
-                            frac=round(ach / MFMA_FP32_PEAK_TFLOPS, 4), traffic=traffic, kernel=dom,
-                            avg_ms=kernels[dom]["ms"])
-        else:
-            ach = b / avg_s / 1e9
-            roofline = dict(bound="hbm", achieved=round(ach, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                            frac=round(ach / HBM_PEAK_GBS, 4), traffic=traffic, kernel=dom,
-                            avg_ms=kernels[dom]["ms"])
-        if traffic:   # measured HBM bytes of the same kernel over the same duration (context for `frac`)
-            roofline["measured_hbm_GBs"] = round(traffic / avg_s / 1e9, 1)
-            roofline["measured_hbm_frac"] = round(traffic / avg_s / 1e9 / HBM_PEAK_GBS, 4)
-        dr_ms = sum(kernels[n]["ms"] for n in DR_KERNELS if n in kernels)
-        dr_flops = sum(models[n][1] for n in DR_KERNELS if n.startswith("dr_spmm"))
-        dr_region = dict(kernels="D-ReLU x2 + DR-SpMM fwd x3 + bwd x3", sum_ms=round(dr_ms, 4),
-                         MB=round(dr_bytes / 1e6, 1), GBs=round(dr_bytes / (dr_ms * 1e-3) / 1e9, 1),
-                         frac_of_hbm_peak=round(dr_bytes / (dr_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                         GFLOPs=round(dr_flops / (dr_ms * 1e-3) / 1e9, 1))
+    workload_label = (f"{args.workload}: {g.Nc} cells, {g.Nn} nets, E_near={E['near']}, E_pins={E['pins']}, D={D}, k={k}"
+                      + (" (cell ids randomly permuted)" if args.permute_cells else ""))
 
     out = {
         "metric": "HeteroConv DR-SpMM fwd+bwd effective GB/s",
-        "value": round(value, 1),
-        "unit": "GB/s",
-        "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
-        "dtype": "f32",
-        "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {g.Nc} cells, {g.Nn} nets, E_near={E['near']}, "
-                               f"E_pins={E['pins']}, D={D}, k={klabel}, one HeteroConv layer fwd+bwd"
-                               + (" (cell ids randomly permuted)" if args.permute_cells else ""),
-                   "step_algorithmic_MB": round(step_bytes / 1e6, 1),
-                   "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
-                   "relation_overlap": args.overlap,
-                   "setup_s": round(t_setup, 2), "context_create_s": round(t_ctx, 3)},
-        "roofline": roofline,
-        "dr_spmm_kernels": dr_region,
-        "kernels": kernels,
+        "value": None, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": None,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": workload_label,
+                   "timed_region": "dr_topk x2 + dr_spmm_fwd x3 + dr_spmm_bwd x3, " +
+                                   ("one stream" if args.serial else "three streams (one per relation), joined by events"),
+                   "setup_s": round(t_setup, 2), "transposes_s": round(t_transposes, 3)},
     }
-    if k_profile:
-        out["k_profile"] = k_profile
+
+    # ------------------------------------------------------------------------------------------------
+    # the timed region: the eight D-ReLU / DR-SpMM kernels, forked on three streams
+    # ------------------------------------------------------------------------------------------------
+    if args.only in ("all", "dr"):
+        region = DrRegion(P, torch, rel, rel_t, X, dY, D, k)
+        models = dr_models(g.Nc, g.Nn, E, D, k)
+        dr_bytes = sum(b for b, _ in models.values())
+        dr_flops = sum(f for n, (_, f) in models.items() if n.startswith("dr_spmm"))
+        wall_ms, event_ms = region.time_region(args.warmup, args.steps, concurrent=not args.serial)
+        out["value"] = round(dr_bytes / (wall_ms * 1e-3) / 1e9, 1)
+        out["ms_per_step"] = round(wall_ms, 4)
+        out["config"].update(step_algorithmic_MB=round(dr_bytes / 1e6, 1), frac_of_hbm_peak=round(out["value"] / HBM_PEAK_GBS, 4),
+                             region_event_ms=round(event_ms, 4), GFLOPs=round(dr_flops / (wall_ms * 1e-3) / 1e9, 1))
+        if args.only == "all":
+            per = region.time_kernels(10, max(10, args.kernel_iters))
+            kernels = {n: dict(ms=round(avg, 4), ms_median=round(med, 4), ms_min=round(mn, 4), MB=round(models[n][0] / 1e6, 2),
+                               GBs=round(models[n][0] / (avg * 1e-3) / 1e9, 1), GFLOPs=round(models[n][1] / (avg * 1e-3) / 1e9, 1))
+                       for n, (avg, med, mn) in per.items()}
+            total = sum(v["ms"] for v in kernels.values())
+            out["dr_kernels"] = dict(protocol=f"each kernel alone on its stream, 10 warm-ups + {max(10, args.kernel_iters)} launches, "
+                                              "HIP events around every launch", sum_ms=round(total, 4),
+                                     GBs_serialized=round(dr_bytes / (total * 1e-3) / 1e9, 1), kernels=kernels)
+            dom = max(kernels, key=lambda n: kernels[n]["ms"])
+            b, f = models[dom]
+            ach = b / (kernels[dom]["ms"] * 1e-3) / 1e9
+            traffic, source = None, None
+            tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+            if os.path.exists(tpath) and not args.permute_cells:
+                try:
+                    tab = json.load(open(tpath))
+                    traffic = tab.get(f"{args.workload}.k{k}", {}).get(dom)
+                    source = tab.get("measured", {}).get(f"{args.workload}.k{k}")
+                except Exception:
+                    traffic = None
+            out["roofline"] = dict(bound="hbm", achieved=round(ach, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                                   frac=round(ach / HBM_PEAK_GBS, 4), traffic=traffic, kernel=dom, avg_ms=kernels[dom]["ms"],
+                                   algorithmic_bytes=b)
+            if traffic:
+                out["roofline"]["traffic_source"] = source or "profiles/hbm_traffic.json (rocprofv3 FETCH_SIZE x 2.0 + WRITE_SIZE)"
+                out["roofline"]["measured_hbm_GBs"] = round(traffic / (kernels[dom]["ms"] * 1e-3) / 1e9, 1)
+            # the same region on one stream, for the value of relation concurrency
+            s_wall, _ = region.time_region(3, max(5, args.steps // 2), concurrent=args.serial)
+            out["config"]["region_ms_other_schedule"] = {("three streams" if args.serial else "one stream"): round(s_wall, 4)}
+        del region
+
+        if args.only == "all" and args.workload == "large" and not args.no_k_sweep:
+            sweep = {}
+            for kk in (8, 16, 32, 64):
+                rg = DrRegion(P, torch, rel, rel_t, X, dY, D, kk)
+                m = dr_models(g.Nc, g.Nn, E, D, kk)
+                bb = sum(b for b, _ in m.values())
+                ff = sum(f for n, (_, f) in m.items() if n.startswith("dr_spmm"))
+                wms, _ = rg.time_region(5, 20, concurrent=not args.serial)
+                sweep[f"k{kk}"] = dict(ms=round(wms, 4), MB=round(bb / 1e6, 1), GBs=round(bb / (wms * 1e-3) / 1e9, 1),
+                                       frac_of_hbm_peak=round(bb / (wms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                                       GFLOPs=round(ff / (wms * 1e-3) / 1e9, 1))
+                del rg
+            out["k_sweep"] = sweep
+
+    # ------------------------------------------------------------------------------------------------
+    # the whole layer: heteroconv_fwd + heteroconv_bwd (projections, merge, weight gradients included)
+    # ------------------------------------------------------------------------------------------------
+    ks = (k, k, k, k)
+    if args.only in ("all", "layer"):
+        layer = P.HeteroConv(rel["near"], rel["pins"], rel["pinned"], D, k, k)
+        k_profile = None
+        if args.profile_k or args.k_per_relation == "best":
+            cand = [c for c in (2, 4, 8, 16, 32, 64) if c <= D]
+            tp = time.perf_counter()
+            ms_f, ms_b, best = layer.heteroconv_profile_k(X["cell"], X["net"], cand, warmup=2, reps=5)
+            k_profile = dict(candidates=cand, relations=["near", "pins", "pinned"],
+                             ms_fwd=[[round(v, 4) for v in r] for r in ms_f], ms_bwd=[[round(v, 4) for v in r] for r in ms_b],
+                             best=list(best), seconds=round(time.perf_counter() - tp, 3))
+            out["k_profile"] = k_profile
+        if args.k_per_relation:
+            kk = k_profile["best"] if args.k_per_relation == "best" else [int(v) for v in args.k_per_relation.split(",")]
+            if len(kk) != 3:
+                print("bench.py: --k-per-relation takes k_near,k_pins,k_pinned", file=sys.stderr)
+                return 2
+            layer.heteroconv_destroy()
+            layer = P.HeteroConv(rel["near"], rel["pins"], rel["pinned"], D, per_relation=kk)
+        ks = layer.heteroconv_get_k()
+        layer.heteroconv_set_overlap({"auto": P.DR_OVERLAP_AUTO, "on": P.DR_OVERLAP_ON, "off": P.DR_OVERLAP_OFF}[args.overlap])
+        saved = layer.alloc_saved()
+        Wd = {n: dev(T.W[n]) for n in P.WEIGHT_NAMES}
+        Y_cell = torch.empty((g.Nc, D), dtype=torch.float32, device="cuda")
+        Y_net = torch.empty((g.Nn, D), dtype=torch.float32, device="cuda")
+        dX_cell, dX_net = torch.empty_like(Y_cell), torch.empty_like(Y_net)
+        dW = {n: torch.empty((D, D), dtype=torch.float32, device="cuda") for n in P.WEIGHT_NAMES}
+
+        def step():
+            layer.heteroconv_fwd(X["cell"], X["net"], Wd, Y_cell, Y_net, saved)
+            layer.heteroconv_bwd(dY["cell"], dY["net"], Wd, saved, dX_cell, dX_net, dW)
+
+        n_steps = args.steps if args.only == "layer" else args.layer_steps
+        n_warm = args.warmup if args.only == "layer" else 3
+        for _ in range(n_warm):
+            step()
+        torch.cuda.synchronize()
+        if not args.no_profile_events:
+            layer.heteroconv_profile(True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n_steps):
+            step()
+        torch.cuda.synchronize()
+        layer_ms = (time.perf_counter() - t0) * 1e3 / n_steps
+        times = {} if args.no_profile_events else layer.heteroconv_kernel_times()
+        layer.heteroconv_profile(False)
+        lmodels = kernel_models(g.Nc, g.Nn, E, D, ks)
+        step_bytes = sum(b for b, _ in operation_models(g.Nc, g.Nn, E, D, ks).values())
+        lk = {}
+        for name, (ms_sum, cnt) in times.items():
+            if cnt:
+                avg = ms_sum / cnt
+                b, f = lmodels[name]
+                lk[name] = dict(ms=round(avg, 4), GBs=round(b / (avg * 1e-3) / 1e9, 1), GFLOPs=round(f / (avg * 1e-3) / 1e9, 1),
+                                MB=round(b / 1e6, 2))
+        klabel = str(k) if not args.k_per_relation else "k_near/k_pins/k_pinned=" + "/".join(str(v) for v in (ks[0], ks[1], ks[3]))
+        out["layer_step"] = dict(what=f"heteroconv_fwd + heteroconv_bwd, k={klabel}, relation_overlap={args.overlap}, "
+                                      f"{n_warm} warm-ups + {n_steps} steps, per-kernel HIP events "
+                                      + ("off" if args.no_profile_events else "on"),
+                                 ms_per_step=round(layer_ms, 4), algorithmic_MB=round(step_bytes / 1e6, 1),
+                                 GBs=round(step_bytes / (layer_ms * 1e-3) / 1e9, 1), kernels=lk)
+        if args.only == "layer":
+            out["value"] = out["layer_step"]["GBs"]
+            out["ms_per_step"] = out["layer_step"]["ms_per_step"]
+            out["metric"] = "HeteroConv layer fwd+bwd effective GB/s (all operations)"
+        layer.heteroconv_destroy()
+
     if not args.no_cpu_baseline:
-        scale = args.cpu_scale or max(1, g.Nc // 200000)     # about 10-15 s of single-thread oracle work
-        out["cpu_baseline"] = cpu_baseline(args.workload, D, ks, scale)
-    layer.heteroconv_destroy()
+        secs = cpu_baseline_dr(g, T, D, k)
+        total = sum(secs.values())
+        dr_bytes = sum(b for b, _ in dr_models(g.Nc, g.Nn, E, D, k).values())
+        scale = args.cpu_scale or max(1, g.Nc // 200000)
+        out["cpu_baseline"] = dict(
+            value=round(dr_bytes / total / 1e9, 4), unit="GB/s", cores=1, kind="oracle",
+            sample=f"the whole workload ({workload_label}): orc_topk x2, orc_spmm_fwd x3, orc_spmm_bwd x3 on the benchmark's own "
+                   f"graph and tensors (fp64, one thread, one call after the other); {total:.1f} s for the same "
+                   f"{dr_bytes / 1e6:.1f} MB of compulsory bytes the GPU region is credited with",
+            seconds=round(total, 3), seconds_per_function={n: round(v, 3) for n, v in secs.items()},
+            host_cores_available=len(os.sched_getaffinity(0)),
+            layer=cpu_baseline_layer(args.workload, D, ks, scale))
     print(json.dumps(out), flush=True)
     return 0
 

@@ -81,6 +81,18 @@ def _rows_cols(rowptr, colidx, rows):
     return np.concatenate([colidx[rp[r]:rp[r + 1]] for r in rows]).astype(np.int64)
 
 
+def sub_rows(rel, rows):
+    """The given destination rows of one relation with all their edges: (rowptr, local colidx, vals, unique source ids)."""
+    rp = rel.rowptr.astype(np.int64)
+    deg = rp[rows + 1] - rp[rows]
+    sub_rp = np.zeros(len(rows) + 1, np.int32)
+    sub_rp[1:] = np.cumsum(deg)
+    take = np.concatenate([np.arange(rp[r], rp[r + 1]) for r in rows]) if len(rows) else np.zeros(0, np.int64)
+    cols = rel.colidx[take]
+    uniq, local = np.unique(cols, return_inverse=True)
+    return sub_rp, local.astype(np.int32), rel.vals[take], uniq
+
+
 def _sub_csr(relation, rows_global, full_rows, col_ids, n_rows):
     """CSR over local ids: local row q (= rows_global[q]) keeps its edges if it is in `full_rows` (a boolean over
     local rows) -- only those whose source is in col_ids (sorted global ids; for a row that must be exact all of them
