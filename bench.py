@@ -107,8 +107,9 @@ class DrRegion:
     seeded N(0,1) upstream gradients of the destination type (in the layer they come from the projection gradients,
     which are not part of this region) and write one compact gradient each."""
 
-    def __init__(self, P, torch, rel, rel_t, X, dH, D, k):
+    def __init__(self, P, torch, rel, rel_t, X, dH, D, k, near_plan=None):
         self.P, self.torch, self.rel, self.rel_t, self.X, self.dH, self.D, self.k = P, torch, rel, rel_t, X, dH, D, k
+        self.near_plan = near_plan      # dr_spmm_plan of the transposed `near` relation in placement order, or None
         f32, i16 = torch.float32, torch.int16
         n = dict(cell=X["cell"].shape[0], net=X["net"].shape[0])
         self.vals = {t: torch.empty((n[t], k), dtype=f32, device="cuda") for t in n}
@@ -127,8 +128,12 @@ class DrRegion:
         for r, (src, dst) in REL_TYPES.items():
             out[f"dr_spmm_fwd.{r}"] = (lambda s, r=r, src=src: P.dr_spmm_fwd(self.rel[r], self.vals[src], self.idx[src], D, k,
                                                                                self.H[r], stream=s))
-            out[f"dr_spmm_bwd.{r}"] = (lambda s, r=r, src=src, dst=dst: P.dr_spmm_bwd(self.rel_t[r], self.dH[dst], self.idx[src],
-                                                                                       D, k, self.G[r], stream=s))
+            if r == "near" and self.near_plan is not None:
+                out["dr_spmm_bwd.near"] = (lambda s: self.near_plan.dr_spmm_bwd_planned(self.dH["cell"], self.idx["cell"], k,
+                                                                                          self.G["near"], stream=s))
+            else:
+                out[f"dr_spmm_bwd.{r}"] = (lambda s, r=r, src=src, dst=dst: P.dr_spmm_bwd(self.rel_t[r], self.dH[dst], self.idx[src],
+                                                                                           D, k, self.G[r], stream=s))
         return out
 
     def run(self, concurrent=True):
@@ -271,6 +276,8 @@ def main() -> int:
                     help="dr: only the timed D-ReLU / DR-SpMM region; layer: only the whole-layer steps (for profiler runs)")
     ap.add_argument("--serial", action="store_true", help="the region's eight launches on one stream (for counter runs)")
     ap.add_argument("--no-k-sweep", action="store_true")
+    ap.add_argument("--no-staging", action="store_true",
+                    help="transposed `near` DR-SpMM without the LDS-staged tiles (the plain gather kernel, as for pins / pinned)")
     ap.add_argument("--kernel-iters", type=int, default=50, help="launches per kernel in the per-kernel timing pass")
     ap.add_argument("--layer-steps", type=int, default=20)
     ap.add_argument("--k-per-relation", default=None,
@@ -338,6 +345,18 @@ def main() -> int:
     t_transposes = time.perf_counter() - t_graph
     X = dict(cell=dev(T.X_cell), net=dev(T.X_net))
     dY = dict(cell=dev(T.dY_cell), net=dev(T.dY_net))
+    near_plan, plan_note = None, "off"
+    if not args.no_staging and g.cell_order is not None:
+        t_plan = time.perf_counter()
+        try:
+            near_plan = P.SpmmPlan(rel_t["near"], D, dev(g.cell_order))
+            n_tiles, reuse = near_plan.dr_spmm_plan_info()
+            plan_note = (f"near^T in placement order: {n_tiles} tiles, {reuse:.2f} edges per staged dH row, "
+                         f"plan built in {time.perf_counter() - t_plan:.2f} s")
+        except P.DrError as e:
+            if e.code != P.DR_ERR_UNSUPPORTED:
+                raise
+            plan_note = f"refused: {e}"
     torch.cuda.synchronize()
     t_setup = time.perf_counter() - t_setup
     workload_label = (f"{args.workload}: {g.Nc} cells, {g.Nn} nets, E_near={E['near']}, E_pins={E['pins']}, D={D}, k={k}"
@@ -350,14 +369,14 @@ def main() -> int:
         "config": {"workload": workload_label,
                    "timed_region": "dr_topk x2 + dr_spmm_fwd x3 + dr_spmm_bwd x3, " +
                                    ("one stream" if args.serial else "three streams (one per relation), joined by events"),
-                   "setup_s": round(t_setup, 2), "transposes_s": round(t_transposes, 3)},
+                   "lds_staging": plan_note, "setup_s": round(t_setup, 2), "transposes_s": round(t_transposes, 3)},
     }
 
     # ------------------------------------------------------------------------------------------------
     # the timed region: the eight D-ReLU / DR-SpMM kernels, forked on three streams
     # ------------------------------------------------------------------------------------------------
     if args.only in ("all", "dr"):
-        region = DrRegion(P, torch, rel, rel_t, X, dY, D, k)
+        region = DrRegion(P, torch, rel, rel_t, X, dY, D, k, near_plan)
         models = dr_models(g.Nc, g.Nn, E, D, k)
         dr_bytes = sum(b for b, _ in models.values())
         dr_flops = sum(f for n, (_, f) in models.items() if n.startswith("dr_spmm"))
@@ -401,7 +420,7 @@ def main() -> int:
         if args.only == "all" and args.workload == "large" and not args.no_k_sweep:
             sweep = {}
             for kk in (8, 16, 32, 64):
-                rg = DrRegion(P, torch, rel, rel_t, X, dY, D, kk)
+                rg = DrRegion(P, torch, rel, rel_t, X, dY, D, kk, near_plan)
                 m = dr_models(g.Nc, g.Nn, E, D, kk)
                 bb = sum(b for b, _ in m.values())
                 ff = sum(f for n, (_, f) in m.items() if n.startswith("dr_spmm"))

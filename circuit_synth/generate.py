@@ -90,6 +90,7 @@ class CircuitGraph:
     near: Pattern     # Nc x Nc
     pins: Pattern     # Nn x Nc
     pinned: Pattern   # Nc x Nn  (transpose pattern of pins)
+    cell_order: Optional[np.ndarray] = None   # int32 [Nc]: the cells sorted along a Z-order curve of their placement
 
 
 @dataclass
@@ -214,6 +215,26 @@ def _make_pins(Nn: int, Nc: int, mean_g: float, cap: Optional[int], evil: float,
     return _csr_from_sorted(rows, cols, Nn, Nc)
 
 
+def placement_order(Nc: int, grid: Tuple[int, int]) -> np.ndarray:
+    """The cells sorted along the Z-order (Morton) curve of their placement coordinates (cell id = y * W + x): any run
+    of 64 consecutive cells of this order covers a compact patch of the layout (an 8 x 8 square where the run is
+    aligned).  A processing-order hint for kernels that stage the neighbourhood of a block of cells; it carries no
+    arithmetic and changes no result."""
+    W, _ = grid
+    ids = np.arange(Nc, dtype=np.int64)
+
+    def spread(v):
+        v = v.astype(np.uint64)
+        v = (v | (v << np.uint64(8))) & np.uint64(0x00FF00FF)
+        v = (v | (v << np.uint64(4))) & np.uint64(0x0F0F0F0F)
+        v = (v | (v << np.uint64(2))) & np.uint64(0x33333333)
+        v = (v | (v << np.uint64(1))) & np.uint64(0x55555555)
+        return v
+
+    key = spread(ids % W) | (spread(ids // W) << np.uint64(1))
+    return np.argsort(key, kind="stable").astype(np.int32)
+
+
 def transpose_pattern(p: Pattern) -> Pattern:
     """Pattern of the transposed relation (index bookkeeping only, no values)."""
     rows = np.repeat(np.arange(p.n_rows, dtype=np.int64), np.diff(p.rowptr.astype(np.int64)))
@@ -237,9 +258,10 @@ def permute_cells(g: CircuitGraph, seed: int = 0) -> CircuitGraph:
         order = np.argsort(rows * np.int64(p.n_cols) + cols, kind="stable")
         return _csr_from_sorted(rows[order], cols[order], p.n_rows, p.n_cols)
 
+    order = None if g.cell_order is None else perm[g.cell_order.astype(np.int64)].astype(np.int32)
     return CircuitGraph(g.name + "-permuted", g.seed, g.Nc, g.Nn,
                         relabel(g.near, True, True), relabel(g.pins, False, True),
-                        relabel(g.pinned, True, False))
+                        relabel(g.pinned, True, False), order)
 
 
 def block_diagonal(graphs) -> CircuitGraph:
@@ -275,7 +297,7 @@ def make_graph(name: str, seed: int = 0, **override) -> CircuitGraph:
     pins = _make_pins(Nn, Nc, float(cfg["net_mean"]), cfg["net_cap"], float(cfg["evil"]),
                       _rng(seed, _STREAM_NET_DEGREE), _rng(seed, _STREAM_NET_MEMBERS))
     pinned = transpose_pattern(pins)
-    return CircuitGraph(name, seed, Nc, Nn, near, pins, pinned)
+    return CircuitGraph(name, seed, Nc, Nn, near, pins, pinned, placement_order(Nc, tuple(cfg["grid"])))
 
 
 def make_tensors(Nc: int, Nn: int, D: int, seed: int = 0, upstream: bool = True) -> LayerTensors:

@@ -92,6 +92,30 @@ int dr_spmm_bwd(const dr_csr* At, const float* dH, const uint16_t* xs_idx,
                 int32_t D, int32_t k, float* dXs, int accumulate, void* stream);
 
 /*
+ * DR-SpMM backward with the gathered rows staged in LDS (paper Section 3.3 / Alg. 2 stage 2, which keeps the interim
+ * rows of a block in shared memory).  Same result as dr_spmm_bwd, for relations in which nearby rows share most of
+ * their neighbours (the geometric `near` relation).  A plan is made once per transposed relation:
+ *   row_order: device array of At->n_rows row ids, a permutation -- the order in which the rows are processed; runs
+ *              of up to 64 consecutive entries form the tiles whose distinct dH rows are loaded into LDS once.  NULL =
+ *              the rows' own order.  The order changes no result (every sum keeps its storage order); it pays when
+ *              rows that share neighbours sit next to each other, e.g. cells sorted along a space-filling curve of
+ *              their placement.
+ * dr_spmm_plan_create reads At on the host (it waits for `stream`), allocates the plan's device arrays and returns
+ * DR_ERR_UNSUPPORTED when D is not a multiple of 32, when a single row does not fit a tile (more than 2048 edges, or
+ * more distinct neighbours than 64 KB / (4 * min(D, 64)) rows) or when the device offers too little LDS; the caller
+ * then stays with dr_spmm_bwd.  dr_spmm_plan_info reports the number of tiles and `reuse` = stored edges per distinct
+ * gathered row summed over the tiles (the factor by which the dH rows fetched per edge shrink).  At, its arrays and
+ * row_order are not referenced after dr_spmm_plan_create returns.
+ * dr_spmm_bwd_planned: arguments as dr_spmm_bwd (D is the plan's); dH must be 16-byte aligned; k <= min(D, 2 * min(D, 64)).
+ */
+typedef struct dr_spmm_plan dr_spmm_plan;
+int dr_spmm_plan_create(dr_spmm_plan** plan, const dr_csr* At, const int32_t* row_order, int32_t D, void* stream);
+int dr_spmm_plan_info(const dr_spmm_plan* plan, int64_t* n_tiles, double* reuse);
+int dr_spmm_bwd_planned(const dr_spmm_plan* plan, const float* dH, const uint16_t* xs_idx, int32_t k, float* dXs,
+                        int accumulate, void* stream);
+int dr_spmm_plan_destroy(dr_spmm_plan* plan);
+
+/*
  * Degree-adaptive K (paper Section 3.2, Alg. 1 stage 2 "dynamic warp partitioning" and the text after Alg. 1):
  * neighbour groups are classified by their size, and the larger a destination's neighbour group the fewer entries
  * of each neighbour's embedding it receives (K1 > K2 > K3).  The paper prints no formula, boundaries or K values;

@@ -30,6 +30,7 @@ DR_OVERLAP_OFF = 2
 WEIGHT_NAMES = ("self_near", "neigh_near", "self_pins", "neigh_pins", "pinned")
 EXPORTS = (
     "dr_last_error", "dr_abi_version", "dr_topk", "dr_spmm_fwd", "dr_spmm_bwd",
+    "dr_spmm_plan_create", "dr_spmm_plan_info", "dr_spmm_bwd_planned", "dr_spmm_plan_destroy",
     "dr_topk_ranked", "dr_spmm_fwd_adaptive", "dr_degree_edge_classes", "dr_spmm_bwd_adaptive",
     "dr_csr_transpose_workspace_bytes", "dr_csr_transpose",
     "dr_csr_normalize_workspace_bytes", "dr_csr_normalize", "dr_csr_normalize_noalloc",
@@ -161,6 +162,39 @@ def dr_spmm_bwd(At: Csr, dH: torch.Tensor, xs_idx: torch.Tensor, D: int, k: int,
     a = At.c()
     _check(load().dr_spmm_bwd(ctypes.byref(a), _ptr(dH), _ptr(xs_idx), ctypes.c_int32(D), ctypes.c_int32(k),
                               _ptr(dXs), ctypes.c_int(1 if accumulate else 0), _stream(stream)))
+
+
+class SpmmPlan:
+    """Owner of a ``dr_spmm_plan*`` (dr_spmm_plan_create / dr_spmm_plan_destroy) for one transposed relation."""
+
+    def __init__(self, At: Csr, D: int, row_order: Optional[torch.Tensor] = None, stream=None):
+        self.D, self.n_rows = D, At.n_rows
+        self._p = ctypes.c_void_p(0)
+        a = At.c()
+        _check(load().dr_spmm_plan_create(ctypes.byref(self._p), ctypes.byref(a), _ptr(row_order), ctypes.c_int32(D),
+                                          _stream(stream)))
+
+    def dr_spmm_plan_info(self):
+        """(number of tiles, stored edges per distinct gathered row)."""
+        n, r = ctypes.c_int64(0), ctypes.c_double(0.0)
+        _check(load().dr_spmm_plan_info(self._p, ctypes.byref(n), ctypes.byref(r)))
+        return int(n.value), float(r.value)
+
+    def dr_spmm_bwd_planned(self, dH: torch.Tensor, xs_idx: torch.Tensor, k: int, dXs: torch.Tensor, accumulate: bool = False,
+                            stream=None) -> None:
+        _check(load().dr_spmm_bwd_planned(self._p, _ptr(dH), _ptr(xs_idx), ctypes.c_int32(k), _ptr(dXs),
+                                          ctypes.c_int(1 if accumulate else 0), _stream(stream)))
+
+    def dr_spmm_plan_destroy(self) -> None:
+        if self._p:
+            _check(load().dr_spmm_plan_destroy(self._p))
+            self._p = ctypes.c_void_p(0)
+
+    def __del__(self):
+        try:
+            self.dr_spmm_plan_destroy()
+        except Exception:
+            pass
 
 
 class dr_degree_classes(ctypes.Structure):

@@ -70,6 +70,11 @@ int launch_csr_normalize(int mode, int64_t n_rows, int64_t n_cols, int64_t nnz, 
 int launch_csr_normalize_noalloc(int mode, int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t* rowptr,
                                  const int32_t* colidx, float* vals_out, hipStream_t s);
 int launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t s);
+// DR-SpMM backward with the gathered rows staged in LDS, tile by tile (staged.hip)
+int spmm_plan_create(dr_spmm_plan** out, const dr_csr* A, const int32_t* row_order, int D, hipStream_t s);
+void spmm_plan_destroy(dr_spmm_plan* p);
+int launch_spmm_bwd_planned(const dr_spmm_plan* p, const float* dH, const uint16_t* xs_idx, int k, float* dXs, int accumulate,
+                            hipStream_t s);
 
 // shape of a layer context (heteroconv.hip owns the struct)
 struct HeteroDims {

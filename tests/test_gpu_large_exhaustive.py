@@ -87,6 +87,18 @@ def test_spmm_bwd_every_element(inputs, whole):
             got = G.cpu().numpy()
             worst = assert_row_bound(got, want, l1row, f"G_{name}")
             assert_elem_bound(got, want, l1elem, f"G_{name}")
+            if name == "near":
+                # the same gradient from the kernel that stages the dH rows of a placement tile in LDS
+                plan = P.SpmmPlan(At, D, dev(inputs["g"].cell_order))
+                n_tiles, reuse = plan.dr_spmm_plan_info()
+                Gp = torch.full((At.n_rows, K), float("nan"), dtype=torch.float32, device="cuda")
+                plan.dr_spmm_bwd_planned(inputs["dT"][f"dY_{dst}"], idx, K, Gp)
+                torch.cuda.synchronize()
+                gp = Gp.cpu().numpy()
+                worst_p = assert_row_bound(gp, want, l1row, "G_near (planned)")
+                assert_elem_bound(gp, want, l1elem, "G_near (planned)")
+                say(f"   dr_spmm_bwd_planned.near: {n_tiles} tiles, reuse {reuse:.2f}, worst err / row L1 = {worst_p:.2e}")
+                plan.dr_spmm_plan_destroy()
             # accumulate: a second pass onto the first doubles every element exactly
             P.dr_spmm_bwd(At, inputs["dT"][f"dY_{dst}"], idx, D, K, G, accumulate=True)
             torch.cuda.synchronize()
