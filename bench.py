@@ -454,6 +454,9 @@ def main() -> int:
             layer.heteroconv_destroy()
             layer = P.HeteroConv(rel["near"], rel["pins"], rel["pinned"], D, per_relation=kk)
         ks = layer.heteroconv_get_k()
+        layer_staged = False
+        if not args.no_staging and g.cell_order is not None:
+            layer_staged = layer.heteroconv_set_cell_order(dev(g.cell_order))
         layer.heteroconv_set_overlap({"auto": P.DR_OVERLAP_AUTO, "on": P.DR_OVERLAP_ON, "off": P.DR_OVERLAP_OFF}[args.overlap])
         saved = layer.alloc_saved()
         Wd = {n: dev(T.W[n]) for n in P.WEIGHT_NAMES}
@@ -492,6 +495,7 @@ def main() -> int:
                                 MB=round(b / 1e6, 2))
         klabel = str(k) if not args.k_per_relation else "k_near/k_pins/k_pinned=" + "/".join(str(v) for v in (ks[0], ks[1], ks[3]))
         out["layer_step"] = dict(what=f"heteroconv_fwd + heteroconv_bwd, k={klabel}, relation_overlap={args.overlap}, "
+                                      f"near^T on LDS-staged tiles: {'yes' if layer_staged else 'no'}, "
                                       f"{n_warm} warm-ups + {n_steps} steps, per-kernel HIP events "
                                       + ("off" if args.no_profile_events else "on"),
                                  ms_per_step=round(layer_ms, 4), algorithmic_MB=round(step_bytes / 1e6, 1),

@@ -299,6 +299,18 @@ int heteroconv_get_transpose(const dr_heteroconv* ctx, int which, dr_csr* out);
 int heteroconv_destroy(dr_heteroconv* ctx);
 
 /*
+ * Processing-order hint for the geometric `near` relation (paper Section 2.2: near links come from the cells'
+ * placement).  cell_order: device array of Nc cell ids, a permutation, in which cells that lie close to each other in
+ * the layout sit next to each other (e.g. sorted along a Z-order curve of their coordinates); NULL = the cells' own
+ * order.  The layer's backward then runs the transposed `near` DR-SpMM through dr_spmm_plan / dr_spmm_bwd_planned (dH
+ * rows of a tile of cells staged in LDS) -- provided the plan can be made and reuses a staged row at least twice on
+ * average; *staged (may be NULL) reports whether it will.  No result changes with the order.  Builds the plan on the
+ * host (waits for `stream` and for the context's transposes); call it once per bound graph, outside the timed loop.
+ * A later re-binding of the context drops the plan.
+ */
+int heteroconv_set_cell_order(dr_heteroconv* ctx, const int32_t* cell_order, int* staged, void* stream);
+
+/*
  * Relation concurrency (paper Section 3.4).  DR_OVERLAP_ON: the near, pins and pinned pipelines are enqueued on
  * three HIP streams and joined by events only where the data flow demands it.  DR_OVERLAP_OFF: the same kernels,
  * in the same dependency order, back to back on one stream.  DR_OVERLAP_AUTO (default): separate streams while one

@@ -36,7 +36,7 @@ EXPORTS = (
     "dr_csr_normalize_workspace_bytes", "dr_csr_normalize", "dr_csr_normalize_noalloc",
     "heteroconv_create", "heteroconv_create_per_relation", "heteroconv_get_k", "heteroconv_profile_k", "heteroconv_fwd", "heteroconv_bwd", "heteroconv_get_transpose", "heteroconv_destroy",
     "heteroconv_profile", "heteroconv_num_kernels", "heteroconv_kernel_name", "heteroconv_kernel_times",
-    "heteroconv_set_overlap",
+    "heteroconv_set_overlap", "heteroconv_set_cell_order",
     "dr_pipeline_create", "dr_pipeline_submit", "dr_pipeline_acquire", "dr_pipeline_relations", "dr_pipeline_release",
     "dr_pipeline_destroy",
     "hgnn_num_params", "hgnn_create", "hgnn_create_batched", "hgnn_train_step", "hgnn_set_inspection", "hgnn_get_layer_buffers", "hgnn_destroy",
@@ -344,6 +344,12 @@ class HeteroConv:
         out = dr_csr()
         _check(load().heteroconv_get_transpose(self._ctx, ctypes.c_int(which), ctypes.byref(out)))
         return out
+
+    def heteroconv_set_cell_order(self, cell_order: Optional[torch.Tensor], stream=None) -> bool:
+        """True when the transposed `near` DR-SpMM of the backward will run on LDS-staged tiles."""
+        staged = ctypes.c_int(0)
+        _check(load().heteroconv_set_cell_order(self._ctx, _ptr(cell_order), ctypes.byref(staged), _stream(stream)))
+        return bool(staged.value)
 
     def heteroconv_set_overlap(self, mode: int) -> None:
         _check(load().heteroconv_set_overlap(self._ctx, ctypes.c_int(mode)))

@@ -46,56 +46,30 @@ struct dr_spmm_plan {
 namespace drc {
 
 constexpr int kStRows = 64;        // rows per tile at most
-constexpr int kStThreads = 1024;    // one workgroup per compute unit: 4 wavefronts per SIMD
+constexpr int kStThreads = 1024;   // one persistent workgroup per compute unit: 4 wavefronts per SIMD
 constexpr int kStEdgeCap = 2048;   // edge records per tile
-constexpr int kStTileBytes = 65536;   // LDS bytes of one column slab of the tile's gathered rows
+constexpr int kStTileBytes = 49152;   // LDS bytes of one column slab of the tile's gathered rows
 constexpr int kStUnroll = 4;       // edges per lane group and trip of the inner loop
 constexpr int kStRecRegs = kStEdgeCap / kStThreads;   // records of the next tile a thread holds while the current one computes
+constexpr int kStRing = 4;         // tiles whose heads (gathered rows, row ids, row offsets) are resident in LDS
+constexpr int kStStartPad = kStRows + 4;
 
 __host__ __device__ constexpr size_t staged_lds_bytes(int cw, int ccap, int ecap) {
-    return sizeof(float) * (size_t)ccap * cw + sizeof(int2) * (size_t)ecap + sizeof(int) * (kStRows + 4) +
-           sizeof(float) * kStThreads * 4;
+    return sizeof(float) * (size_t)ccap * cw + 2 * sizeof(int2) * (size_t)ecap + sizeof(float) * kStThreads * 4 +
+           sizeof(int) * kStRing * ((size_t)ccap + kStRows + kStStartPad + 4);
 }
 
-// What a thread needs of a tile before anything of it can be fetched: found from the tile number alone.
-template <int NL, int RPQ> struct TileHead {
-    int4 d;            // desc
-    int col[NL];       // gathered row of each of the thread's 16-byte pieces of a slab (padding repeats the last row)
-    int row[RPQ];      // the rows of the thread's lane group (-1: none)
-    int start;         // row_start[tid] (threads 0..64)
-};
-
-template <int NL, int RPQ, int LPR, int NQ>
-__device__ __forceinline__ void load_head(TileHead<NL, RPQ>& x, int t, const int4* __restrict__ desc,
-                                          const int32_t* __restrict__ rows, const int32_t* __restrict__ row_start,
-                                          const int32_t* __restrict__ cols, int ccap, int tid) {
-    x.d = desc[t];
-#pragma unroll
-    for (int u = 0; u < NL; ++u) x.col[u] = cols[(size_t)t * ccap + (u * kStThreads + tid) / LPR];
-    const int q = tid / LPR;
-#pragma unroll
-    for (int ri = 0; ri < RPQ; ++ri) {
-        const int lr = (ri & 1) ? (ri * NQ + NQ - 1 - q) : (ri * NQ + q);      // serpentine over the length-sorted rows
-        x.row[ri] = lr < kStRows ? rows[(size_t)t * kStRows + lr] : -1;
-    }
-    x.start = row_start[(size_t)t * (kStRows + 1) + min(tid, kStRows)];
-}
-
-// All of a thread's pieces of one slab, unconditionally (padding pieces re-read the tile's last gathered row): the
-// loads go out back to back and stay in flight together.
 typedef float v4f __attribute__((ext_vector_type(4)));     // a native vector: arrays of it stay in registers
 
-template <int NL>
-__device__ __forceinline__ void fetch_slab(v4f (&pre)[NL], const int (&col)[NL], const float* __restrict__ slab, int D) {
-#pragma unroll
-    for (int u = 0; u < NL; ++u) pre[u] = *reinterpret_cast<const v4f*>(slab + (size_t)(uint32_t)col[u] * (uint32_t)D);
-}
-
-// A persistent workgroup walks a contiguous range of tiles.  While it computes on one tile, the loads of the next one
-// are in flight: its head from the first slab on; its records, saved columns and first slab during the last slab of the
-// tile before; every further slab during the slab before it.  Everything fetched ahead waits in registers and enters
-// LDS after the barrier that ends the phase still reading the old contents.
-template <int CW, int KS>
+// A persistent workgroup walks a contiguous range of tiles; the work is a stream of jobs (tile, column slab).  While it
+// computes on one job, the loads of the next two are in flight in two register sets, each written to LDS after the
+// barrier that ends the job still reading the old slab.  What the loads need to know of a tile -- its gathered rows,
+// row ids, row offsets, record range: the tile's head -- is fetched three tiles ahead and parked in a ring of LDS
+// slots; the records and saved columns of the next tile are fetched during the whole current tile.
+// Which register set a job uses is a compile-time fact (NS slabs per tile, two tiles per trip of the loop): a set
+// chosen at run time would have to be merged with selects, and a select needs its load to have landed.  For the
+// same reason no load below is conditional: addresses are clamped to something valid and the result is ignored.
+template <int CW, int KS, int NS>
 __global__ __launch_bounds__(kStThreads) void spmm_bwd_staged_kernel(
     const int4* __restrict__ desc, const int32_t* __restrict__ rows, const int32_t* __restrict__ row_start,
     const int32_t* __restrict__ cols, const int2* __restrict__ recs,
@@ -106,12 +80,14 @@ __global__ __launch_bounds__(kStThreads) void spmm_bwd_staged_kernel(
     constexpr int RPQ = (kStRows + NQ - 1) / NQ;   // rows of the tile per lane group (with 8 lanes per row half the groups idle)
     constexpr int NL = kStTileBytes / 16 / kStThreads;   // 16-byte pieces of a slab per thread
     static_assert(kStTileBytes % (16 * kStThreads) == 0 && kStEdgeCap % kStThreads == 0, "tile shape");
-    using Head = TileHead<NL, RPQ>;
     extern __shared__ float4 smem4[];
-    float* sTile = reinterpret_cast<float*>(smem4);                       // [ccap][CW]
-    int2* sRec = reinterpret_cast<int2*>(sTile + (size_t)ccap * CW);      // [ecap]
-    int* sRowStart = reinterpret_cast<int*>(sRec + ecap);                 // [kStRows + 1] (+3: alignment)
-    float* sScr = reinterpret_cast<float*>(sRowStart + kStRows + 4);      // [NQ][CW], 16-byte aligned
+    float* sTile = reinterpret_cast<float*>(smem4);                              // [ccap][CW]
+    long long* sRec8 = reinterpret_cast<long long*>(sTile + (size_t)ccap * CW);  // [2][ecap] records of this tile / the next
+    float* sScr = reinterpret_cast<float*>(sRec8 + 2 * (size_t)ecap);            // [NQ][CW]
+    int* sCols = reinterpret_cast<int*>(sScr + kStThreads * 4);                  // [kStRing][ccap]
+    int* sRows = sCols + kStRing * ccap;                                         // [kStRing][kStRows]
+    int* sStart = sRows + kStRing * kStRows;                                     // [kStRing][kStStartPad]
+    int* sDesc = sStart + kStRing * kStStartPad;                                 // [kStRing][4] (record offset, records, gathered rows, rows)
 
     // contiguous tile ranges, and neighbouring ranges on one XCD (workgroups are dealt to the XCDs round-robin)
     const int n_wg = gridDim.x;
@@ -122,144 +98,159 @@ __global__ __launch_bounds__(kStThreads) void spmm_bwd_staged_kernel(
     const int tid = threadIdx.x;
     const int q = tid / LPR, l = tid % LPR;
     float* scr = sScr + q * CW;
-    const int n_slabs = D / CW;
     const float* my_cols = dH + l * 4;              // this thread's 4 columns of slab 0
     const long long* recs8 = reinterpret_cast<const long long*>(recs);
-    long long* sRec8 = reinterpret_cast<long long*>(sRec);
+    const int* desc_i = reinterpret_cast<const int*>(desc);
 
-    Head a, b;
-    v4f pre[NL];
-    long long nrec[kStRecRegs];
-    int ci[RPQ][KS], ci_next[RPQ][KS];
+    int h_col, h_row, h_start, h_desc;              // a tile's head on its way to the ring
+    v4f pre[2][NL];                                 // the slabs of the next two jobs
+    long long nrec[kStRecRegs];                     // the next tile's records
+    int ci[RPQ][KS], ci_next[RPQ][KS];              // saved columns of this thread's slots: this tile, the next
 
-    // ---- the first tile: nothing to hide behind ----
-    load_head<NL, RPQ, LPR, NQ>(a, t_begin, desc, rows, row_start, cols, ccap, tid);
-    fetch_slab<NL>(pre, a.col, my_cols, D);
-#pragma unroll
-    for (int j = 0; j < kStRecRegs; ++j) {
-        const int e = j * kStThreads + tid;
-        nrec[j] = __builtin_nontemporal_load(recs8 + a.d.x + min(e, max(a.d.y - 1, 0)));
+#define DRC_LOAD_HEAD(T)                                                                                      \
+    do {                                                                                                      \
+        const int t_ = min((T), t_end - 1);                                                                   \
+        h_col = cols[(size_t)t_ * ccap + min(tid, ccap - 1)];                                                 \
+        h_row = rows[(size_t)t_ * kStRows + min(tid, kStRows - 1)];                                           \
+        h_start = row_start[(size_t)t_ * (kStRows + 1) + min(tid, kStRows)];                                  \
+        h_desc = desc_i[(size_t)t_ * 4 + (tid & 3)];                                                          \
+    } while (0)
+#define DRC_PARK_HEAD(T)                                                                                      \
+    do {                                                                                                      \
+        const int s_ = (T) & (kStRing - 1);                                                                   \
+        if (tid < ccap) sCols[s_ * ccap + tid] = h_col;                                                       \
+        if (tid < kStRows) sRows[s_ * kStRows + tid] = h_row;                                                 \
+        if (tid <= kStRows) sStart[s_ * kStStartPad + tid] = h_start;                                         \
+        if (tid < 4) sDesc[s_ * 4 + tid] = h_desc;                                                            \
+    } while (0)
+    // this thread's pieces of slab HH of tile TT (padding pieces re-read the tile's last gathered row)
+#define DRC_FETCH(SET, TT, HH)                                                                                \
+    do {                                                                                                      \
+        const int* c_ = sCols + (min((TT), t_end - 1) & (kStRing - 1)) * ccap;                                \
+        const float* slab_ = my_cols + (size_t)(HH) * CW;                                                     \
+        _Pragma("unroll") for (int u = 0; u < NL; ++u)                                                        \
+            pre[SET][u] = *reinterpret_cast<const v4f*>(slab_ + (size_t)(uint32_t)c_[(u * kStThreads + tid) / LPR] * (uint32_t)D); \
+    } while (0)
+    // records and saved columns of tile T (rows past the tile's and slots past k read something valid that is never used)
+#define DRC_LOAD_TILE_SIDE(T, CI)                                                                             \
+    do {                                                                                                      \
+        const int s_ = min((T), t_end - 1) & (kStRing - 1);                                                   \
+        const int e0_ = sDesc[s_ * 4 + 0], ne_ = sDesc[s_ * 4 + 1];                                           \
+        _Pragma("unroll") for (int j_ = 0; j_ < kStRecRegs; ++j_)                                             \
+            nrec[j_] = __builtin_nontemporal_load(recs8 + e0_ + min(j_ * kStThreads + tid, max(ne_ - 1, 0)));  \
+        _Pragma("unroll") for (int ri = 0; ri < RPQ; ++ri) {                                                  \
+            const int lr_ = (ri & 1) ? (ri * NQ + NQ - 1 - q) : (ri * NQ + q);                                \
+            const int row_ = max(sRows[s_ * kStRows + min(lr_, kStRows - 1)], 0);                             \
+            _Pragma("unroll") for (int s2 = 0; s2 < KS; ++s2)                                                 \
+                CI[ri][s2] = (int)__builtin_nontemporal_load(xs_idx + (size_t)row_ * k + min(l + LPR * s2, k - 1)); \
+        }                                                                                                     \
+    } while (0)
+#define DRC_STORE_RECORDS(T, BUF)                                                                             \
+    do {                                                                                                      \
+        const int ne_ = sDesc[(min((T), t_end - 1) & (kStRing - 1)) * 4 + 1];                                 \
+        _Pragma("unroll") for (int j_ = 0; j_ < kStRecRegs; ++j_)                                             \
+            if (j_ * kStThreads + tid < ne_) sRec8[(size_t)(BUF) * ecap + j_ * kStThreads + tid] = nrec[j_];   \
+    } while (0)
+
+    // One tile whose first job uses register set PAR.  Job h of the tile uses set (PAR + h) & 1 and, once its slab is in
+    // LDS, refills that set with the job two ahead: slab h + 2 of this tile, or slab h + 2 - NS of the next, or (NS = 1)
+    // the slab of the tile after the next.
+#define DRC_TILE(PAR)                                                                                         \
+    do {                                                                                                      \
+        const int slot = t & (kStRing - 1);                                                                   \
+        const int buf = (t - t_begin) & 1;                                                                    \
+        DRC_LOAD_HEAD(t + kStRing - 1);                 /* parked when this tile is done */                   \
+        DRC_LOAD_TILE_SIDE(t + 1, ci_next);             /* stored when this tile is done */                   \
+        const int total = sDesc[slot * 4 + 2] * LPR;                                                          \
+        const long long* rec_t = sRec8 + (size_t)buf * ecap;                                                  \
+        const int* start_t = sStart + slot * kStStartPad;                                                     \
+        float out[RPQ][KS];                                                                                   \
+        _Pragma("unroll") for (int ri = 0; ri < RPQ; ++ri)                                                    \
+            _Pragma("unroll") for (int s = 0; s < KS; ++s) out[ri][s] = 0.f;                                  \
+        _Pragma("unroll") for (int h = 0; h < NS; ++h) {                                                      \
+            constexpr int dummy_ = 0; (void)dummy_;                                                           \
+            _Pragma("unroll") for (int u = 0; u < NL; ++u)                                                    \
+                if (u * kStThreads + tid < total)                                                             \
+                    *reinterpret_cast<v4f*>(sTile + (size_t)(u * kStThreads + tid) * 4) = pre[((PAR) + h) & 1][u]; \
+            __syncthreads();     /* the slab (and, first slab, what was parked when the tile before ended) is in LDS */ \
+            DRC_FETCH(((PAR) + h) & 1, t + (h + 2) / NS, (h + 2) % NS);                                       \
+            _Pragma("unroll") for (int ri = 0; ri < RPQ; ++ri) {                                              \
+                const int lr = (ri & 1) ? (ri * NQ + NQ - 1 - q) : (ri * NQ + q);                             \
+                int cur = start_t[min(lr, kStRows)];                                                          \
+                const int end = start_t[min(lr + 1, kStRows)];                                                \
+                v4f acc = {0.f, 0.f, 0.f, 0.f};                                                               \
+                long long rec[kStUnroll];                                                                     \
+                _Pragma("unroll") for (int u = 0; u < kStUnroll; ++u) rec[u] = rec_t[(cur + u < end) ? cur + u : 0]; \
+                while (__any(cur < end)) {                                                                    \
+                    v4f v[kStUnroll];                                                                         \
+                    float w[kStUnroll];                                                                       \
+                    _Pragma("unroll") for (int u = 0; u < kStUnroll; ++u) {                                   \
+                        v[u] = *reinterpret_cast<const v4f*>(sTile + (int)(rec[u] & 0xffffffffLL) * CW + l * 4); \
+                        w[u] = (cur + u < end) ? __int_as_float((int)(rec[u] >> 32)) : 0.f;                   \
+                    }                                                                                         \
+                    cur += kStUnroll;                                                                         \
+                    _Pragma("unroll") for (int u = 0; u < kStUnroll; ++u) rec[u] = rec_t[(cur + u < end) ? cur + u : 0]; \
+                    _Pragma("unroll") for (int u = 0; u < kStUnroll; ++u) {                                   \
+                        acc.x = fmaf(w[u], v[u].x, acc.x);                                                    \
+                        acc.y = fmaf(w[u], v[u].y, acc.y);                                                    \
+                        acc.z = fmaf(w[u], v[u].z, acc.z);                                                    \
+                        acc.w = fmaf(w[u], v[u].w, acc.w);                                                    \
+                    }                                                                                         \
+                }                                                                                             \
+                /* pick the saved columns that fall into this slab (one wavefront's LDS accesses run in program order) */ \
+                *reinterpret_cast<v4f*>(scr + l * 4) = acc;                                                   \
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");                                        \
+                __builtin_amdgcn_wave_barrier();                                                              \
+                _Pragma("unroll") for (int s = 0; s < KS; ++s) {                                              \
+                    const int col = ci[ri][s];                                                                \
+                    const float picked = scr[col % CW];                                                       \
+                    out[ri][s] = (col / CW == h) ? picked : out[ri][s];                                       \
+                }                                                                                             \
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");                                        \
+                __builtin_amdgcn_wave_barrier();                                                              \
+            }                                                                                                 \
+            __syncthreads();      /* nobody reads the slab any more */                                        \
+        }                                                                                                     \
+        _Pragma("unroll") for (int ri = 0; ri < RPQ; ++ri) {                                                  \
+            const int lr = (ri & 1) ? (ri * NQ + NQ - 1 - q) : (ri * NQ + q);                                 \
+            const int row = lr < kStRows ? sRows[slot * kStRows + lr] : -1;                                   \
+            if (row >= 0) {                                                                                   \
+                float* o = dXs + (size_t)row * k;                                                             \
+                _Pragma("unroll") for (int s = 0; s < KS; ++s) {                                              \
+                    const int ts = l + LPR * s;                                                               \
+                    if (ts < k) o[ts] = accumulate ? (o[ts] + out[ri][s]) : out[ri][s];                       \
+                }                                                                                             \
+            }                                                                                                 \
+        }                                                                                                     \
+        DRC_PARK_HEAD(t + kStRing - 1);   /* into the slot of the tile before this one, which nobody reads any more */ \
+        DRC_STORE_RECORDS(t + 1, buf ^ 1);                                                                    \
+        _Pragma("unroll") for (int ri = 0; ri < RPQ; ++ri)                                                    \
+            _Pragma("unroll") for (int s = 0; s < KS; ++s) ci[ri][s] = ci_next[ri][s];                        \
+    } while (0)
+
+    // ---- prologue: nothing to hide behind ----
+    for (int t = t_begin; t < t_begin + kStRing - 1; ++t) {
+        DRC_LOAD_HEAD(t);
+        DRC_PARK_HEAD(t);
     }
-#pragma unroll
-    for (int ri = 0; ri < RPQ; ++ri)
-#pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            const int ts = min(l + LPR * s, k - 1);
-            const int v = (int)__builtin_nontemporal_load(xs_idx + (size_t)max(a.row[ri], 0) * k + ts);
-            ci[ri][s] = (a.row[ri] >= 0 && l + LPR * s < k) ? v : -1;
-        }
-#pragma unroll
-    for (int j = 0; j < kStRecRegs; ++j) {
-        const int e = j * kStThreads + tid;
-        if (e < a.d.y) sRec8[e] = nrec[j];
+    __syncthreads();
+    DRC_LOAD_TILE_SIDE(t_begin, ci);
+    DRC_STORE_RECORDS(t_begin, 0);
+    DRC_FETCH(0, t_begin, 0);
+    DRC_FETCH(1, t_begin + 1 / NS, 1 % NS);
+
+    for (int t = t_begin; t < t_end;) {
+        DRC_TILE(0);
+        if (++t >= t_end) break;
+        DRC_TILE(NS & 1);
+        ++t;
     }
-    if (tid <= kStRows) sRowStart[tid] = a.start;
-
-    for (int t = t_begin; t < t_end; ++t) {
-        const bool has_next = t + 1 < t_end;
-        load_head<NL, RPQ, LPR, NQ>(b, has_next ? t + 1 : t, desc, rows, row_start, cols, ccap, tid);   // needed in the last slab
-        float out[RPQ][KS];
-#pragma unroll
-        for (int ri = 0; ri < RPQ; ++ri)
-#pragma unroll
-            for (int s = 0; s < KS; ++s) out[ri][s] = 0.f;
-        const int total = a.d.z * LPR;
-
-        for (int h = 0; h < n_slabs; ++h) {
-#pragma unroll
-            for (int u = 0; u < NL; ++u) {
-                const int p = u * kStThreads + tid;
-                if (p < total) *reinterpret_cast<v4f*>(sTile + (size_t)p * 4) = pre[u];
-            }
-            __syncthreads();        // the slab, and (first slab) the tile's records and row offsets, are in LDS
-            if (h + 1 < n_slabs) {
-                fetch_slab<NL>(pre, a.col, my_cols + (size_t)(h + 1) * CW, D);
-            } else if (has_next) {
-                fetch_slab<NL>(pre, b.col, my_cols, D);
-#pragma unroll
-                for (int j = 0; j < kStRecRegs; ++j) {
-                    const int e = j * kStThreads + tid;
-                    nrec[j] = __builtin_nontemporal_load(recs8 + b.d.x + min(e, max(b.d.y - 1, 0)));   // read once
-                }
-#pragma unroll
-                for (int ri = 0; ri < RPQ; ++ri)
-#pragma unroll
-                    for (int s = 0; s < KS; ++s) {
-                        const int ts = min(l + LPR * s, k - 1);
-                        const int v = (int)__builtin_nontemporal_load(xs_idx + (size_t)max(b.row[ri], 0) * k + ts);
-                        ci_next[ri][s] = (b.row[ri] >= 0 && l + LPR * s < k) ? v : -1;
-                    }
-            }
-
-            // ---- rows: records are read one trip ahead of the tile reads that need them ----
-#pragma unroll
-            for (int ri = 0; ri < RPQ; ++ri) {
-                const int lr = (ri & 1) ? (ri * NQ + NQ - 1 - q) : (ri * NQ + q);
-                int cur = sRowStart[min(lr, kStRows)];
-                const int end = sRowStart[min(lr + 1, kStRows)];
-                float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-                int2 rec[kStUnroll];
-#pragma unroll
-                for (int u = 0; u < kStUnroll; ++u) rec[u] = sRec[(cur + u < end) ? cur + u : 0];   // past the row: any valid record
-                while (__any(cur < end)) {
-                    float4 v[kStUnroll];
-                    float w[kStUnroll];
-#pragma unroll
-                    for (int u = 0; u < kStUnroll; ++u) {
-                        v[u] = *reinterpret_cast<const float4*>(sTile + rec[u].x * CW + l * 4);
-                        w[u] = (cur + u < end) ? __int_as_float(rec[u].y) : 0.f;                    // ... with weight 0
-                    }
-                    cur += kStUnroll;
-#pragma unroll
-                    for (int u = 0; u < kStUnroll; ++u) rec[u] = sRec[(cur + u < end) ? cur + u : 0];
-#pragma unroll
-                    for (int u = 0; u < kStUnroll; ++u) {
-                        acc.x = fmaf(w[u], v[u].x, acc.x);
-                        acc.y = fmaf(w[u], v[u].y, acc.y);
-                        acc.z = fmaf(w[u], v[u].z, acc.z);
-                        acc.w = fmaf(w[u], v[u].w, acc.w);
-                    }
-                }
-                // pick the saved columns that fall into this slab (one wavefront's LDS accesses run in program order)
-                *reinterpret_cast<float4*>(scr + l * 4) = acc;
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-#pragma unroll
-                for (int s = 0; s < KS; ++s) {
-                    const int col = ci[ri][s];
-                    const float picked = scr[max(col, 0) % CW];
-                    out[ri][s] = (col >= 0 && col / CW == h) ? picked : out[ri][s];
-                }
-                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-            }
-            __syncthreads();      // nobody reads the slab, the records or the row offsets any more
-        }
-
-#pragma unroll
-        for (int ri = 0; ri < RPQ; ++ri) {
-            if (a.row[ri] < 0) continue;
-            float* o = dXs + (size_t)a.row[ri] * k;
-#pragma unroll
-            for (int s = 0; s < KS; ++s) {
-                const int ts = l + LPR * s;
-                if (ts < k) o[ts] = accumulate ? (o[ts] + out[ri][s]) : out[ri][s];
-            }
-        }
-        if (has_next) {
-#pragma unroll
-            for (int j = 0; j < kStRecRegs; ++j) {
-                const int e = j * kStThreads + tid;
-                if (e < b.d.y) sRec8[e] = nrec[j];
-            }
-            if (tid <= kStRows) sRowStart[tid] = b.start;
-        }
-        a = b;
-#pragma unroll
-        for (int ri = 0; ri < RPQ; ++ri)
-#pragma unroll
-            for (int s = 0; s < KS; ++s) ci[ri][s] = ci_next[ri][s];
-    }
+#undef DRC_LOAD_HEAD
+#undef DRC_PARK_HEAD
+#undef DRC_FETCH
+#undef DRC_LOAD_TILE_SIDE
+#undef DRC_STORE_RECORDS
+#undef DRC_TILE
 }
 
 static int lds_limit(int* out) {
@@ -270,28 +261,35 @@ static int lds_limit(int* out) {
     return DR_OK;
 }
 
-template <int CW, int KS>
+template <int CW, int KS, int NS>
 static int launch_staged(const dr_spmm_plan* p, const float* dH, const uint16_t* xs_idx, int k, float* dXs, int accumulate,
                          hipStream_t s) {
     const size_t lds = staged_lds_bytes(p->cw, p->ccap, p->ecap);
     static bool raised = false;      // per instantiation
     if (!raised) {
-        DRC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&spmm_bwd_staged_kernel<CW, KS>),
+        DRC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&spmm_bwd_staged_kernel<CW, KS, NS>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         raised = true;
-        if (getenv("DRC_DEBUG_OCCUPANCY")) {
-            int nb = -1;
-            (void)hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, reinterpret_cast<const void*>(&spmm_bwd_staged_kernel<CW, KS>), kStThreads, lds);
-            fprintf(stderr, "spmm_bwd_staged_kernel<%d,%d>: %zu bytes of LDS, %d workgroups per CU\n", CW, KS, lds, nb);
-        }
     }
     // one persistent workgroup per compute unit, a multiple of the XCD count
     int n_wg = std::min(p->n_cu, p->n_tiles);
     n_wg = (n_wg + kNumXcd - 1) / kNumXcd * kNumXcd;
-    hipLaunchKernelGGL((spmm_bwd_staged_kernel<CW, KS>), dim3((unsigned)n_wg), dim3(kStThreads), lds, s, p->desc, p->rows,
+    hipLaunchKernelGGL((spmm_bwd_staged_kernel<CW, KS, NS>), dim3((unsigned)n_wg), dim3(kStThreads), lds, s, p->desc, p->rows,
                        p->row_start, p->cols, p->recs, dH, xs_idx, dXs, p->D, k, p->n_tiles, p->ccap, p->ecap, accumulate ? 1 : 0);
     DRC_HIP(hipGetLastError());
     return DR_OK;
+}
+
+template <int CW, int KS>
+static int launch_staged_ns(const dr_spmm_plan* p, const float* dH, const uint16_t* xs_idx, int k, float* dXs, int accumulate,
+                            hipStream_t s) {
+    switch (p->D / CW) {
+        case 1: return launch_staged<CW, KS, 1>(p, dH, xs_idx, k, dXs, accumulate, s);
+        case 2: return launch_staged<CW, KS, 2>(p, dH, xs_idx, k, dXs, accumulate, s);
+        case 3: return launch_staged<CW, KS, 3>(p, dH, xs_idx, k, dXs, accumulate, s);
+        case 4: return launch_staged<CW, KS, 4>(p, dH, xs_idx, k, dXs, accumulate, s);
+    }
+    return fail(DR_ERR_UNSUPPORTED, "dr_spmm_bwd_planned: D = %d needs more than 4 column slabs", p->D);
 }
 
 int launch_spmm_bwd_planned(const dr_spmm_plan* p, const float* dH, const uint16_t* xs_idx, int k, float* dXs, int accumulate,
@@ -305,10 +303,10 @@ int launch_spmm_bwd_planned(const dr_spmm_plan* p, const float* dH, const uint16
     const int ks = (k + lpr - 1) / lpr;
 #define DRC_STAGED(CW)                                                                              \
     do {                                                                                            \
-        if (ks <= 1) return launch_staged<CW, 1>(p, dH, xs_idx, k, dXs, accumulate, s);             \
-        if (ks <= 2) return launch_staged<CW, 2>(p, dH, xs_idx, k, dXs, accumulate, s);             \
-        if (ks <= 4) return launch_staged<CW, 4>(p, dH, xs_idx, k, dXs, accumulate, s);             \
-        if (ks <= 8) return launch_staged<CW, 8>(p, dH, xs_idx, k, dXs, accumulate, s);             \
+        if (ks <= 1) return launch_staged_ns<CW, 1>(p, dH, xs_idx, k, dXs, accumulate, s);          \
+        if (ks <= 2) return launch_staged_ns<CW, 2>(p, dH, xs_idx, k, dXs, accumulate, s);          \
+        if (ks <= 4) return launch_staged_ns<CW, 4>(p, dH, xs_idx, k, dXs, accumulate, s);          \
+        if (ks <= 8) return launch_staged_ns<CW, 8>(p, dH, xs_idx, k, dXs, accumulate, s);          \
     } while (0)
     if (p->cw == 64) DRC_STAGED(64);
     else DRC_STAGED(32);

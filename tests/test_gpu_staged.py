@@ -97,6 +97,49 @@ def test_planned_bwd_on_a_placed_near_relation():
     assert plain.dr_spmm_plan_info()[1] < reuse          # rows of one grid line share fewer neighbours than a square patch
 
 
+def test_layer_backward_with_a_cell_order_equals_the_layer_without():
+    """heteroconv_set_cell_order switches the transposed `near` DR-SpMM of the layer's backward to the staged kernel:
+    same gradients (bit for bit on cells that feed at most 32 destinations, where both kernels sum in storage order;
+    within the rounding of a different summation order elsewhere), and the whole layer still matches the oracle."""
+    from circuit_synth import make_tensors
+    g = make_graph("small", seed=0)
+    D, k = 64, 16
+    T = make_tensors(g.Nc, g.Nn, D, seed=0)
+    rels = [P.device_relation(g.near, P.DR_NORM_MEAN), P.device_relation(g.pins, P.DR_NORM_MEAN),
+            P.device_relation(g.pinned, P.DR_NORM_SYM)]
+    layer = P.HeteroConv(*rels, D, k, k)
+    saved = layer.alloc_saved()
+    Wd = {n: dev(T.W[n]) for n in P.WEIGHT_NAMES}
+    Yc = torch.empty((g.Nc, D), device="cuda")
+    Yn = torch.empty((g.Nn, D), device="cuda")
+    layer.heteroconv_fwd(dev(T.X_cell), dev(T.X_net), Wd, Yc, Yn, saved)
+
+    def backward():
+        dXc = torch.full((g.Nc, D), float("nan"), device="cuda")
+        dXn = torch.full((g.Nn, D), float("nan"), device="cuda")
+        dW = {n: torch.empty((D, D), device="cuda") for n in P.WEIGHT_NAMES}
+        layer.heteroconv_bwd(dev(T.dY_cell), dev(T.dY_net), Wd, saved, dXc, dXn, dW)
+        torch.cuda.synchronize()
+        return dXc.cpu().numpy(), dXn.cpu().numpy(), {n: dW[n].cpu().numpy() for n in dW}
+
+    plain = backward()
+    assert layer.heteroconv_set_cell_order(dev(g.cell_order)) is True
+    staged = backward()
+    out_deg = np.bincount(g.near.colidx, minlength=g.Nc)          # destinations a cell feeds = edges of its row of near^T
+    short = out_deg <= 32
+    assert short.mean() > 0.9
+    assert np.array_equal(plain[0][short], staged[0][short])
+    scale = np.abs(plain[0]).sum(axis=1, keepdims=True) + 1e-30
+    assert np.all(np.abs(plain[0] - staged[0]) <= 1e-6 * scale)
+    assert np.array_equal(plain[1], staged[1])
+    for n in P.WEIGHT_NAMES:
+        assert np.array_equal(plain[2][n], staged[2][n]), n
+    # a random order shares too few neighbours per tile: the layer keeps the plain kernel
+    assert layer.heteroconv_set_cell_order(dev(np.random.default_rng(0).permutation(g.Nc).astype(np.int32))) is False
+    assert np.array_equal(backward()[0], plain[0])
+    layer.heteroconv_destroy()
+
+
 def test_plan_refusals():
     rng = np.random.default_rng(0)
     lib = P.load()
