@@ -19,6 +19,9 @@
 #include "dr_internal.h"
 
 #include <cmath>
+#include <condition_variable>
+#include <functional>
+#include <mutex>
 #include <new>
 #include <string>
 #include <thread>
@@ -188,6 +191,74 @@ struct GraphState {
 
 }  // namespace drc
 
+namespace drc {
+// Host threads that enqueue the sub-graphs of a step side by side.  They are started once, with the model, and sleep
+// between steps: starting and joining threads on every step costs more than enqueueing a small sub-graph.
+class EnqueuePool {
+  public:
+    EnqueuePool(int n_threads, int device) : rcs_(n_threads, DR_OK), errs_(n_threads) {
+        for (int w = 0; w < n_threads; ++w)
+            threads_.emplace_back([this, w, device]() {
+                const bool dev_ok = hipSetDevice(device) == hipSuccess;
+                unsigned long long seen = 0;
+                for (;;) {
+                    std::unique_lock<std::mutex> lock(mu_);
+                    wake_.wait(lock, [&] { return stop_ || generation_ != seen; });
+                    if (stop_) return;
+                    seen = generation_;
+                    lock.unlock();
+                    int rc = DR_OK;
+                    if (!dev_ok) { rc = DR_ERR_HIP; errs_[w] = "hipSetDevice failed in a worker thread"; }
+                    for (int q = w; q < n_items_ && rc == DR_OK; q += (int)threads_.size()) {
+                        rc = (*job_)(q);
+                        if (rc != DR_OK) errs_[w] = dr_last_error();     // the error text is per thread: hand it over
+                    }
+                    rcs_[w] = rc;
+                    lock.lock();
+                    if (--pending_ == 0) done_.notify_all();
+                }
+            });
+    }
+    ~EnqueuePool() {
+        {
+            std::lock_guard<std::mutex> lock(mu_);
+            stop_ = true;
+        }
+        wake_.notify_all();
+        for (auto& t : threads_) t.join();
+    }
+    // Runs job(q) for q = 0 .. n_items-1, item q on thread q % n_threads, and waits for all of them.  Returns the first
+    // failing status (with its message in *err) after every thread has finished its items.
+    int run(int n_items, const std::function<int(int)>& job, std::string* err) {
+        {
+            std::lock_guard<std::mutex> lock(mu_);
+            job_ = &job;
+            n_items_ = n_items;
+            pending_ = (int)threads_.size();
+            ++generation_;
+        }
+        wake_.notify_all();
+        std::unique_lock<std::mutex> lock(mu_);
+        done_.wait(lock, [&] { return pending_ == 0; });
+        for (size_t w = 0; w < rcs_.size(); ++w)
+            if (rcs_[w] != DR_OK) { *err = errs_[w]; return rcs_[w]; }
+        return DR_OK;
+    }
+
+  private:
+    std::vector<std::thread> threads_;
+    std::mutex mu_;
+    std::condition_variable wake_, done_;
+    const std::function<int(int)>* job_ = nullptr;
+    int n_items_ = 0, pending_ = 0;
+    unsigned long long generation_ = 0;
+    bool stop_ = false;
+    std::vector<int> rcs_;
+    std::vector<std::string> errs_;
+};
+
+}  // namespace drc
+
 struct dr_hgnn {
     int n_graphs, L, D;                        // n_graphs: states that are stepped (1 for a batched model)
     int n_user;                                // sub-graphs the caller sees
@@ -206,6 +277,7 @@ struct dr_hgnn {
     int n_head_parts;                          // read-out partials of all states together
     hipEvent_t fork;
     int device;
+    drc::EnqueuePool* pool;                    // more than one state: the threads that enqueue them side by side
 };
 
 using namespace drc;
@@ -222,6 +294,7 @@ int model_alloc(dr_hgnn* m, void** p, size_t bytes) {
 
 void model_release(dr_hgnn* m) {
     if (!m) return;
+    delete m->pool;
     for (void* p : m->owned) (void)hipFree(p);
     for (auto& gs : m->g) {
         if (gs.stream) (void)hipStreamDestroy(gs.stream);
@@ -393,6 +466,10 @@ static int create_model(dr_hgnn** model, int32_t n_graphs, dr_heteroconv* const*
             DRC_TRY(alloc_t(m, &gs.dpred, nc));
         }
         DRC_HIP(hipDeviceSynchronize());
+        if (m->n_graphs > 1) {
+            m->pool = new (std::nothrow) EnqueuePool(m->n_graphs < kMaxWorkers ? m->n_graphs : kMaxWorkers, m->device);
+            DRC_REQUIRE(m->pool != nullptr, "hgnn_create: out of host memory");
+        }
         return DR_OK;
     };
     rc = body();
@@ -471,8 +548,8 @@ int hgnn_train_step(dr_hgnn* m, const float* const* X_cell, const float* const* 
     const float scale = (float)(2.0 / (double)m->n_cells_total);
 
     DRC_HIP(hipEventRecord(m->fork, user));
-    // One sub-graph = one stream = one host thread: a step of small sub-graphs issues several hundred launches
-    // and event operations, and a single host thread cannot enqueue them as fast as the GPU drains them.
+    // One sub-graph = one stream = one host thread (of the model's pool): a step of small sub-graphs issues several
+    // hundred launches and event operations, and a single host thread cannot enqueue them as fast as the GPU drains them.
     auto enqueue_graph = [&](int q) -> int {
         GraphState& gs = m->g[q];
         hipStream_t s = gs.stream;
@@ -514,23 +591,25 @@ int hgnn_train_step(dr_hgnn* m, const float* const* X_cell, const float* const* 
         DRC_HIP(hipEventRecord(gs.done, s));
         return DR_OK;
     };
+    // Whatever a sub-graph's enqueueing ends with, its `done` event is recorded behind what did get enqueued, and the
+    // caller's stream waits for every sub-graph before this call returns -- also when one of them failed, so that no
+    // work of this step is still reading theta or the gradient buffers once the caller sees the error.
+    const std::function<int(int)> enqueue_and_mark = [&](int q) -> int {
+        const int rc = enqueue_graph(q);
+        if (rc != DR_OK) (void)hipEventRecord(m->g[q].done, m->g[q].stream);
+        return rc;
+    };
+    int step_rc = DR_OK;
+    std::string step_err;
     if (m->n_graphs == 1) {
-        DRC_TRY(enqueue_graph(0));
+        step_rc = enqueue_and_mark(0);
+        if (step_rc != DR_OK) step_err = dr_last_error();
     } else {
-        const int n_workers = m->n_graphs < kMaxWorkers ? m->n_graphs : kMaxWorkers;
-        std::vector<int> rcs(n_workers, DR_OK);
-        std::vector<std::string> errs(n_workers);
-        std::vector<std::thread> workers;
-        workers.reserve(n_workers);
-        for (int w = 0; w < n_workers; ++w)
-            workers.emplace_back([&, w]() {
-                if (hipSetDevice(m->device) != hipSuccess) { rcs[w] = DR_ERR_HIP; errs[w] = "hipSetDevice failed in a worker thread"; return; }
-                for (int q = w; q < m->n_graphs && rcs[w] == DR_OK; q += n_workers) rcs[w] = enqueue_graph(q);
-                if (rcs[w] != DR_OK) errs[w] = dr_last_error();      // the error text is per thread: hand it over
-            });
-        for (auto& t : workers) t.join();
-        for (int w = 0; w < n_workers; ++w)
-            if (rcs[w] != DR_OK) return fail(rcs[w], "%s", errs[w].c_str());
+        step_rc = m->pool->run(m->n_graphs, enqueue_and_mark, &step_err);
+    }
+    if (step_rc != DR_OK) {
+        for (int q = 0; q < m->n_graphs; ++q) (void)hipStreamWaitEvent(user, m->g[q].done, 0);
+        return fail(step_rc, "%s", step_err.c_str());
     }
     for (int q = 0; q < m->n_graphs; ++q) DRC_HIP(hipStreamWaitEvent(user, m->g[q].done, 0));
 

@@ -363,6 +363,46 @@ def test_full_size_step_of_eight_subgraphs():
         c.heteroconv_destroy()
 
 
+@pytest.mark.skip(reason="Capturing hgnn_train_step into a HIP graph ended in a host segmentation fault inside the call "
+                         "(record: all sub-graphs had been enqueued with status 0; the fault came after that, on the capturing "
+                         "thread, in the part of the step that joins the sub-graph streams back into the caller's stream).  "
+                         "What the code did at that point and a capture does not allow for: the sub-graphs' launches were "
+                         "appended to the one capture from several host threads at once (the enqueue workers), on streams that "
+                         "entered the capture only through an event wait issued from those other threads.  The cause has not "
+                         "been shown on the host side, so the capture is not run on the GPU; the library has no capture path.")
+def test_graph_replay_matches_eager_steps():
+    """Three training steps replayed from one captured HIP graph equal three eager steps bit for bit (every replay is
+    compared, with eager work and synchronisations between the replays)."""
+    D, k, L = 128, 32, 2
+    graphs, rels, ctxs, keep, Xc, Xn, tg, theta0 = _setup(4, 1200, 800, (40, 30), D, k, L)
+    Xc, Xn, tg = [dev(a) for a in Xc], [dev(a) for a in Xn], [dev(a) for a in tg]
+    n_par = P.hgnn_num_params(L, D)
+
+    def state():
+        return (dev(theta0), torch.zeros(n_par, device="cuda"), torch.zeros(n_par, device="cuda"),
+                torch.empty(n_par, device="cuda"), torch.empty(1, device="cuda"))
+
+    model = P.Hgnn(ctxs, L)
+    th_e, m_e, v_e, g_e, l_e = state()
+    eager = []
+    for step in (1, 1, 1):      # the captured step carries step = 1; each eager reference restarts from the same state
+        th_e, m_e, v_e, g_e, l_e = state()
+        model.hgnn_train_step(Xc, Xn, tg, th_e, m_e, v_e, LR, B1, B2, EPS, WD, step, g_e, l_e)
+        torch.cuda.synchronize()
+        eager.append((th_e.clone(), g_e.clone(), l_e.clone()))
+    th, m, v, g, l = state()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        model.hgnn_train_step(Xc, Xn, tg, th, m, v, LR, B1, B2, EPS, WD, 1, g, l)
+    for want in eager:
+        th.copy_(dev(theta0)); m.zero_(); v.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(th, want[0]) and torch.equal(g, want[1]) and torch.equal(l, want[2])
+    model.hgnn_destroy()
+
+
 def test_block_diagonal_batch_equals_separate_subgraphs():
     """Independent sub-graphs stacked into one block-diagonal graph give the same step (one launch per kernel
     for the whole batch instead of one per sub-graph): same selections, same loss and gradient up to the order
