@@ -156,7 +156,8 @@ int dr_spmm_bwd_adaptive(const dr_csr* At, const uint8_t* edge_class, const floa
  * Setup: stable CSR transpose (Alg. 2 stage 1, "transpose A to CSC").  Row j of the result lists the
  * entries of column j of A in increasing original row and, for equal rows, original storage order.
  * Outputs t_rowptr[n_cols+1], t_colidx[nnz], t_vals[nnz] (t_vals and A->vals may both be NULL for a
- * pattern-only transpose).  Integer-exact and deterministic.  workspace: device scratch of at least
+ * pattern-only transpose).  Integer-exact and deterministic.  Every A->colidx must lie in [0, n_cols) and rowptr must
+ * be non-decreasing with rowptr[n_rows] == nnz (device data, not checked).  workspace: device scratch of at least
  * dr_csr_transpose_workspace_bytes() bytes, 256-byte aligned, contents undefined before and after.
  */
 size_t dr_csr_transpose_workspace_bytes(int64_t n_rows, int64_t n_cols, int64_t nnz);

@@ -151,9 +151,9 @@ static size_t align256(size_t b) { return (b + 255) & ~size_t(255); }
 size_t dr_csr_transpose_workspace_bytes(int64_t n_rows, int64_t n_cols, int64_t nnz) {
     (void)n_rows;
     if (n_cols < 0 || nnz < 0) return 0;
-    // cursor[n_cols] | edge key[nnz] | edge row[nnz] | block sums
+    // cursor[n_cols] | edge key[nnz] | edge row[nnz] | block sums | counter and list of the rows of more than 64 entries
     return align256(4 * (size_t)(n_cols + 1)) + 2 * align256(4 * (size_t)(nnz + 1)) +
-           align256(4 * ((size_t)(n_cols + 1) / 1024 + 2));
+           align256(4 * ((size_t)(n_cols + 1) / 1024 + 2)) + align256(4 * ((size_t)n_cols + 64));
 }
 
 int dr_csr_transpose(const dr_csr* A, int32_t* t_rowptr, int32_t* t_colidx, float* t_vals, void* workspace,

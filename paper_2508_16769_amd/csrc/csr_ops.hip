@@ -108,7 +108,8 @@ int launch_csr_normalize_noalloc(int mode, int64_t n_rows, int64_t n_cols, int64
 //   3. every entry e takes some slot of its column segment (atomic cursor) and records key e there
 //   4. per segment, each entry's final place is the number of smaller keys in the segment: increasing e
 //      is exactly "increasing original row, then storage order", so the result is the stable order
-//      whatever slots step 3 handed out.
+//      whatever slots step 3 handed out.  Segments of up to 16 entries are ranked inside a group of 16 lanes, up to
+//      64 inside a wavefront, longer ones (high-fanout nets) by a workgroup through LDS.
 // ---------------------------------------------------------------------------------------------------
 
 constexpr int kScanBlock = 1024;
@@ -187,23 +188,97 @@ __global__ void transpose_scatter_kernel(const int32_t* __restrict__ rowptr, con
     key[slot] = e;
 }
 
-// one wavefront per output row
+// Step 4 for rows of up to 64 entries.  A group of 16 lanes owns one output row (four rows per wavefront): its keys
+// sit in the group's registers and every entry counts the smaller keys of its row through 15 lane rotations.  Rows of
+// 17 .. 64 entries are then ranked by the whole wavefront, one after the other, their keys broadcast lane by lane.
+// Longer rows are only noted down (in any order: each is handled on its own by the kernel below).
 __global__ __launch_bounds__(256) void transpose_place_kernel(const int32_t* __restrict__ t_rowptr, int n_cols,
                                                               const int32_t* __restrict__ key,
                                                               const int32_t* __restrict__ erow,
                                                               const float* __restrict__ vals,
                                                               int32_t* __restrict__ t_colidx,
-                                                              float* __restrict__ t_vals) {
-    const int lane = threadIdx.x & 63;
-    const int j = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-    if (j >= n_cols) return;
-    const int b = t_rowptr[j], e = t_rowptr[j + 1];
-    for (int p = b + lane; p < e; p += kWave) {
-        int my = key[p];
+                                                              float* __restrict__ t_vals,
+                                                              int32_t* __restrict__ long_rows,
+                                                              int32_t* __restrict__ n_long) {
+    const int lane = threadIdx.x & 63, l = lane & 15, grp = lane >> 4;
+    const int wave = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const int j = wave * 4 + grp;
+    const int b = j < n_cols ? t_rowptr[j] : 0;
+    const int d = j < n_cols ? t_rowptr[j + 1] - b : 0;
+    if (d <= 16) {
+        const int my = l < d ? key[b + l] : 0x7fffffff;        // padding keys rank behind every entry
         int rank = 0;
-        for (int q = b; q < e; ++q) rank += (key[q] < my) ? 1 : 0;
-        t_colidx[b + rank] = erow[my];
-        if (t_vals) t_vals[b + rank] = vals[my];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) rank += (__shfl(my, (l + r) & 15, 16) < my) ? 1 : 0;
+        if (l < d) {
+            t_colidx[b + rank] = erow[my];
+            if (t_vals) t_vals[b + rank] = vals[my];
+        }
+    }
+    // rows of this wavefront that one group cannot hold
+    for (int g = 0; g < 4; ++g) {
+        const int dg = __builtin_amdgcn_readfirstlane(__shfl(d, g * 16, 64));      // wave-uniform by construction
+        const int bg = __builtin_amdgcn_readfirstlane(__shfl(b, g * 16, 64));
+        if (dg <= 16) continue;
+        if (dg > 64) {
+            if (lane == 0) long_rows[atomicAdd(n_long, 1)] = wave * 4 + g;
+            continue;
+        }
+        const int my = lane < dg ? key[bg + lane] : 0x7fffffff;
+        int rank = 0;
+        for (int q = 0; q < dg; ++q) rank += (__builtin_amdgcn_readlane(my, q) < my) ? 1 : 0;
+        if (lane < dg) {
+            t_colidx[bg + rank] = erow[my];
+            if (t_vals) t_vals[bg + rank] = vals[my];
+        }
+    }
+}
+
+// Step 4 for the rows noted down above: one workgroup per row; the row's keys pass through LDS in chunks and every
+// entry adds up, chunk by chunk, how many keys are smaller than its own.
+constexpr int kLongChunk = 2048;
+__global__ __launch_bounds__(256) void transpose_place_long_kernel(const int32_t* __restrict__ t_rowptr,
+                                                                   const int32_t* __restrict__ long_rows,
+                                                                   const int32_t* __restrict__ n_long,
+                                                                   const int32_t* __restrict__ key,
+                                                                   const int32_t* __restrict__ erow,
+                                                                   const float* __restrict__ vals,
+                                                                   int32_t* __restrict__ t_colidx,
+                                                                   float* __restrict__ t_vals) {
+    __shared__ int sKey[kLongChunk];
+    const int total = *n_long;
+    for (int i = blockIdx.x; i < total; i += gridDim.x) {
+        const int j = long_rows[i];
+        const int b = t_rowptr[j], d = t_rowptr[j + 1] - b;
+        for (int p0 = 0; p0 < d; p0 += 256 * 4) {               // four entries per thread and pass
+            int my[4], rank[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int p = p0 + u * 256 + (int)threadIdx.x;
+                my[u] = p < d ? key[b + p] : 0x7fffffff;
+                rank[u] = 0;
+            }
+            for (int c0 = 0; c0 < d; c0 += kLongChunk) {
+                const int n = min(kLongChunk, d - c0);
+                __syncthreads();
+                for (int q = threadIdx.x; q < n; q += 256) sKey[q] = key[b + c0 + q];
+                __syncthreads();
+                for (int q = 0; q < n; ++q) {
+                    const int kq = sKey[q];                     // every lane reads the same word: a broadcast
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) rank[u] += (kq < my[u]) ? 1 : 0;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int p = p0 + u * 256 + (int)threadIdx.x;
+                if (p < d) {
+                    t_colidx[b + rank[u]] = erow[my[u]];
+                    if (t_vals) t_vals[b + rank[u]] = vals[my[u]];
+                }
+            }
+        }
+        __syncthreads();
     }
 }
 
@@ -220,7 +295,11 @@ int launch_csr_transpose(const dr_csr* A, int32_t* t_rowptr, int32_t* t_colidx, 
     int32_t* erow = reinterpret_cast<int32_t*>(w);
     w += align256(4 * (size_t)(nnz + 1));
     int32_t* sums = reinterpret_cast<int32_t*>(w);
+    w += align256(4 * ((size_t)(n_cols + 1) / 1024 + 2));
+    int32_t* n_long = reinterpret_cast<int32_t*>(w);            // [1] (+ padding), then the rows of more than 64 entries
+    int32_t* long_rows = n_long + 64;
 
+    if (int rc = launch_fill_u32(reinterpret_cast<uint32_t*>(n_long), 1, 0u, s)) return rc;
     if (int rc = launch_fill_u32(reinterpret_cast<uint32_t*>(t_rowptr), (size_t)n_cols + 1, 0u, s)) return rc;
     if (int rc = launch_fill_u32(reinterpret_cast<uint32_t*>(cursor), (size_t)n_cols + 1, 0u, s)) return rc;
     if (nnz > 0) {
@@ -233,9 +312,11 @@ int launch_csr_transpose(const dr_csr* A, int32_t* t_rowptr, int32_t* t_colidx, 
         hipLaunchKernelGGL(scan_apply_kernel, dim3(nb), dim3(kScanBlock), 0, s, t_rowptr + 1, n_cols, sums);
         hipLaunchKernelGGL(transpose_scatter_kernel, dim3(eb), dim3(256), 0, s, A->rowptr, A->colidx, n_rows, nnz,
                            t_rowptr, cursor, key, erow);
-        unsigned pb = (unsigned)((n_cols + 3) / 4);
+        unsigned pb = (unsigned)((n_cols + 15) / 16);          // 16 output rows per workgroup of four wavefronts
         hipLaunchKernelGGL(transpose_place_kernel, dim3(pb), dim3(256), 0, s, t_rowptr, n_cols, key, erow, A->vals,
-                           t_colidx, t_vals);
+                           t_colidx, t_vals, long_rows, n_long);
+        hipLaunchKernelGGL(transpose_place_long_kernel, dim3(2048), dim3(256), 0, s, t_rowptr, long_rows, n_long, key, erow,
+                           A->vals, t_colidx, t_vals);
     }
     DRC_HIP(hipGetLastError());
     return DR_OK;
