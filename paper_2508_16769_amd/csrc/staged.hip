@@ -89,11 +89,15 @@ __global__ __launch_bounds__(kStThreads) void spmm_bwd_staged_kernel(
     int* sStart = sRows + kStRing * kStRows;                                     // [kStRing][kStStartPad]
     int* sDesc = sStart + kStRing * kStStartPad;                                 // [kStRing][4] (record offset, records, gathered rows, rows)
 
-    // contiguous tile ranges, and neighbouring ranges on one XCD (workgroups are dealt to the XCDs round-robin)
-    const int n_wg = gridDim.x;
-    const int wg = (blockIdx.x % kNumXcd) * (n_wg / kNumXcd) + blockIdx.x / kNumXcd;
-    const int t_begin = (int)((long long)wg * n_tiles / n_wg), t_end = (int)((long long)(wg + 1) * n_tiles / n_wg);
-    if (t_begin >= t_end) return;
+    // Each XCD owns one contiguous range of tiles (workgroups are dealt to the XCDs round-robin) and its workgroups walk
+    // it abreast: at step i the XCD's L workgroups hold L consecutive tiles -- with a placement order one compact patch
+    // of the layout, whose shared dH rows the XCD's L2 fetches from memory once.
+    const int L = gridDim.x / kNumXcd, xcd = blockIdx.x % kNumXcd, local = blockIdx.x / kNumXcd;
+    const int x_begin = (int)((long long)xcd * n_tiles / kNumXcd), x_end = (int)((long long)(xcd + 1) * n_tiles / kNumXcd);
+    const int n_my = (x_end - x_begin - local + L - 1) / L;          // tiles of this workgroup: x_begin + local + i * L
+    if (n_my <= 0) return;
+    const int t_begin = 0, t_end = n_my;                             // from here on a tile is named by its step i
+#define DRC_TILE_ID(I) (x_begin + local + min((I), n_my - 1) * L)
 
     const int tid = threadIdx.x;
     const int q = tid / LPR, l = tid % LPR;
@@ -109,7 +113,7 @@ __global__ __launch_bounds__(kStThreads) void spmm_bwd_staged_kernel(
 
 #define DRC_LOAD_HEAD(T)                                                                                      \
     do {                                                                                                      \
-        const int t_ = min((T), t_end - 1);                                                                   \
+        const int t_ = DRC_TILE_ID(T);                                                                        \
         h_col = cols[(size_t)t_ * ccap + min(tid, ccap - 1)];                                                 \
         h_row = rows[(size_t)t_ * kStRows + min(tid, kStRows - 1)];                                           \
         h_start = row_start[(size_t)t_ * (kStRows + 1) + min(tid, kStRows)];                                  \
@@ -245,6 +249,7 @@ __global__ __launch_bounds__(kStThreads) void spmm_bwd_staged_kernel(
         DRC_TILE(NS & 1);
         ++t;
     }
+#undef DRC_TILE_ID
 #undef DRC_LOAD_HEAD
 #undef DRC_PARK_HEAD
 #undef DRC_FETCH
