@@ -433,6 +433,8 @@ def mode_overlap(argv) -> int:
         X = dict(cell=dev(T.X_cell), net=dev(T.X_net))
         dY = dict(cell=dev(T.dY_cell), net=dev(T.dY_net))
         layer = P.HeteroConv(rel["near"], rel["pins"], rel["pinned"], D, k, k)
+        layer.heteroconv_set_cell_order(dev(g.cell_order))           # as bench.py: transposed near on LDS-staged tiles
+        near_plan = P.SpmmPlan(rel_t["near"], D, dev(g.cell_order))
         saved = layer.alloc_saved()
         Wd = {n: dev(T.W[n]) for n in P.WEIGHT_NAMES}
         Yc = torch.empty((g.Nc, D), device="cuda")
@@ -451,7 +453,7 @@ def mode_overlap(argv) -> int:
             torch.cuda.synchronize()
             return (time.perf_counter() - t0) * 1e3 / args.steps
 
-        region = bench.DrRegion(P, torch, rel, rel_t, X, dY, D, k)
+        region = bench.DrRegion(P, torch, rel, rel_t, X, dY, D, k, near_plan)
         l1 = min(layer_ms(P.DR_OVERLAP_OFF) for _ in range(1))
         l3 = layer_ms(P.DR_OVERLAP_ON)
         l1 = min(l1, layer_ms(P.DR_OVERLAP_OFF))
