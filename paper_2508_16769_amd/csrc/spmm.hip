@@ -183,15 +183,17 @@ __device__ __forceinline__ void stage_chunk(const WavePlan& p, const int32_t* __
 // Strided mode (long rows): records g, g + 8, ... of the staged chunk, no row boundaries.
 struct Stream {
     int cur, row_end, row, done;
+    // Every member is assigned on every path (selects, no branches): with a member written on one side of a branch
+    // only, the compiler keeps the record in scratch memory and stores through a selected address, and a scratch
+    // access is a vector-memory operation -- waiting for it drains the gathers in flight.
     __device__ __forceinline__ void take_slot(const WavePlan& p, int li, int sa, int npass, int base) {
-        if (li < npass) {
-            const int s = sa + li;
-            cur = p.sStart[s] - base;
-            row_end = p.sStart[s + 1] - base;
-            row = p.sOrder[s];
-        } else {
-            done = 1;
-        }
+        const bool ok = li < npass;
+        const int s = sa + (ok ? li : 0);
+        const int c = p.sStart[s] - base, e = p.sStart[s + 1] - base, r = p.sOrder[s];
+        cur = ok ? c : cur;
+        row_end = ok ? e : row_end;
+        row = ok ? r : row;
+        done = ok ? done : 1;
     }
     __device__ __forceinline__ void next_row(const WavePlan& p, int sa, int npass, int base) {
         const int lane = threadIdx.x;
