@@ -37,9 +37,10 @@ struct dr_spmm_plan {
     // device arrays; per-tile arrays are padded to a fixed stride so that a tile's entries are found from its number alone
     int4* desc;              // [n_tiles]          (offset of the tile's records, records, distinct gathered rows, rows)
     int32_t* rows;           // [n_tiles][64]      row ids, longest row first; -1 past the tile's rows
-    int32_t* row_start;      // [n_tiles][65]      offsets of the rows' records inside the tile (entries past the rows = records)
+    int32_t* row_start;      // [n_tiles][65]      offsets of the rows' records inside the tile (entries past the rows = records);
+                             //                    every row's records are padded to a multiple of 4 with zero-valued ones
     int32_t* cols;           // [n_tiles][ccap]    distinct gathered rows (padded with a valid one)
-    int2* recs;              // [nnz]              (index of the gathered row within the tile's list, bits of the edge value)
+    int2* recs;              // [n_recs]           (index of the gathered row within the tile's list, bits of the edge value)
     int device, n_cu;
 };
 
@@ -55,11 +56,12 @@ constexpr int kStRing = 4;         // tiles whose heads (gathered rows, row ids,
 constexpr int kStStartPad = kStRows + 4;
 
 __host__ __device__ constexpr size_t staged_lds_bytes(int cw, int ccap, int ecap) {
-    return sizeof(float) * (size_t)ccap * cw + 2 * sizeof(int2) * (size_t)ecap + sizeof(float) * kStThreads * 4 +
-           sizeof(int) * kStRing * ((size_t)ccap + kStRows + kStStartPad + 4);
+    return sizeof(float) * (size_t)ccap * cw + 2 * sizeof(int2) * (size_t)ecap + sizeof(int2) * kStUnroll +
+           sizeof(float) * kStThreads * 4 + sizeof(int) * kStRing * ((size_t)ccap + kStRows + kStStartPad + 4);
 }
 
 typedef float v4f __attribute__((ext_vector_type(4)));     // a native vector: arrays of it stay in registers
+typedef int v4i __attribute__((ext_vector_type(4)));
 
 // A persistent workgroup walks a contiguous range of tiles; the work is a stream of jobs (tile, column slab).  While it
 // computes on one job, the loads of the next two are in flight in two register sets, each written to LDS after the
@@ -83,7 +85,8 @@ __global__ __launch_bounds__(kStThreads) void spmm_bwd_staged_kernel(
     extern __shared__ float4 smem4[];
     float* sTile = reinterpret_cast<float*>(smem4);                              // [ccap][CW]
     long long* sRec8 = reinterpret_cast<long long*>(sTile + (size_t)ccap * CW);  // [2][ecap] records of this tile / the next
-    float* sScr = reinterpret_cast<float*>(sRec8 + 2 * (size_t)ecap);            // [NQ][CW]
+    long long* sZero = sRec8 + 2 * (size_t)ecap;                                 // [kStUnroll] records of value zero: what a lane group reads once its row has ended
+    float* sScr = reinterpret_cast<float*>(sZero + kStUnroll);                   // [NQ][CW]
     int* sCols = reinterpret_cast<int*>(sScr + kStThreads * 4);                  // [kStRing][ccap]
     int* sRows = sCols + kStRing * ccap;                                         // [kStRing][kStRows]
     int* sStart = sRows + kStRing * kStRows;                                     // [kStRing][kStStartPad]
@@ -153,7 +156,9 @@ __global__ __launch_bounds__(kStThreads) void spmm_bwd_staged_kernel(
     do {                                                                                                      \
         const int ne_ = sDesc[(min((T), t_end - 1) & (kStRing - 1)) * 4 + 1];                                 \
         _Pragma("unroll") for (int j_ = 0; j_ < kStRecRegs; ++j_)                                             \
-            if (j_ * kStThreads + tid < ne_) sRec8[(size_t)(BUF) * ecap + j_ * kStThreads + tid] = nrec[j_];   \
+            if (j_ * kStThreads + tid < ne_)                                                                  \
+                sRec8[(size_t)(BUF) * ecap + j_ * kStThreads + tid] =                                         \
+                    (nrec[j_] & 0xffffffff00000000LL) | (long long)((uint32_t)nrec[j_] * (uint32_t)(CW * 4));  /* index -> byte offset of the row in the slab */ \
     } while (0)
 
     // One tile whose first job uses register set PAR.  Job h of the tile uses set (PAR + h) & 1 and, once its slab is in
@@ -180,26 +185,28 @@ __global__ __launch_bounds__(kStThreads) void spmm_bwd_staged_kernel(
             DRC_FETCH(((PAR) + h) & 1, t + (h + 2) / NS, (h + 2) % NS);                                       \
             _Pragma("unroll") for (int ri = 0; ri < RPQ; ++ri) {                                              \
                 const int lr = (ri & 1) ? (ri * NQ + NQ - 1 - q) : (ri * NQ + q);                             \
-                int cur = start_t[min(lr, kStRows)];                                                          \
+                int cur = start_t[min(lr, kStRows)];            /* in records; every row starts at a multiple of kStUnroll */ \
                 const int end = start_t[min(lr + 1, kStRows)];                                                \
                 v4f acc = {0.f, 0.f, 0.f, 0.f};                                                               \
-                long long rec[kStUnroll];                                                                     \
-                _Pragma("unroll") for (int u = 0; u < kStUnroll; ++u) rec[u] = rec_t[(cur + u < end) ? cur + u : 0]; \
+                const char* const tile_l = reinterpret_cast<const char*>(sTile) + l * 16;                     \
+                /* four records per trip, two 16-byte LDS reads; a group whose row has ended reads the zero records */ \
+                const v4i* chunk = reinterpret_cast<const v4i*>(cur < end ? rec_t + cur : sZero);             \
+                v4i r01 = chunk[0], r23 = chunk[1];                                                           \
                 while (__any(cur < end)) {                                                                    \
-                    v4f v[kStUnroll];                                                                         \
-                    float w[kStUnroll];                                                                       \
-                    _Pragma("unroll") for (int u = 0; u < kStUnroll; ++u) {                                   \
-                        v[u] = *reinterpret_cast<const v4f*>(sTile + (int)(rec[u] & 0xffffffffLL) * CW + l * 4); \
-                        w[u] = (cur + u < end) ? __int_as_float((int)(rec[u] >> 32)) : 0.f;                   \
-                    }                                                                                         \
+                    const v4f v0 = *reinterpret_cast<const v4f*>(tile_l + (uint32_t)r01.x);                   \
+                    const v4f v1 = *reinterpret_cast<const v4f*>(tile_l + (uint32_t)r01.z);                   \
+                    const v4f v2 = *reinterpret_cast<const v4f*>(tile_l + (uint32_t)r23.x);                   \
+                    const v4f v3 = *reinterpret_cast<const v4f*>(tile_l + (uint32_t)r23.z);                   \
+                    const float w0 = __int_as_float(r01.y), w1 = __int_as_float(r01.w);                       \
+                    const float w2 = __int_as_float(r23.y), w3 = __int_as_float(r23.w);                       \
                     cur += kStUnroll;                                                                         \
-                    _Pragma("unroll") for (int u = 0; u < kStUnroll; ++u) rec[u] = rec_t[(cur + u < end) ? cur + u : 0]; \
-                    _Pragma("unroll") for (int u = 0; u < kStUnroll; ++u) {                                   \
-                        acc.x = fmaf(w[u], v[u].x, acc.x);                                                    \
-                        acc.y = fmaf(w[u], v[u].y, acc.y);                                                    \
-                        acc.z = fmaf(w[u], v[u].z, acc.z);                                                    \
-                        acc.w = fmaf(w[u], v[u].w, acc.w);                                                    \
-                    }                                                                                         \
+                    chunk = reinterpret_cast<const v4i*>(cur < end ? rec_t + cur : sZero);                    \
+                    r01 = chunk[0];                                                                           \
+                    r23 = chunk[1];                                                                           \
+                    acc.x = fmaf(w0, v0.x, acc.x); acc.y = fmaf(w0, v0.y, acc.y); acc.z = fmaf(w0, v0.z, acc.z); acc.w = fmaf(w0, v0.w, acc.w); \
+                    acc.x = fmaf(w1, v1.x, acc.x); acc.y = fmaf(w1, v1.y, acc.y); acc.z = fmaf(w1, v1.z, acc.z); acc.w = fmaf(w1, v1.w, acc.w); \
+                    acc.x = fmaf(w2, v2.x, acc.x); acc.y = fmaf(w2, v2.y, acc.y); acc.z = fmaf(w2, v2.z, acc.z); acc.w = fmaf(w2, v2.w, acc.w); \
+                    acc.x = fmaf(w3, v3.x, acc.x); acc.y = fmaf(w3, v3.y, acc.y); acc.z = fmaf(w3, v3.z, acc.z); acc.w = fmaf(w3, v3.w, acc.w); \
                 }                                                                                             \
                 /* pick the saved columns that fall into this slab (one wavefront's LDS accesses run in program order) */ \
                 *reinterpret_cast<v4f*>(scr + l * 4) = acc;                                                   \
@@ -233,6 +240,7 @@ __global__ __launch_bounds__(kStThreads) void spmm_bwd_staged_kernel(
     } while (0)
 
     // ---- prologue: nothing to hide behind ----
+    if (tid < kStUnroll) sZero[tid] = 0;
     for (int t = t_begin; t < t_begin + kStRing - 1; ++t) {
         DRC_LOAD_HEAD(t);
         DRC_PARK_HEAD(t);
@@ -323,6 +331,8 @@ int launch_spmm_bwd_planned(const dr_spmm_plan* p, const float* dH, const uint16
 // plan: tiles from the processing order (host side; once per relation)
 // ---------------------------------------------------------------------------------------------------
 
+static inline int pad_unroll(int deg) { return (deg + kStUnroll - 1) / kStUnroll * kStUnroll; }
+
 int spmm_plan_create(dr_spmm_plan** out, const dr_csr* A, const int32_t* row_order, int D, hipStream_t s) {
     *out = nullptr;
     const int cw = (D % 64 == 0) ? 64 : ((D % 32 == 0) ? 32 : 0);
@@ -379,7 +389,7 @@ int spmm_plan_create(dr_spmm_plan** out, const dr_csr* A, const int32_t* row_ord
                     fresh.push_back(c);
                 }
             }
-            const bool fits = ncur + (int)fresh.size() <= ccap && ecur + deg <= ecap && rows_in < kStRows;
+            const bool fits = ncur + (int)fresh.size() <= ccap && ecur + pad_unroll(deg) <= ecap && rows_in < kStRows;
             if (fits) break;
             for (int32_t c : fresh) stamp[(size_t)c] = -1;
             if (rows_in == 0)
@@ -392,7 +402,7 @@ int spmm_plan_create(dr_spmm_plan** out, const dr_csr* A, const int32_t* row_ord
         }
         cols.insert(cols.end(), fresh.begin(), fresh.end());
         ncur += (int)fresh.size();
-        ecur += deg;
+        ecur += pad_unroll(deg);
         ++rows_in;
         // the row's records are written below, once the tile's internal order is known; remember the local indices now
         for (int e = rp[(size_t)r]; e < rp[(size_t)r + 1]; ++e) ci[(size_t)e] = loc[(size_t)ci[(size_t)e]];   // column -> index in the tile
@@ -407,7 +417,8 @@ int spmm_plan_create(dr_spmm_plan** out, const dr_csr* A, const int32_t* row_ord
     std::vector<int4> desc((size_t)n_tiles);
     std::vector<int32_t> rows_p((size_t)n_tiles * kStRows, -1), start_p((size_t)n_tiles * (kStRows + 1), 0);
     std::vector<int32_t> cols_p((size_t)n_tiles * ccap, 0);
-    std::vector<int2> recs((size_t)E);
+    std::vector<int2> recs;
+    recs.reserve((size_t)E + (size_t)n * (kStUnroll - 1) / 2 + 16);
     int64_t w = 0;
     for (int t = 0; t < n_tiles; ++t) {
         auto b = ord.begin() + tile_row[(size_t)t], e = ord.begin() + tile_row[(size_t)t + 1];
@@ -422,8 +433,11 @@ int spmm_plan_create(dr_spmm_plan** out, const dr_csr* A, const int32_t* row_ord
             for (int q = rp[(size_t)r]; q < rp[(size_t)r + 1]; ++q) {
                 int bits;
                 memcpy(&bits, &av[(size_t)q], 4);
-                recs[(size_t)w++] = make_int2(ci[(size_t)q], bits);
+                recs.push_back(make_int2(ci[(size_t)q], bits));
+                ++w;
             }
+            // zero-valued records up to the next multiple of the inner loop's trip (they read the tile's first gathered row)
+            for (; w % kStUnroll; ++w) recs.push_back(make_int2(0, 0));
         }
         for (int i = nr; i <= kStRows; ++i) start_p[(size_t)t * (kStRows + 1) + i] = (int32_t)(w - e0);
         for (int i = 0; i < ccap; ++i)
