@@ -56,6 +56,30 @@ def build(verbose: bool = True) -> str:
     return LIB
 
 
+def kernel_resources(source: str) -> dict:
+    """{mangled kernel name: {"VGPRs", "ScratchSize", "Occupancy", "LDS Size", ...}} of one translation unit of csrc/, as
+    the compiler reports them (-Rpass-analysis=kernel-resource-usage; device code only, nothing is written).  A kernel
+    whose ScratchSize is not 0 keeps something in scratch memory: every access to it is a vector-memory operation whose
+    wait also waits for the loads in flight."""
+    import re
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "--cuda-device-only",
+           "-Rpass-analysis=kernel-resource-usage", "-c", os.path.join(CSRC, source), "-o", os.devnull]
+    err = subprocess.run(cmd, check=True, capture_output=True, text=True).stderr
+    out, cur = {}, None
+    for line in err.splitlines():
+        m = re.search(r"remark:\s+(Function Name|[A-Za-z ]+(?:\[[^\]]*\])?):\s+(\S+)", line)
+        if not m:
+            continue
+        key, val = m.group(1).strip(), m.group(2)
+        if key == "Function Name":
+            cur = out.setdefault(val, {})
+        elif cur is not None:
+            key = re.sub(r"\s*\[.*\]", "", key)
+            cur[key] = int(val) if val.lstrip("-").isdigit() else val
+    return out
+
+
 if __name__ == "__main__":
     build()
     print(LIB)
