@@ -104,3 +104,45 @@ def test_spmm_bwd_every_element(inputs, whole):
             torch.cuda.synchronize()
             assert np.array_equal(G.cpu().numpy(), got + got), f"G_{name} accumulate"
             say(f"   {got.shape[0]} rows x {K}: worst err / row L1 = {worst:.2e}")
+
+
+@pytest.mark.parametrize("k", (8, 16, 64))
+def test_other_widths_of_the_k_sweep_on_the_cells_and_near(inputs, k):
+    """The other widths bench.py's k sweep times (other kernel instantiations): dr_topk of all cells bit-exact, and
+    every element of dr_spmm_fwd, dr_spmm_bwd and dr_spmm_bwd_planned on the whole `near` relation."""
+    D, T, tr = inputs["D"], inputs["T"], inputs["tr"]
+    rel = inputs["rel"]["near"]
+    say(f"large k={k}: oracle.topk of the cells, oracle.spmm_fwd / spmm_bwd of near")
+    with ThreadPoolExecutor(max_workers=2) as pool:
+        ov, oi = oracle.topk(T.X_cell, k)
+        f_fwd = pool.submit(oracle.spmm_fwd, rel.rowptr, rel.colidx, rel.vals, ov, oi, D, True)
+        f_bwd = pool.submit(oracle.spmm_bwd, *tr["near"], T.dY_cell, oi, True)
+        X = inputs["dT"]["X_cell"]
+        vals = torch.full((X.shape[0], k), float("nan"), dtype=torch.float32, device="cuda")
+        idx = torch.full((X.shape[0], k), -1, dtype=torch.int16, device="cuda")
+        P.dr_topk(X, k, vals, idx)
+        torch.cuda.synchronize()
+        assert np.array_equal(host_idx(idx), oi)
+        assert np.array_equal(vals.cpu().numpy().astype(np.float64), ov)
+        A = inputs["dev_rel"]["near"]
+        H = torch.full((A.n_rows, D), float("nan"), dtype=torch.float32, device="cuda")
+        P.dr_spmm_fwd(A, vals, idx, D, k, H)
+        torch.cuda.synchronize()
+        want, l1row, l1elem = f_fwd.result()
+        worst_f = assert_row_bound(H.cpu().numpy(), want, l1row, f"H_near k={k}")
+        assert_elem_bound(H.cpu().numpy(), want, l1elem, f"H_near k={k}")
+        del want, l1row, l1elem, H
+        At = P.device_transpose(A)
+        want, l1row, l1elem = f_bwd.result()
+        G = torch.full((At.n_rows, k), float("nan"), dtype=torch.float32, device="cuda")
+        P.dr_spmm_bwd(At, inputs["dT"]["dY_cell"], idx, D, k, G)
+        plan = P.SpmmPlan(At, D, dev(inputs["g"].cell_order))
+        Gp = torch.full((At.n_rows, k), float("nan"), dtype=torch.float32, device="cuda")
+        plan.dr_spmm_bwd_planned(inputs["dT"]["dY_cell"], idx, k, Gp)
+        torch.cuda.synchronize()
+        worst_b = assert_row_bound(G.cpu().numpy(), want, l1row, f"G_near k={k}")
+        assert_elem_bound(G.cpu().numpy(), want, l1elem, f"G_near k={k}")
+        worst_p = assert_row_bound(Gp.cpu().numpy(), want, l1row, f"G_near (planned) k={k}")
+        assert_elem_bound(Gp.cpu().numpy(), want, l1elem, f"G_near (planned) k={k}")
+        plan.dr_spmm_plan_destroy()
+    say(f"   worst err / row L1: fwd {worst_f:.2e}, bwd {worst_b:.2e}, bwd planned {worst_p:.2e}")
