@@ -38,6 +38,9 @@ CASES = [
     (129, 60, 5, 32, 32, False),
     (90, 50, 200, 128, 32, True),         # long rows over few neighbours: tiles cut by the edge capacity
     (64, 64, 0, 128, 8, False),           # no edges at all
+    (300, 260, 11, 192, 40, False),       # three column slabs
+    (210, 180, 9, 256, 64, True),         # four column slabs, four outputs per lane
+    (150, 4000, 70, 256, 16, False),      # 256 columns, tiles cut by the gathered-row capacity
 ]
 
 
